@@ -1,0 +1,229 @@
+/*
+ * ssd.h -- C ABI of the MI355X (gfx950) library for the decode-time hot path
+ * of SSD, spatial-semantic head-decoupled KV-cache compression
+ * (arxiv 2510.18716).
+ *
+ * What the library does: batched single-token decode attention over a
+ * per-head heterogeneous compressed KV cache.  Each attention head of each
+ * layer is either a spatial-locality head, which keeps S initial "sink"
+ * tokens and a ring of the W most recent tokens, or a semantic-sink head,
+ * which keeps up to M heavy-hitter tokens chosen by accumulated attention
+ * probability plus a row buffer of up to C recently appended tokens of which
+ * the newest R are never evicted (Sec. 3.3, Algorithm 1; row buffer:
+ * Appendix B, Algorithm 2).
+ *
+ * Conventions that hold for every entry point
+ *   - "dev" pointers are device (HBM) addresses owned by the caller; "host"
+ *     pointers are ordinary host memory.  The library allocates no device
+ *     memory and frees none.  Tensors are dense, row-major, innermost
+ *     dimension last, 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls only enqueue work on it and never wait for the device, with one
+ *     exception: the first launching call on a cache copies a few KB of
+ *     layout tables to the device with a blocking host-to-device copy.
+ *   - Return value: 0 (SSD_OK) or a negative ssd_status.  Argument, range,
+ *     ordering and overflow errors are found from host-side counters before
+ *     anything is enqueued and leave the cache unchanged.  The text of the
+ *     last error of the calling thread is available from ssd_last_error().
+ *   - All sequences of a cache advance together (same prompt length, same
+ *     number of generated tokens; Sec. 3.1: every image has the same N), so
+ *     token counts are kept per layer on the host, not per sequence.
+ *   - Sequences b = 2i and b = 2i+1 are the conditional / unconditional pair
+ *     of prompt i under classifier-free guidance (Sec. 3.1, Eq. 1).  The
+ *     library treats them as independent sequences.
+ *   - Token positions are absolute, 0-based, prompt tokens first and visual
+ *     tokens after them in raster order (Sec. 3.1).
+ *
+ * Call order per generated token and layer:
+ *     ssd_append_token -> ssd_decode_attn -> (ssd_compress_kv when due)
+ * Compressing after every token is Algorithm 1; compressing every 24 tokens
+ * (one grid row) is Algorithm 2.  The row buffer holds C tokens, so at most
+ * C - R tokens can be appended between two compressions.
+ */
+#ifndef SSD_H
+#define SSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ssd_dtype { SSD_F32 = 0, SSD_BF16 = 1 } ssd_dtype;
+
+/* Head types of Eq. (3). */
+typedef enum ssd_head_type { SSD_SPATIAL = 0, SSD_SEMANTIC = 1 } ssd_head_type;
+
+typedef enum ssd_status {
+    SSD_OK = 0,
+    SSD_ERR_INVALID_ARG = -1,    /* null / misaligned pointer, bad config value, bad size       */
+    SSD_ERR_LAYER_RANGE = -2,    /* [layer_begin, layer_end) not inside [0, n_layers)           */
+    SSD_ERR_STAGE_OVERFLOW = -3, /* append with a full row buffer ("Row buffer overflow", Alg. 2) */
+    SSD_ERR_ORDER = -4,          /* attention or export on a layer that holds no token yet      */
+    SSD_ERR_HIP = -5             /* the HIP runtime refused a copy or a launch                  */
+} ssd_status;
+
+/*
+ * Shape and policy parameters (Algorithm 1 "Parameter" line; Sec. 3.3).
+ * One config describes one cache: all layers share W, S, M, R, C.
+ */
+typedef struct ssd_config {
+    int32_t n_layers;      /* L                                                            */
+    int32_t n_seqs;        /* B = 2 x prompts                                              */
+    int32_t n_heads;       /* H, one query row per KV head (plain multi-head attention)     */
+    int32_t head_dim;      /* d: 64 or 128                                                 */
+    int32_t dtype;         /* ssd_dtype of q, k, v, the cache rows and the output          */
+    int32_t window;        /* W >= 1: ring slots of a spatial head, counts the new token   */
+    int32_t n_init_sink;   /* S >= 0: first S positions a spatial head always keeps        */
+    int32_t budget;        /* M >= 1: heavy-hitter slots of a semantic head                */
+    int32_t recent;        /* R >= 0: newest tokens a semantic head never evicts           */
+    int32_t stage_cap;     /* C > R: row-buffer slots of a semantic head; M + C <= 4096    */
+    float   softmax_scale; /* 0 selects 1/sqrt(d)                                          */
+    int32_t reserved[5];   /* must be 0                                                    */
+} ssd_config;
+
+/* Host-side descriptor of a cache: layout, per-layer head lists, token counters. */
+typedef struct ssd_cache ssd_cache;
+
+/*
+ * Bytes of device memory a cache needs for `cfg` and the head-type table
+ * `head_type` (host, [L*H], values of ssd_head_type; the table Algorithm 1
+ * takes as given).  Returns 0 if the config or the table is invalid.
+ */
+size_t ssd_cache_bytes(const ssd_config *cfg, const uint8_t *head_type);
+
+/*
+ * Create the descriptor of a cache that lives in dev_mem[0..bytes).
+ * dev_mem: device, 256-byte aligned, at least ssd_cache_bytes() long, owned
+ * by the caller and must outlive the descriptor; its contents need not be
+ * initialised.  Touches no device memory.  The cache starts empty.
+ */
+int ssd_cache_init(const ssd_config *cfg, const uint8_t *head_type, void *dev_mem,
+                   size_t bytes, ssd_cache **out);
+
+/* Free the descriptor (not dev_mem).  NULL is allowed. */
+void ssd_cache_free(ssd_cache *cache);
+
+/* Forget every token: all host counters back to zero.  Enqueues nothing. */
+int ssd_cache_reset(ssd_cache *cache);
+
+/*
+ * Host counters of one layer: out4 = { n tokens appended, m heavy slots in
+ * use, c row-buffer slots in use, ring index of the oldest row-buffer slot }.
+ */
+int ssd_cache_layer_state(const ssd_cache *cache, int layer, int32_t out4[4]);
+
+/*
+ * Test hook: with enable == 0 every later call on this cache does all of its
+ * checking and counter updates but enqueues nothing (for exercising the host
+ * logic on a machine without a GPU).  Default: enabled.
+ */
+int ssd_cache_set_launch(ssd_cache *cache, int enable);
+
+/*
+ * Head classification by attention sparsity (Sec. 3.3, "Spatial Sparsity
+ * Analysis", and Eq. 3).
+ *   far, tot : dev float [L, P, H, T].  For profiled sequence p and visual
+ *              step t (1-based), with a the attention distribution of that
+ *              step's query over all rows and visual rows indexed
+ *              i = 0..t-1 (i = t-1 is the query's own row):
+ *              tot = sum_{i=0}^{t-1} a(i), far = sum_{i=0}^{t-1-w} a(i).
+ *              ssd_dense_decode_attn produces them.
+ *   s_out    : dev float [L, H]  = mean over (p, t) of far/tot (0 where tot = 0)
+ *   type_out : dev uint8 [L, H]  = SSD_SEMANTIC if s > tau else SSD_SPATIAL
+ */
+int ssd_classify_heads(const float *far, const float *tot, int L, int P, int H, int T,
+                       float tau, float *s_out, uint8_t *type_out, void *stream);
+
+/*
+ * Append one new token to layers [layer_begin, layer_end) (the "Append" of
+ * Algorithm 1, the row-buffer append of Algorithm 2).
+ *   k_new, v_new : dev [layer_end - layer_begin, B, H, d] of the cache dtype.
+ * Spatial head: the row overwrites the oldest ring slot (positions < S go to
+ * the sink slots).  Semantic head: the row enters the row buffer with
+ * accumulated score 0.  Fails with SSD_ERR_STAGE_OVERFLOW, appending to no
+ * layer, if any layer of the range already holds C buffered tokens.
+ */
+int ssd_append_token(ssd_cache *cache, int layer_begin, int layer_end,
+                     const void *k_new, const void *v_new, void *stream);
+
+/*
+ * Single-token attention of every (sequence, head) of the layers over its
+ * retained rows: out = softmax(scale * q K^T) V (Algorithm 1,
+ * "AttentionScores"; the retained rows include the token just appended).
+ *   q   : dev [layer_end - layer_begin, B, H, d], cache dtype
+ *   out : dev, same shape and dtype
+ * accumulate_scores != 0: every semantic head also adds this step's
+ * post-softmax probabilities to the running scores of its retained tokens
+ * (Algorithm 1, "AggregateAttentionScores", fp32).
+ * SSD_ERR_ORDER if a layer of the range holds no token.
+ */
+int ssd_decode_attn(ssd_cache *cache, int layer_begin, int layer_end,
+                    const void *q, void *out, int accumulate_scores, void *stream);
+
+/*
+ * Compression (Algorithm 1 "IndicesOfTopM" + "SelectAndAppend"; Algorithm 2
+ * "Compress ... Reset row buffer").
+ *
+ * In-place mode (K_src == NULL): for every semantic head of the layers,
+ * candidates = heavy tokens + buffered tokens except the R newest; the M
+ * candidates with the highest accumulated score stay (ties: lower position
+ * first; all stay if there are at most M), the rest are dropped with their
+ * scores; the R newest tokens remain in the row buffer.  Spatial heads need
+ * nothing.  A layer with at most R buffered tokens is left as it is.
+ *
+ * Dense-source mode (K_src != NULL): rebuild the layers from a full cache
+ * segment (the prefill branch of Algorithm 2).
+ *   K_src, V_src : dev [layer_end - layer_begin, B, H, n_src, d], cache dtype
+ *   score_src    : dev float [layer_end - layer_begin, B, H, n_src] accumulated
+ *                  scores of those tokens, or NULL for all zero
+ *   n_src        : 1 .. 4096 tokens
+ * Spatial heads take positions {0..S-1} and the last W; semantic heads take
+ * the top-M of positions 0..n_src-R-1 and put the R newest into the row
+ * buffer.  Afterwards the layers hold n_src tokens.
+ */
+int ssd_compress_kv(ssd_cache *cache, int layer_begin, int layer_end,
+                    const void *K_src, const void *V_src, const float *score_src,
+                    int n_src, void *stream);
+
+/*
+ * Test / benchmark export of one layer's index table.
+ *   pos   : dev int32 [B, H, slots]  absolute position held by each slot, -1 if unused
+ *   score : dev float [B, H, slots]  accumulated score of the slot (0 for spatial heads)
+ *   count : dev int32 [B, H]         retained tokens of the head
+ * slots = ssd_cache_export_slots(cache) = max(S + W, M + C).  Any of the three may be NULL.
+ */
+int ssd_cache_export_slots(const ssd_cache *cache);
+int ssd_cache_export(ssd_cache *cache, int layer, int32_t *pos, int32_t *count,
+                     float *score, void *stream);
+
+/*
+ * Full-cache decode attention, the baseline the paper compares against
+ * (Sec. 4.1 "Full Cache"), which also produces the (far, tot) masses that
+ * ssd_classify_heads consumes.
+ *   q, out : dev [B, H, d]
+ *   K, V   : dev [B, H, n_cap, d]; rows 0..n-1 are attended
+ *   far, tot : dev float, element of unit (b, h) at index (b*H + h) * mass_stride;
+ *              both NULL to skip.  Visual rows start at vis_start; w is the
+ *              recency window of the metric (the paper uses 32).
+ *   workspace : dev scratch of at least ssd_dense_workspace_bytes(B, H, d, n) bytes,
+ *               256-byte aligned (partial results of the split over rows)
+ */
+size_t ssd_dense_workspace_bytes(int B, int H, int d, int n);
+int ssd_dense_decode_attn(const void *q, const void *K, const void *V, void *out,
+                          int B, int H, int d, int dtype, int n_cap, int n,
+                          float softmax_scale, float *far, float *tot, int mass_stride,
+                          int vis_start, int w, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
+/* Text of the calling thread's most recent error ("" if none). Never NULL. */
+const char *ssd_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int ssd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSD_H */

@@ -1,0 +1,233 @@
+"""ctypes binding of include/ssd.h.  Same names, same argument order; tensors are passed as
+`data_ptr()` and the stream as the raw hipStream_t of torch's current stream."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+import torch
+
+SSD_F32, SSD_BF16 = 0, 1
+SSD_SPATIAL, SSD_SEMANTIC = 0, 1
+SSD_OK = 0
+SSD_ERR_INVALID_ARG, SSD_ERR_LAYER_RANGE, SSD_ERR_STAGE_OVERFLOW, SSD_ERR_ORDER, SSD_ERR_HIP = -1, -2, -3, -4, -5
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+lib_path = os.path.join(_HERE, "libssd_hip.so")
+
+
+def _load():
+    if not os.path.exists(lib_path):
+        # build only if nothing is built; never fall back to another implementation
+        from . import build as _b
+        _b.build(force=True, verbose=False)
+    return C.CDLL(lib_path)
+
+
+lib = _load()
+
+
+class SsdConfig(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("n_seqs", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("dtype", C.c_int32), ("window", C.c_int32), ("n_init_sink", C.c_int32), ("budget", C.c_int32),
+        ("recent", C.c_int32), ("stage_cap", C.c_int32), ("softmax_scale", C.c_float), ("reserved", C.c_int32 * 5),
+    ]
+
+
+_vp = C.c_void_p
+lib.ssd_cache_bytes.argtypes = [C.POINTER(SsdConfig), _vp]
+lib.ssd_cache_bytes.restype = C.c_size_t
+lib.ssd_cache_init.argtypes = [C.POINTER(SsdConfig), _vp, _vp, C.c_size_t, C.POINTER(_vp)]
+lib.ssd_cache_init.restype = C.c_int
+lib.ssd_cache_free.argtypes = [_vp]
+lib.ssd_cache_free.restype = None
+lib.ssd_cache_reset.argtypes = [_vp]
+lib.ssd_cache_reset.restype = C.c_int
+lib.ssd_cache_layer_state.argtypes = [_vp, C.c_int, C.POINTER(C.c_int32 * 4)]
+lib.ssd_cache_layer_state.restype = C.c_int
+lib.ssd_cache_set_launch.argtypes = [_vp, C.c_int]
+lib.ssd_cache_set_launch.restype = C.c_int
+lib.ssd_classify_heads.argtypes = [_vp, _vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, _vp, _vp, _vp]
+lib.ssd_classify_heads.restype = C.c_int
+lib.ssd_append_token.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp]
+lib.ssd_append_token.restype = C.c_int
+lib.ssd_decode_attn.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, C.c_int, _vp]
+lib.ssd_decode_attn.restype = C.c_int
+lib.ssd_compress_kv.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp, C.c_int, _vp]
+lib.ssd_compress_kv.restype = C.c_int
+lib.ssd_cache_export_slots.argtypes = [_vp]
+lib.ssd_cache_export_slots.restype = C.c_int
+lib.ssd_cache_export.argtypes = [_vp, C.c_int, _vp, _vp, _vp, _vp]
+lib.ssd_cache_export.restype = C.c_int
+lib.ssd_dense_workspace_bytes.argtypes = [C.c_int] * 4
+lib.ssd_dense_workspace_bytes.restype = C.c_size_t
+lib.ssd_dense_decode_attn.argtypes = [_vp, _vp, _vp, _vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                      C.c_float, _vp, _vp, C.c_int, C.c_int, C.c_int, _vp, C.c_size_t, _vp]
+lib.ssd_dense_decode_attn.restype = C.c_int
+lib.ssd_last_error.argtypes = []
+lib.ssd_last_error.restype = C.c_char_p
+lib.ssd_version.argtypes = []
+lib.ssd_version.restype = C.c_int
+lib.ssd_tune_attend.argtypes = [C.c_int] * 3
+lib.ssd_tune_attend.restype = C.c_int
+lib.ssd_tune_dense.argtypes = [C.c_int]
+lib.ssd_tune_dense.restype = C.c_int
+
+
+class SsdError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s failed with %d: %s" % (where, code, ssd_last_error()))
+
+
+def ssd_last_error() -> str:
+    return lib.ssd_last_error().decode()
+
+
+def ssd_version() -> int:
+    return lib.ssd_version()
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != SSD_OK:
+        raise SsdError(rc, where)
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_contiguous(), "tensors handed to the library must be contiguous"
+    return t.data_ptr()
+
+
+def _stream(stream=None) -> Optional[int]:
+    if stream is not None:
+        return stream if isinstance(stream, int) else stream.cuda_stream
+    if torch.cuda.is_available():
+        return torch.cuda.current_stream().cuda_stream
+    return None
+
+
+def _dtype_code(dt) -> int:
+    if isinstance(dt, int):
+        return dt                      # passed through; the library validates it
+    if dt in (torch.bfloat16, "bf16"):
+        return SSD_BF16
+    if dt in (torch.float32, "f32"):
+        return SSD_F32
+    raise ValueError("unsupported dtype %r" % (dt,))
+
+
+def make_config(L, B, H, d, dtype, W, S, M, R, C_, softmax_scale=0.0) -> SsdConfig:
+    cfg = SsdConfig()
+    cfg.n_layers, cfg.n_seqs, cfg.n_heads, cfg.head_dim = L, B, H, d
+    cfg.dtype = _dtype_code(dtype)
+    cfg.window, cfg.n_init_sink, cfg.budget, cfg.recent, cfg.stage_cap = W, S, M, R, C_
+    cfg.softmax_scale = softmax_scale
+    return cfg
+
+
+def ssd_cache_bytes(cfg: SsdConfig, head_type: np.ndarray) -> int:
+    ht = np.ascontiguousarray(head_type, dtype=np.uint8)
+    return lib.ssd_cache_bytes(C.byref(cfg), ht.ctypes.data)
+
+
+class Cache:
+    """Owner of one ssd_cache descriptor and of the torch tensor that backs it in HBM.
+
+    `device=None` creates a descriptor over a fake, never dereferenced address with launches
+    switched off: the host-side logic (validation, counters, error codes) can then be exercised
+    on a machine without a GPU.
+    """
+
+    def __init__(self, cfg: SsdConfig, head_type: np.ndarray, device="cuda"):
+        self.cfg = cfg
+        self.head_type = np.ascontiguousarray(head_type, dtype=np.uint8)
+        nbytes = lib.ssd_cache_bytes(C.byref(cfg), self.head_type.ctypes.data)
+        if nbytes == 0:
+            raise SsdError(SSD_ERR_INVALID_ARG, "ssd_cache_bytes")
+        self.head_type = self.head_type.reshape(cfg.n_layers, cfg.n_heads)
+        self.nbytes = nbytes
+        self._h = _vp()
+        if device is None:
+            self.mem = None
+            base = 1 << 20
+        else:
+            self.mem = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+            base = (self.mem.data_ptr() + 255) // 256 * 256
+        _check(lib.ssd_cache_init(C.byref(cfg), self.head_type.ctypes.data, base, nbytes, C.byref(self._h)), "ssd_cache_init")
+        if device is None:
+            _check(lib.ssd_cache_set_launch(self._h, 0), "ssd_cache_set_launch")
+        self.torch_dtype = torch.bfloat16 if cfg.dtype == SSD_BF16 else torch.float32
+
+    def __del__(self):
+        h = getattr(self, "_h", None)
+        if h is not None and h.value:
+            lib.ssd_cache_free(h)
+            self._h = None
+
+    @property
+    def handle(self):
+        return self._h
+
+    def reset(self):
+        _check(lib.ssd_cache_reset(self._h), "ssd_cache_reset")
+
+    def layer_state(self, layer: int):
+        out = (C.c_int32 * 4)()
+        _check(lib.ssd_cache_layer_state(self._h, layer, C.byref(out)), "ssd_cache_layer_state")
+        return tuple(out)
+
+    @property
+    def export_slots(self) -> int:
+        return lib.ssd_cache_export_slots(self._h)
+
+    def export(self, layer: int, stream=None):
+        """(pos int32 [B,H,slots], count int32 [B,H], score float32 [B,H,slots]) on the cache's device."""
+        B, H, slots = self.cfg.n_seqs, self.cfg.n_heads, self.export_slots
+        dev = self.mem.device
+        pos = torch.empty((B, H, slots), dtype=torch.int32, device=dev)
+        cnt = torch.empty((B, H), dtype=torch.int32, device=dev)
+        sc = torch.empty((B, H, slots), dtype=torch.float32, device=dev)
+        _check(lib.ssd_cache_export(self._h, layer, _ptr(pos), _ptr(cnt), _ptr(sc), _stream(stream)), "ssd_cache_export")
+        return pos, cnt, sc
+
+
+def ssd_append_token(cache: Cache, layer_begin: int, layer_end: int, k_new, v_new, stream=None) -> None:
+    _check(lib.ssd_append_token(cache.handle, layer_begin, layer_end, _ptr(k_new), _ptr(v_new), _stream(stream)),
+           "ssd_append_token")
+
+
+def ssd_decode_attn(cache: Cache, layer_begin: int, layer_end: int, q, out, accumulate_scores: bool = True,
+                    stream=None) -> None:
+    _check(lib.ssd_decode_attn(cache.handle, layer_begin, layer_end, _ptr(q), _ptr(out), int(bool(accumulate_scores)),
+                               _stream(stream)), "ssd_decode_attn")
+
+
+def ssd_compress_kv(cache: Cache, layer_begin: int, layer_end: int, K_src=None, V_src=None, score_src=None,
+                    n_src: int = 0, stream=None) -> None:
+    _check(lib.ssd_compress_kv(cache.handle, layer_begin, layer_end, _ptr(K_src), _ptr(V_src), _ptr(score_src), int(n_src),
+                               _stream(stream)), "ssd_compress_kv")
+
+
+def ssd_classify_heads(far, tot, L: int, P: int, H: int, T: int, tau: float, s_out, type_out, stream=None) -> None:
+    _check(lib.ssd_classify_heads(_ptr(far), _ptr(tot), L, P, H, T, float(tau), _ptr(s_out), _ptr(type_out),
+                                  _stream(stream)), "ssd_classify_heads")
+
+
+def ssd_dense_workspace_bytes(B: int, H: int, d: int, n: int) -> int:
+    return lib.ssd_dense_workspace_bytes(B, H, d, n)
+
+
+def ssd_dense_decode_attn(q, K, V, out, B: int, H: int, d: int, dtype, n_cap: int, n: int, softmax_scale: float = 0.0,
+                          far=None, tot=None, mass_stride: int = 1, vis_start: int = 0, w: int = 32, workspace=None,
+                          stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.ssd_dense_decode_attn(_ptr(q), _ptr(K), _ptr(V), _ptr(out), B, H, d, _dtype_code(dtype), n_cap, n,
+                                     float(softmax_scale), _ptr(far), _ptr(tot), mass_stride, vis_start, w,
+                                     _ptr(workspace), ws_bytes, _stream(stream)), "ssd_dense_decode_attn")

@@ -1,0 +1,313 @@
+// Cache descriptor: config validation, HBM layout, host-side token counters, error text, and the
+// export kernel that copies a layer's index table out for tests.
+//
+// HBM layout of a cache (all regions 256-byte aligned), chosen so that everything one
+// (layer, sequence, head) unit reads in a decode step is one contiguous run:
+//   [ tables : LayerMeta[L], head_info[L*H] ]
+//   per layer l:
+//     spatial units  [B][Hs_l] : K plane (S+W rows) then V plane (S+W rows)
+//     semantic units [B][Hm_l] : K plane (M+C rows) then V plane (M+C rows)
+//     score          [B][Hm_l][M+C] float   running sum of attention probabilities (Algorithm 1)
+//     pos            [B][Hm_l][M+C] int32   absolute token position held by each slot
+// Spatial slots: 0..S-1 hold positions 0..S-1 (the initial sink tokens of Sec. 3.3); slot
+// S + ((p-S) mod W) holds position p >= S, so the ring always contains the W newest tokens.
+// Semantic slots: 0..M-1 heavy hitters (the first m in use); M..M+C-1 the row buffer of
+// Algorithm 2, used as a ring so that the R protected newest tokens never have to move.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <cmath>
+#include <new>
+
+#include "ssd_device.h"
+
+namespace ssd {
+
+static thread_local char g_err[512] = {0};
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(hipError_t e, const char *what) {
+    snprintf(g_err, sizeof(g_err), "%s: %s", what, hipGetErrorString(e));
+    return SSD_ERR_HIP;
+}
+
+void clear_error() { g_err[0] = 0; }
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static int esize_of(int dtype) { return dtype == SSD_F32 ? 4 : dtype == SSD_BF16 ? 2 : 0; }
+
+static int validate(const ssd_config *c, const uint8_t *head_type) {
+    if (!c || !head_type) return fail(SSD_ERR_INVALID_ARG, "config or head_type is NULL");
+    if (c->n_layers < 1 || c->n_layers > 1024) return fail(SSD_ERR_INVALID_ARG, "n_layers=%d outside 1..1024", c->n_layers);
+    if (c->n_seqs < 1 || c->n_seqs > (1 << 20)) return fail(SSD_ERR_INVALID_ARG, "n_seqs=%d outside 1..2^20", c->n_seqs);
+    if (c->n_heads < 1 || c->n_heads > 1024) return fail(SSD_ERR_INVALID_ARG, "n_heads=%d outside 1..1024", c->n_heads);
+    if (c->head_dim != 64 && c->head_dim != 128) return fail(SSD_ERR_INVALID_ARG, "head_dim=%d, supported: 64, 128", c->head_dim);
+    if (esize_of(c->dtype) == 0) return fail(SSD_ERR_INVALID_ARG, "dtype=%d is neither SSD_F32 nor SSD_BF16", c->dtype);
+    if (c->window < 1) return fail(SSD_ERR_INVALID_ARG, "window W=%d must be >= 1", c->window);
+    if (c->n_init_sink < 0) return fail(SSD_ERR_INVALID_ARG, "n_init_sink S=%d must be >= 0", c->n_init_sink);
+    if (c->budget < 1) return fail(SSD_ERR_INVALID_ARG, "budget M=%d must be >= 1", c->budget);
+    if (c->recent < 0) return fail(SSD_ERR_INVALID_ARG, "recent R=%d must be >= 0", c->recent);
+    if (c->stage_cap <= c->recent) return fail(SSD_ERR_INVALID_ARG, "stage_cap C=%d must exceed recent R=%d", c->stage_cap, c->recent);
+    if ((int64_t)c->budget + c->stage_cap > 4096) return fail(SSD_ERR_INVALID_ARG, "M + C = %lld exceeds 4096", (long long)c->budget + c->stage_cap);
+    if ((int64_t)c->n_init_sink + c->window > 65536) return fail(SSD_ERR_INVALID_ARG, "S + W exceeds 65536");
+    if (!(c->softmax_scale >= 0.f) || !std::isfinite(c->softmax_scale)) return fail(SSD_ERR_INVALID_ARG, "softmax_scale must be finite and >= 0");
+    for (int i = 0; i < 5; ++i)
+        if (c->reserved[i] != 0) return fail(SSD_ERR_INVALID_ARG, "reserved[%d] must be 0", i);
+    const size_t n = (size_t)c->n_layers * c->n_heads;
+    for (size_t i = 0; i < n; ++i)
+        if (head_type[i] > 1) return fail(SSD_ERR_INVALID_ARG, "head_type[%zu]=%d is neither SSD_SPATIAL nor SSD_SEMANTIC", i, head_type[i]);
+    return SSD_OK;
+}
+
+// Fills lmeta/hinfo (if non-null) and returns the total byte size.
+static size_t plan_layout(const ssd_config *c, const uint8_t *head_type, std::vector<LayerMeta> *lmeta,
+                          std::vector<uint32_t> *hinfo, size_t *meta_bytes, int *n_sp_total, int *n_se_total) {
+    const int L = c->n_layers, H = c->n_heads;
+    const size_t row = (size_t)c->head_dim * esize_of(c->dtype);
+    const size_t unit_sp = 2 * (size_t)(c->n_init_sink + c->window) * row;
+    const size_t unit_se = 2 * (size_t)(c->budget + c->stage_cap) * row;
+    const size_t slots = (size_t)c->budget + c->stage_cap;
+    size_t off = align_up(sizeof(LayerMeta) * (size_t)L, 256);
+    off = align_up(off + sizeof(uint32_t) * (size_t)L * H, 256);
+    if (meta_bytes) *meta_bytes = off;
+    if (lmeta) lmeta->resize(L);
+    if (hinfo) hinfo->resize((size_t)L * H);
+    int sp_tot = 0, se_tot = 0;
+    for (int l = 0; l < L; ++l) {
+        int n_sp = 0, n_se = 0;
+        for (int h = 0; h < H; ++h) {
+            const bool sem = head_type[(size_t)l * H + h] == SSD_SEMANTIC;
+            const uint32_t local = sem ? n_se++ : n_sp++;
+            if (hinfo) (*hinfo)[(size_t)l * H + h] = local | (sem ? HEAD_SEM_BIT : 0u);
+        }
+        LayerMeta m;
+        m.n_sp = n_sp;
+        m.n_se = n_se;
+        m.off_sp = off;
+        off = align_up(off + (size_t)c->n_seqs * n_sp * unit_sp, 256);
+        m.off_se = off;
+        off = align_up(off + (size_t)c->n_seqs * n_se * unit_se, 256);
+        m.off_score = off;
+        off = align_up(off + (size_t)c->n_seqs * n_se * slots * sizeof(float), 256);
+        m.off_pos = off;
+        off = align_up(off + (size_t)c->n_seqs * n_se * slots * sizeof(int32_t), 256);
+        if (lmeta) (*lmeta)[l] = m;
+        sp_tot += n_sp;
+        se_tot += n_se;
+    }
+    if (n_sp_total) *n_sp_total = sp_tot;
+    if (n_se_total) *n_se_total = se_tot;
+    return off;
+}
+
+int check_layers(const ssd_cache *c, int lb, int le) {
+    if (!c) return fail(SSD_ERR_INVALID_ARG, "cache is NULL");
+    if (lb < 0 || le > c->cfg.n_layers || lb >= le)
+        return fail(SSD_ERR_LAYER_RANGE, "layer range [%d, %d) is not inside [0, %d)", lb, le, c->cfg.n_layers);
+    return SSD_OK;
+}
+
+int ensure_meta(ssd_cache *c, hipStream_t s) {
+    if (c->meta_uploaded) return SSD_OK;
+    // Blocking copies from pageable memory: the host buffers may be reused as soon as they return.
+    // Ordered before any later kernel on `s` because they complete before this function returns.
+    (void)s;
+    hipError_t e = hipMemcpy(c->dev, c->lmeta.data(), sizeof(LayerMeta) * c->lmeta.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return hip_fail(e, "upload of the layer table");
+    const size_t hoff = align_up(sizeof(LayerMeta) * c->lmeta.size(), 256);
+    e = hipMemcpy(c->dev + hoff, c->hinfo.data(), sizeof(uint32_t) * c->hinfo.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return hip_fail(e, "upload of the head table");
+    c->meta_uploaded = true;
+    return SSD_OK;
+}
+
+Geom make_geom(const ssd_cache *c) {
+    Geom g;
+    g.base = c->dev;
+    g.lmeta = reinterpret_cast<const LayerMeta *>(c->dev);
+    g.hinfo = reinterpret_cast<const uint32_t *>(c->dev + align_up(sizeof(LayerMeta) * c->lmeta.size(), 256));
+    g.B = c->cfg.n_seqs;
+    g.H = c->cfg.n_heads;
+    g.S = c->cfg.n_init_sink;
+    g.W = c->cfg.window;
+    g.M = c->cfg.budget;
+    g.C = c->cfg.stage_cap;
+    g.row_bytes = c->cfg.head_dim * c->esize;
+    g.unit_sp_bytes = 2u * (uint32_t)(g.S + g.W) * (uint32_t)g.row_bytes;
+    g.unit_se_bytes = 2u * (uint32_t)(g.M + g.C) * (uint32_t)g.row_bytes;
+    return g;
+}
+
+Segs spatial_segs(const ssd_cache *c, const LayerState &st) {
+    // the ring fills front to back, so the valid slots are always a prefix
+    Segs s = {{0, 0, 0}, {0, 0, 0}, 0};
+    const int cap = c->cfg.n_init_sink + c->cfg.window;
+    s.len[0] = st.n < cap ? st.n : cap;
+    s.total = s.len[0];
+    return s;
+}
+
+Segs semantic_segs(const ssd_cache *c, const LayerState &st) {
+    Segs s = {{0, 0, 0}, {0, 0, 0}, 0};
+    const int M = c->cfg.budget, C = c->cfg.stage_cap;
+    s.start[0] = 0;
+    s.len[0] = st.m;
+    const int first = st.base + st.c <= C ? st.c : C - st.base;   // run up to the end of the ring
+    s.start[1] = M + st.base;
+    s.len[1] = first;
+    s.start[2] = M;
+    s.len[2] = st.c - first;                                      // wrapped part
+    s.total = s.len[0] + s.len[1] + s.len[2];
+    return s;
+}
+
+int same_state_run(const ssd_cache *c, int lb, int le) {
+    int l = lb + 1;
+    while (l < le && c->st[l] == c->st[lb]) ++l;
+    return l;
+}
+
+// ---- export ---------------------------------------------------------------
+
+__global__ void export_kernel(Geom g, int layer, LayerState st, Segs se, int slots, int32_t *pos_out,
+                              int32_t *count_out, float *score_out) {
+    const int unit = blockIdx.x;   // b*H + h
+    const int b = unit / g.H, h = unit % g.H;
+    const UnitRef u = unit_ref(g, layer, b, h);
+    const size_t o = (size_t)unit * (size_t)slots;
+    int count;
+    if (u.sem) {
+        count = se.total;
+        for (int s = threadIdx.x; s < slots; s += blockDim.x) {
+            bool valid = false;
+            for (int k = 0; k < 3; ++k) valid = valid || (s >= se.start[k] && s < se.start[k] + se.len[k]);
+            if (pos_out) pos_out[o + s] = valid ? u.pos[s] : -1;
+            if (score_out) score_out[o + s] = valid ? u.score[s] : 0.f;
+        }
+    } else {
+        const int cap = g.S + g.W;
+        count = st.n < cap ? st.n : cap;
+        for (int s = threadIdx.x; s < slots; s += blockDim.x) {
+            int p = -1;
+            if (s < g.S) {
+                p = s < st.n ? s : -1;
+            } else if (s < cap && st.n > g.S) {
+                // newest position whose ring slot is s
+                const int j = s - g.S;
+                const int last = st.n - 1;
+                const int kl = (last - g.S) % g.W;
+                const int cand = last - ((kl - j + g.W) % g.W);
+                p = cand >= g.S ? cand : -1;
+            }
+            if (pos_out) pos_out[o + s] = p;
+            if (score_out) score_out[o + s] = 0.f;
+        }
+    }
+    if (count_out && threadIdx.x == 0) count_out[unit] = count;
+}
+
+}  // namespace ssd
+
+using namespace ssd;
+
+extern "C" {
+
+size_t ssd_cache_bytes(const ssd_config *cfg, const uint8_t *head_type) {
+    clear_error();
+    if (validate(cfg, head_type) != SSD_OK) return 0;
+    return plan_layout(cfg, head_type, nullptr, nullptr, nullptr, nullptr, nullptr);
+}
+
+int ssd_cache_init(const ssd_config *cfg, const uint8_t *head_type, void *dev_mem, size_t bytes, ssd_cache **out) {
+    clear_error();
+    if (!out) return fail(SSD_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    int rc = validate(cfg, head_type);
+    if (rc != SSD_OK) return rc;
+    if (!dev_mem) return fail(SSD_ERR_INVALID_ARG, "dev_mem is NULL");
+    if (!aligned(dev_mem, 256)) return fail(SSD_ERR_INVALID_ARG, "dev_mem is not 256-byte aligned");
+    ssd_cache *c = new (std::nothrow) ssd_cache();
+    if (!c) return fail(SSD_ERR_INVALID_ARG, "out of host memory");
+    c->cfg = *cfg;
+    c->esize = esize_of(cfg->dtype);
+    c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+    c->head_type.assign(head_type, head_type + (size_t)cfg->n_layers * cfg->n_heads);
+    const size_t need = plan_layout(cfg, head_type, &c->lmeta, &c->hinfo, &c->meta_bytes, &c->n_sp_total, &c->n_se_total);
+    if (bytes < need) {
+        delete c;
+        return fail(SSD_ERR_INVALID_ARG, "dev_mem holds %zu bytes, the cache needs %zu", bytes, need);
+    }
+    c->dev = static_cast<char *>(dev_mem);
+    c->bytes = bytes;
+    c->meta_uploaded = false;
+    c->launch_enabled = true;
+    c->st.assign(cfg->n_layers, LayerState{0, 0, 0, 0});
+    *out = c;
+    return SSD_OK;
+}
+
+void ssd_cache_free(ssd_cache *cache) { delete cache; }
+
+int ssd_cache_reset(ssd_cache *cache) {
+    clear_error();
+    if (!cache) return fail(SSD_ERR_INVALID_ARG, "cache is NULL");
+    cache->st.assign(cache->cfg.n_layers, LayerState{0, 0, 0, 0});
+    return SSD_OK;
+}
+
+int ssd_cache_layer_state(const ssd_cache *cache, int layer, int32_t out4[4]) {
+    clear_error();
+    int rc = check_layers(cache, layer, layer + 1);
+    if (rc != SSD_OK) return rc;
+    if (!out4) return fail(SSD_ERR_INVALID_ARG, "out4 is NULL");
+    const LayerState &s = cache->st[layer];
+    out4[0] = s.n; out4[1] = s.m; out4[2] = s.c; out4[3] = s.base;
+    return SSD_OK;
+}
+
+int ssd_cache_set_launch(ssd_cache *cache, int enable) {
+    clear_error();
+    if (!cache) return fail(SSD_ERR_INVALID_ARG, "cache is NULL");
+    cache->launch_enabled = enable != 0;
+    return SSD_OK;
+}
+
+int ssd_cache_export_slots(const ssd_cache *cache) {
+    if (!cache) return 0;
+    const int a = cache->cfg.n_init_sink + cache->cfg.window, b = cache->cfg.budget + cache->cfg.stage_cap;
+    return a > b ? a : b;
+}
+
+int ssd_cache_export(ssd_cache *cache, int layer, int32_t *pos, int32_t *count, float *score, void *stream) {
+    clear_error();
+    int rc = check_layers(cache, layer, layer + 1);
+    if (rc != SSD_OK) return rc;
+    if (!aligned(pos, 4) || !aligned(count, 4) || !aligned(score, 4)) return fail(SSD_ERR_INVALID_ARG, "misaligned output");
+    if (!cache->launch_enabled) return SSD_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rc = ensure_meta(cache, s);
+    if (rc != SSD_OK) return rc;
+    const LayerState st = cache->st[layer];
+    const Segs se = semantic_segs(cache, st);
+    const int units = cache->cfg.n_seqs * cache->cfg.n_heads;
+    hipLaunchKernelGGL(export_kernel, dim3(units), dim3(64), 0, s, make_geom(cache), layer, st, se,
+                       ssd_cache_export_slots(cache), pos, count, score);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "export launch");
+    return SSD_OK;
+}
+
+const char *ssd_last_error(void) { return g_err; }
+
+int ssd_version(void) { return 100; }
+
+}  // extern "C"

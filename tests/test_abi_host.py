@@ -1,0 +1,192 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares, and its
+host-side logic (validation, counters, ordering and overflow errors) behaves as the header says.
+No kernel is launched here: caches are created over a fake address with launches switched off."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2510_18716_amd as ssd
+from paper_2510_18716_amd.binding import make_config
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 1 << 24          # a 16-byte aligned non-null "device pointer" that is never dereferenced
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "ssd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(ssd_[a-z_0-9]+)\s*\(", text)))
+    assert {"ssd_classify_heads", "ssd_compress_kv", "ssd_decode_attn", "ssd_append_token"} <= set(names)
+    for n in names:
+        assert hasattr(ssd.lib, n), n
+    assert ssd.ssd_version() >= 100
+    assert ssd.ssd_last_error() == "" or isinstance(ssd.ssd_last_error(), str)
+
+
+def _ht(L, H, frac=0.5):
+    m = np.ones((L, H), np.uint8)
+    m[:, : int(H * frac)] = 0
+    return m
+
+
+def test_cache_bytes_matches_layout_formula():
+    L, B, H, d, W, S, M, R, C_ = 3, 4, 8, 128, 64, 1, 64, 1, 2
+    cfg = make_config(L, B, H, d, "bf16", W, S, M, R, C_)
+    ht = _ht(L, H)
+    row = d * 2
+    per_layer = B * 4 * 2 * (S + W) * row + B * 4 * 2 * (M + C_) * row + 2 * B * 4 * (M + C_) * 4
+    got = ssd.ssd_cache_bytes(cfg, ht)
+    assert per_layer * L <= got <= per_layer * L + 4096 + 4 * 256 * L
+    # fp32 rows are twice as long
+    cfg32 = make_config(L, B, H, d, "f32", W, S, M, R, C_)
+    assert ssd.ssd_cache_bytes(cfg32, ht) > 1.9 * per_layer * L
+
+
+@pytest.mark.parametrize("field,value", [
+    ("n_layers", 0), ("n_seqs", 0), ("n_heads", 0), ("head_dim", 96), ("dtype", 7), ("window", 0),
+    ("n_init_sink", -1), ("budget", 0), ("recent", -1), ("stage_cap", 1), ("softmax_scale", -1.0),
+    ("softmax_scale", float("nan")), ("budget", 4096),
+])
+def test_bad_config_is_refused(field, value):
+    cfg = make_config(2, 2, 4, 64, "f32", 8, 1, 8, 1, 2)
+    setattr(cfg, field, value)
+    assert ssd.ssd_cache_bytes(cfg, _ht(2, 4)) == 0
+    assert ssd.ssd_last_error() != ""
+    with pytest.raises(ssd.SsdError):
+        ssd.Cache(cfg, _ht(max(cfg.n_layers, 1), max(cfg.n_heads, 1)), device=None)
+
+
+def test_bad_head_type_and_reserved_fields():
+    cfg = make_config(1, 2, 4, 64, "f32", 8, 1, 8, 1, 2)
+    bad = np.array([[0, 1, 2, 0]], np.uint8)
+    assert ssd.ssd_cache_bytes(cfg, bad) == 0
+    cfg.reserved[2] = 5
+    assert ssd.ssd_cache_bytes(cfg, _ht(1, 4)) == 0
+
+
+def test_init_checks_pointer_and_size():
+    import ctypes as C
+    cfg = make_config(1, 2, 4, 64, "f32", 8, 1, 8, 1, 2)
+    ht = _ht(1, 4)
+    need = ssd.ssd_cache_bytes(cfg, ht)
+    h = C.c_void_p()
+    assert ssd.lib.ssd_cache_init(C.byref(cfg), ht.ctypes.data, None, need, C.byref(h)) == ssd.SSD_ERR_INVALID_ARG
+    assert ssd.lib.ssd_cache_init(C.byref(cfg), ht.ctypes.data, FAKE + 16, need, C.byref(h)) == ssd.SSD_ERR_INVALID_ARG
+    assert "256" in ssd.ssd_last_error()
+    assert ssd.lib.ssd_cache_init(C.byref(cfg), ht.ctypes.data, FAKE, need - 1, C.byref(h)) == ssd.SSD_ERR_INVALID_ARG
+    assert ssd.lib.ssd_cache_init(C.byref(cfg), ht.ctypes.data, FAKE, need, C.byref(h)) == ssd.SSD_OK
+    ssd.lib.ssd_cache_free(h)
+    ssd.lib.ssd_cache_free(None)
+
+
+def test_layer_range_order_and_pointer_errors():
+    cfg = make_config(3, 2, 4, 64, "f32", 8, 1, 8, 1, 3)
+    c = ssd.Cache(cfg, _ht(3, 4), device=None)
+    for lb, le in [(-1, 1), (0, 4), (2, 2), (2, 1)]:
+        with pytest.raises(ssd.SsdError) as e:
+            ssd.ssd_append_token(c, lb, le, FAKE, FAKE)
+        assert e.value.code == ssd.SSD_ERR_LAYER_RANGE
+    with pytest.raises(ssd.SsdError) as e:
+        ssd.ssd_decode_attn(c, 0, 3, FAKE, FAKE)
+    assert e.value.code == ssd.SSD_ERR_ORDER                      # nothing appended yet
+    ssd.ssd_append_token(c, 0, 2, FAKE, FAKE)
+    ssd.ssd_decode_attn(c, 0, 2, FAKE, FAKE)
+    with pytest.raises(ssd.SsdError) as e:
+        ssd.ssd_decode_attn(c, 0, 3, FAKE, FAKE)                  # layer 2 is still empty
+    assert e.value.code == ssd.SSD_ERR_ORDER
+    for args in [(None, FAKE), (FAKE, None), (FAKE + 4, FAKE)]:
+        with pytest.raises(ssd.SsdError) as e:
+            ssd.ssd_append_token(c, 0, 1, *args)
+        assert e.value.code == ssd.SSD_ERR_INVALID_ARG
+    assert c.layer_state(0)[0] == 1                               # failed calls changed nothing
+    with pytest.raises(ssd.SsdError) as e:
+        ssd.ssd_compress_kv(c, 0, 1, FAKE, None, None, 4)
+    assert e.value.code == ssd.SSD_ERR_INVALID_ARG
+    with pytest.raises(ssd.SsdError):
+        ssd.ssd_compress_kv(c, 0, 1, FAKE, FAKE, None, 0)
+    with pytest.raises(ssd.SsdError):
+        ssd.ssd_compress_kv(c, 0, 1, FAKE, FAKE, None, 4097)
+
+
+def test_row_buffer_overflow_refuses_the_whole_call():
+    cfg = make_config(2, 2, 4, 64, "f32", 8, 1, 8, 1, 3)
+    c = ssd.Cache(cfg, _ht(2, 4), device=None)
+    ssd.ssd_append_token(c, 0, 1, FAKE, FAKE)                     # layer 0 one token ahead
+    for _ in range(2):
+        ssd.ssd_append_token(c, 0, 2, FAKE, FAKE)
+    assert c.layer_state(0)[:3] == (3, 0, 3) and c.layer_state(1)[:3] == (2, 0, 2)
+    with pytest.raises(ssd.SsdError) as e:
+        ssd.ssd_append_token(c, 0, 2, FAKE, FAKE)
+    assert e.value.code == ssd.SSD_ERR_STAGE_OVERFLOW and "overflow" in ssd.ssd_last_error()
+    assert c.layer_state(1)[:3] == (2, 0, 2)                      # layer 1 was not touched either
+    ssd.ssd_compress_kv(c, 0, 2)
+    assert c.layer_state(0) == (3, 2, 1, 2) and c.layer_state(1) == (2, 1, 1, 1)
+    ssd.ssd_append_token(c, 0, 2, FAKE, FAKE)
+    c.reset()
+    assert c.layer_state(0) == (0, 0, 0, 0)
+
+
+def test_all_spatial_layer_has_no_row_buffer():
+    cfg = make_config(1, 2, 4, 64, "f32", 8, 1, 8, 1, 2)
+    c = ssd.Cache(cfg, np.zeros((1, 4), np.uint8), device=None)
+    for _ in range(50):
+        ssd.ssd_append_token(c, 0, 1, FAKE, FAKE)
+    assert c.layer_state(0) == (50, 0, 0, 0)
+    ssd.ssd_compress_kv(c, 0, 1)
+    assert c.layer_state(0) == (50, 0, 0, 0)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_host_counters_follow_the_oracle_policy(seed):
+    r = np.random.default_rng(seed)
+    M, R = int(r.integers(1, 9)), int(r.integers(0, 4))
+    C_ = R + int(r.integers(1, 7))
+    cfg = make_config(1, 2, 2, 64, "f32", 4, 1, M, R, C_)
+    c = ssd.Cache(cfg, np.array([[0, 1]], np.uint8), device=None)
+    u = oracle.Unit(True, 4, 1, M, R, C_)
+    for step in range(60):
+        rc = u.append()
+        if rc != 0:
+            with pytest.raises(ssd.SsdError) as e:
+                ssd.ssd_append_token(c, 0, 1, FAKE, FAKE)
+            assert e.value.code == ssd.SSD_ERR_STAGE_OVERFLOW
+            u.compress(); ssd.ssd_compress_kv(c, 0, 1)
+            assert u.append() == 0
+        ssd.ssd_append_token(c, 0, 1, FAKE, FAKE)
+        if r.random() < 0.4:
+            u.compress(); ssd.ssd_compress_kv(c, 0, 1)
+        hp, _, sp, _ = u.state()
+        n, m, cc, base = c.layer_state(0)
+        assert (n, m, cc) == (u.n, len(hp), len(sp))
+        assert 0 <= base < C_
+    # dense-source mode sets the counters as one compression of n_src tokens would
+    for n_src in (1, R, R + 1, M + R, M + R + 5):
+        if n_src < 1:
+            continue
+        ssd.ssd_compress_kv(c, 0, 1, FAKE, FAKE, None, n_src)
+        v = oracle.Unit(True, 4, 1, M, R, C_)
+        v.load_dense(n_src)
+        hp, _, sp, _ = v.state()
+        assert c.layer_state(0) == (n_src, len(hp), len(sp), 0)
+
+
+def test_dense_and_classify_argument_checks():
+    lib = ssd.lib
+    ok = dict(B=2, H=2, d=64, dtype=0, n_cap=8, n=8)
+    def dense(**kw):
+        a = dict(ok); a.update(kw)
+        return lib.ssd_dense_decode_attn(kw.get("q", FAKE), FAKE, FAKE, FAKE, a["B"], a["H"], a["d"], a["dtype"], a["n_cap"],
+                                         a["n"], 0.0, kw.get("far"), kw.get("tot"), 1, 0, 32, None, 0, None)
+    assert dense(q=None) == ssd.SSD_ERR_INVALID_ARG
+    assert dense(d=80) == ssd.SSD_ERR_INVALID_ARG
+    assert dense(n=9) == ssd.SSD_ERR_INVALID_ARG
+    assert dense(n=0) == ssd.SSD_ERR_INVALID_ARG
+    assert dense(dtype=3) == ssd.SSD_ERR_INVALID_ARG
+    assert dense(far=FAKE) == ssd.SSD_ERR_INVALID_ARG              # far without tot
+    assert ssd.ssd_dense_workspace_bytes(2, 2, 64, 100) >= 2 * 2 * 68 * 4
+    assert lib.ssd_classify_heads(None, FAKE, 1, 1, 1, 1, 0.5, FAKE, FAKE, None) == ssd.SSD_ERR_INVALID_ARG
+    assert lib.ssd_classify_heads(FAKE, FAKE, 1, 0, 1, 1, 0.5, FAKE, FAKE, None) == ssd.SSD_ERR_INVALID_ARG
+    assert lib.ssd_classify_heads(FAKE, FAKE, 1, 1, 1, 1, 0.5, None, None, None) == ssd.SSD_ERR_INVALID_ARG

@@ -1,0 +1,161 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Small shapes compare every unit at every step; the Janus-Pro-shaped configurations run at full size in
+the benchmark's launch configuration and compare sampled units.  Index sets are compared exactly,
+outputs within the stated tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_18716_amd as ssd
+import workload
+from harness import (GAP_MARGIN, check_outputs, check_selection_on_own_scores, compare_unit_sets, gpu_decode,
+                     make_cache, oracle_unit, sample_units, say)
+
+pytestmark = pytest.mark.gpu
+
+
+def _to_cuda(data):
+    return {k: v.cuda() for k, v in data.items()}
+
+
+def _full_compare(wl, ht=None, lpc=None, k_units=10 ** 9, export_every=1, seed=0, device_gen=False):
+    ht = workload.head_map(wl) if ht is None else ht
+    schedule = workload.compress_schedule(wl)
+    say("case", wl.name, wl.dtype, "L%d B%d H%d d%d n0=%d N=%d W%d S%d M%d R%d C%d cadence%d lpc=%s" % (
+        wl.L, wl.B, wl.H, wl.d, wl.n0, wl.N, wl.W, wl.S, wl.M, wl.R, wl.C, wl.cadence, lpc))
+    if device_gen:
+        dev_data = workload.generate(wl, device="cuda", head_type=ht)
+    else:
+        data = workload.generate(wl, head_type=ht)
+        dev_data = _to_cuda(data)
+    units = sample_units(wl, ht, k_units, seed)
+    if export_every == 1:
+        steps = list(range(wl.n_total))
+    else:
+        comp = [p for p in range(wl.n_total) if schedule[p]]
+        steps = sorted(set(range(0, wl.n_total, export_every)) | {wl.n_total - 1} | set(comp[:: max(1, len(comp) // 8)]))
+    outs, exports, cache = gpu_decode(wl, dev_data, ht, schedule, units, layers_per_call=lpc, export_steps=steps)
+    say("  gpu decode done: %d units, %d exported steps" % (len(units), len(exports)))
+    # sampled units back on the host: the oracle sees the very same bits
+    layers = sorted(set(l for (l, _, _) in units))
+    near_ties, worst, t3 = 0, 0.0, 0
+    final_pos, final_score = exports[wl.n_total - 1]["post"]
+    for ui, unit in enumerate(units):
+        l, b, h = unit
+        host = {x: dev_data[x][:, l:l + 1, b:b + 1, h:h + 1].cpu() for x in "qkv"}
+        o_ref, hl, gl, u = oracle_unit(wl, host, ht[l:l + 1, h:h + 1], schedule, (0, 0, 0))
+        li = layers.index(l)
+        diverged = compare_unit_sets(wl, ht, unit, li, exports, hl, gl, schedule)
+        t3 += check_selection_on_own_scores(wl, ht, unit, li, exports)
+        upto = wl.n_total if diverged is None else diverged + 1
+        worst = max(worst, check_outputs(outs[:upto, ui], o_ref[:upto], wl.dtype, "unit %s" % (unit,)))
+        if diverged is not None:
+            near_ties += 1
+            continue
+        if ht[l, h] == workload.SEMANTIC:
+            hp, hs, sp, ss = u.state()
+            ref = dict(zip(hp.tolist() + sp.tolist(), hs.tolist() + ss.tolist()))
+            got = {int(p): float(s) for p, s in zip(final_pos[li, b, h], final_score[li, b, h]) if p >= 0}
+            assert sorted(got) == sorted(ref)
+            for p in ref:
+                assert abs(got[p] - ref[p]) <= 1e-4 * max(1.0, abs(ref[p])), ("score", unit, p, got[p], ref[p])
+    say("  max abs output error %.3e, near-tie units %d of %d, own-score selections checked %d" % (
+        worst, near_ties, len(units), t3))
+    assert near_ties <= max(1, len(units) // 10)
+    return cache
+
+
+# ------------------------------------------------------------------ tiny, every unit, every step ----
+
+@pytest.mark.parametrize("S,cadence", [(1, 1), (0, 1), (1, 8)])
+def test_config1_every_unit_every_step(S, cadence):
+    wl = workload.config(1).replace(S=S, cadence=cadence, C=1 + cadence)
+    _full_compare(wl)
+
+
+def test_config1_plain_gaussian_inputs():
+    # no planted structure: every retained row carries weight, so a wrong row shows in the output
+    wl = workload.config(1).replace(plain=True, name="cfg1-plain")
+    _full_compare(wl)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128), ("f32", 64)])
+def test_small_shapes_all_dtypes(dtype, d):
+    wl = workload.Workload("small-%s-%d" % (dtype, d), L=3, prompts=2, H=6, d=d, dtype=dtype, n0=9, grid_h=7,
+                           grid_w=9, W=13, M=10, S=2, R=2, C=7, cadence=5, spatial_frac=0.5, seed=77,
+                           plain=True)
+    _full_compare(wl)
+    _full_compare(wl.replace(name=wl.name + "-perlayer"), lpc=1)
+
+
+def test_ragged_sizes_and_long_row_buffer():
+    # row counts that are not multiples of the rows-per-load (4) or the chunk (16); a row buffer that wraps
+    wl = workload.Workload("ragged", L=2, prompts=1, H=5, d=128, dtype="bf16", n0=3, grid_h=9, grid_w=11, W=67,
+                           M=33, S=3, R=5, C=41, cadence=36, spatial_frac=0.4, seed=5, plain=True)
+    _full_compare(wl)
+
+
+def test_all_spatial_and_all_semantic_head_maps():
+    # the two special cases the paper compares against: window + sink tokens only, heavy hitters only
+    wl = workload.Workload("all-spatial", L=2, prompts=1, H=4, d=64, dtype="bf16", n0=4, grid_h=6, grid_w=6, W=8,
+                           M=6, S=1, R=1, C=2, cadence=1, seed=9, plain=True)
+    _full_compare(wl, ht=np.zeros((2, 4), np.uint8))
+    _full_compare(wl.replace(name="all-semantic"), ht=np.ones((2, 4), np.uint8))
+    mixed = np.array([[0, 0, 0, 0], [1, 1, 1, 1]], np.uint8)      # head lists that differ per layer
+    _full_compare(wl.replace(name="layerwise-types"), ht=mixed)
+
+
+def test_degenerate_parameters():
+    base = dict(L=1, prompts=1, H=4, d=64, dtype="f32", n0=2, grid_h=5, grid_w=5, seed=3, plain=True)
+    _full_compare(workload.Workload("W1-M1", W=1, M=1, S=0, R=1, C=2, cadence=1, **base))
+    _full_compare(workload.Workload("R0", W=2, M=3, S=1, R=0, C=1, cadence=1, **base))
+    _full_compare(workload.Workload("S-exceeds-n0", W=4, M=4, S=6, R=3, C=4, cadence=1, **base))
+
+
+def test_unbounded_window_and_budget_equal_dense_kernel():
+    wl = workload.Workload("unbounded", L=1, prompts=1, H=4, d=128, dtype="bf16", n0=5, grid_h=6, grid_w=7, W=64,
+                           M=64, S=0, R=1, C=2, cadence=1, seed=11, plain=True)
+    ht = workload.head_map(wl)
+    data = _to_cuda(workload.generate(wl, head_type=ht))
+    units = sample_units(wl, ht, 10 ** 9)
+    outs, _, _ = gpu_decode(wl, data, ht, workload.compress_schedule(wl), units, export_steps=[wl.n_total - 1])
+    K = workload.dense_layout(data["k"])[0]
+    V = workload.dense_layout(data["v"])[0]
+    out = torch.empty((wl.B, wl.H, wl.d), dtype=torch.bfloat16, device="cuda")
+    for p in range(wl.n_total):
+        ssd.ssd_dense_decode_attn(data["q"][p, 0], K, V, out, wl.B, wl.H, wl.d, "bf16", wl.n_total, p + 1)
+        dense = out.float().cpu().numpy().reshape(-1, wl.d)
+        # both kernels round to bf16 at the end: allow one bf16 ulp of the value
+        np.testing.assert_allclose(outs[p], dense, atol=4e-3, rtol=8e-3)
+
+
+# ------------------------------------------------------------------ paper-shaped, full size ----------
+
+def test_config2_full_size_sampled_units():
+    wl = workload.config(2)
+    _full_compare(wl, k_units=48, export_every=64, device_gen=True)
+
+
+def test_config2_per_layer_launches():
+    wl = workload.config(2).replace(name="cfg2-perlayer", L=4)
+    _full_compare(wl, lpc=1, k_units=24, export_every=96, device_gen=True)
+
+
+def test_config4_high_resolution_row_buffer():
+    wl = workload.config(4)
+    _full_compare(wl, k_units=32, export_every=256, device_gen=True)
+
+
+def test_determinism_same_inputs_same_bits():
+    wl = workload.config(2).replace(name="cfg2-determinism", L=2, prompts=4, grid_h=6)
+    ht = workload.head_map(wl)
+    data = workload.generate(wl, device="cuda", head_type=ht)
+    units = sample_units(wl, ht, 10 ** 9)
+    sched = workload.compress_schedule(wl)
+    a, ea, _ = gpu_decode(wl, data, ht, sched, units, export_steps=[wl.n_total - 1])
+    b, eb, _ = gpu_decode(wl, data, ht, sched, units, export_steps=[wl.n_total - 1])
+    np.testing.assert_array_equal(a, b)
+    for k in (0, 1):
+        np.testing.assert_array_equal(ea[wl.n_total - 1]["post"][k], eb[wl.n_total - 1]["post"][k])

@@ -1,0 +1,273 @@
+#!/usr/bin/env python3
+"""Benchmark of the SSD compressed decode-attention path on one MI355X.
+
+A "step" is one generated visual token for the whole batch: for every layer, ssd_append_token ->
+ssd_decode_attn (with score accumulation) -> ssd_compress_kv, on synthetic Janus-Pro-shaped inputs that are
+already resident in HBM.  The cache is first filled by decoding the prompt and the earlier part of the image
+(untimed), so the timed steps run at the end of the raster decode with every window and budget full.
+
+Prints ONE JSON line: visual tokens/s (prompts x steps / wall time), the roofline figures of the dominant
+kernel (the attention kernel; algorithmic bytes / mean launch duration from HIP events on the launch
+stream), the same steps through the dense full-cache kernel, and the CPU oracle timed on a sample of units.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM traffic of one attention launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; scaled by the
+# same counters on a copy of known size), keyed by (workload, layers per call).  See profiles/.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes_attend(wl, ht, layers, state):
+    """Bytes one ssd_decode_attn launch over `layers` must move: K and V rows of every retained token, q in,
+    output out, and the score read-modify-write of semantic heads."""
+    n, m, c = state
+    row = wl.d * (2 if wl.dtype == "bf16" else 4)
+    rows_sp = min(n, wl.S + wl.W)
+    rows_se = m + c
+    total = 0
+    for l in layers:
+        hs = int((ht[l] == 0).sum())
+        hm = wl.H - hs
+        total += wl.B * hs * (rows_sp * 2 * row + 2 * row)
+        total += wl.B * hm * (rows_se * 2 * row + rows_se * 8 + 2 * row)
+    return total
+
+
+def algorithmic_bytes_append(wl, ht, layers):
+    """Bytes the append moves: the new K and V rows read and written, plus position and score of a semantic head."""
+    row = wl.d * (2 if wl.dtype == "bf16" else 4)
+    total = 0
+    for l in layers:
+        hm = int((ht[l] == 1).sum())
+        total += wl.B * wl.H * 4 * row + wl.B * hm * 8
+    return total
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=3, help="workload: index into the benchmark configurations (1-based)")
+    ap.add_argument("--layers-per-call", type=int, default=1, help="layers handed to each library call (1 = as a real model would)")
+    ap.add_argument("--prompts", type=int, default=0, help="override the number of prompts (0 = the configuration's)")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--tune", type=str, default="", help="ch,wpu launch-shape knobs of the attention kernel")
+    ap.add_argument("--separate", action="store_true", help="three launches per layer (append, attend, compress) instead of the fused ssd_decode_step")
+    ap.add_argument("--cpu-units", type=int, default=256)
+    ap.add_argument("--grid-rows", type=int, default=0, help="profiling aid: shorten the image to this many grid rows (0 = full image)")
+    ap.add_argument("--no-accumulate", action="store_true", help="experiment: attention without the running-score update")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every unit of work is independent; see DESIGN.md for how it "
+              "would shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2510_18716_amd as ssd
+    import workload
+    from paper_2510_18716_amd.binding import make_config
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    wl = workload.config(args.config)
+    if args.prompts:
+        wl = wl.replace(prompts=args.prompts)
+    if args.grid_rows:
+        wl = wl.replace(grid_h=args.grid_rows, name=wl.name + "-rows%d" % args.grid_rows)
+    accumulate = not args.no_accumulate
+    ht = workload.head_map(wl)
+    K_steps, W_steps = args.steps, args.warmup
+    assert K_steps + W_steps < wl.n_total - wl.S - wl.W - 2, "too many steps for this workload"
+    if args.tune:
+        t = [int(x) for x in args.tune.split(",")] + [0]
+        assert ssd.lib.ssd_tune_attend(t[0], t[1], t[2]) == 0
+    lpc = max(1, min(wl.L, args.layers_per_call))
+    fused = not args.separate
+
+    t0 = time.time()
+    data = workload.generate(wl, device=dev, head_type=ht)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t0
+    sched = workload.compress_schedule(wl)
+    cfg = make_config(wl.L, wl.B, wl.H, wl.d, wl.dtype, wl.W, wl.S, wl.M, wl.R, wl.C, 0.0)
+    cache = ssd.Cache(cfg, ht, device=dev)
+    out = torch.empty((wl.L, wl.B, wl.H, wl.d), dtype=wl.torch_dtype, device=dev)
+    calls = [(lb, min(wl.L, lb + lpc)) for lb in range(0, wl.L, lpc)]
+
+    def step(p, timers=None, acct=None):
+        q, k, v = data["q"][p], data["k"][p], data["v"][p]
+        for ci, (lb, le) in enumerate(calls):
+            if fused:
+                if acct is not None:                # what this launch has to move, from the live counters
+                    n_, m_, c_, _ = cache.layer_state(lb)
+                    acct.append(algorithmic_bytes_attend(wl, ht, range(lb, le), (n_ + 1, m_, c_ + 1)) +
+                                algorithmic_bytes_append(wl, ht, range(lb, le)))
+                if timers is not None:
+                    timers[0][ci].record()
+                ssd.ssd_decode_step(cache, lb, le, q[lb:le], k[lb:le], v[lb:le], out[lb:le], accumulate, bool(sched[p]))
+                if timers is not None:
+                    timers[1][ci].record()
+                continue
+            ssd.ssd_append_token(cache, lb, le, k[lb:le], v[lb:le])
+            if acct is not None:
+                acct.append(algorithmic_bytes_attend(wl, ht, range(lb, le), cache.layer_state(lb)[:3]))
+            if timers is not None:
+                timers[0][ci].record()
+            ssd.ssd_decode_attn(cache, lb, le, q[lb:le], out[lb:le], accumulate)
+            if timers is not None:
+                timers[1][ci].record()
+            if sched[p]:
+                ssd.ssd_compress_kv(cache, lb, le)
+
+    p_timed = wl.n_total - K_steps
+    p_warm = p_timed - W_steps
+    for p in range(0, p_warm):                      # untimed fill: prompt and the earlier part of the image
+        step(p)
+    torch.cuda.synchronize()
+    for p in range(p_warm, p_timed):
+        step(p)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for p in range(p_timed, wl.n_total):
+        step(p)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / K_steps * 1e3
+    tokens_per_s = wl.prompts * K_steps / dt
+    # algorithmic bytes of the attention launches of the timed steps, from the counters each launch ran with
+    acct = []
+    ssd.lib.ssd_cache_set_launch(cache.handle, 0)
+    cache.reset()
+    for p in range(0, wl.n_total):
+        step(p, acct=acct if p >= p_timed else None)
+    ssd.lib.ssd_cache_set_launch(cache.handle, 1)
+    bytes_step = sum(acct) / K_steps
+
+    result = {
+        "metric": "visual tokens/sec per GPU (compressed decode attn, all layers)",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.L, "prompts": wl.prompts, "sequences": wl.B, "heads": wl.H,
+                   "head_dim": wl.d, "prompt_tokens": wl.n0, "visual_tokens": wl.N, "window": wl.W, "budget": wl.M,
+                   "init_sink": wl.S, "recent": wl.R, "stage_cap": wl.C, "cadence": wl.cadence,
+                   "spatial_fraction": wl.spatial_frac, "layers_per_call": lpc,
+                   "step": "append + attend(+score accumulate) + compress, every layer",
+                   "launches_per_layer": "1 (ssd_decode_step)" if fused else "3 (ssd_append_token, ssd_decode_attn, ssd_compress_kv)",
+                   "timed_at": "last %d tokens of the raster decode (n -> %d)" % (K_steps, wl.n_total)},
+        "algorithmic_GB_per_step": bytes_step / 1e9,
+        "whole_step_GBps": bytes_step / 1e9 / (dt / K_steps),
+        "setup_s": {"generate_inputs": round(t_gen, 2)},
+    }
+
+    # ---- roofline of the dominant kernel: HIP events around every attention launch, second pass ----------
+    if not args.no_roofline:
+        cache.reset()                               # same decode again from an empty cache
+        for p in range(0, p_warm):
+            step(p)
+        for p in range(p_warm, p_timed):
+            step(p)
+        ev = [[[torch.cuda.Event(enable_timing=True) for _ in calls] for _ in range(2)] for _ in range(K_steps)]
+        torch.cuda.synchronize()
+        for i, p in enumerate(range(p_timed, wl.n_total)):
+            step(p, ev[i])
+        torch.cuda.synchronize()
+        durs = [ev[i][0][ci].elapsed_time(ev[i][1][ci]) for i in range(K_steps) for ci in range(len(calls))]
+        avg_ms = float(np.mean(durs))
+        bytes_launch = bytes_step / len(calls)
+        achieved = bytes_launch / 1e9 / (avg_ms / 1e3)
+        traffic = MEASURED_TRAFFIC_BYTES.get((wl.name, lpc))
+        result["roofline"] = {"bound": "hbm", "kernel": "step_kernel (ssd_decode_step: append + attention + selection)" if fused else "step_kernel (ssd_decode_attn)", "achieved": achieved,
+                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                              "algorithmic_bytes_per_launch": bytes_launch, "avg_launch_ms": avg_ms,
+                              "median_launch_ms": float(np.median(durs)), "launches": len(durs),
+                              "timer": "HIP events on the launch stream around each launch"}
+
+    # ---- the same steps through the dense full-cache kernel -----------------------------------------------
+    if not args.no_dense:
+        t0 = time.time()
+        n = wl.n_total
+        Kd = [workload.dense_layout(data["k"][:, l:l + 1])[0] for l in range(wl.L)]
+        Vd = [workload.dense_layout(data["v"][:, l:l + 1])[0] for l in range(wl.L)]
+        ws = torch.empty(ssd.ssd_dense_workspace_bytes(wl.B, wl.H, wl.d, n), dtype=torch.uint8, device=dev)
+        outd = torch.empty((wl.B, wl.H, wl.d), dtype=wl.torch_dtype, device=dev)
+        torch.cuda.synchronize()
+        t_dense_setup = time.time() - t0
+        reps = max(3, min(K_steps, 20))
+
+        def dense_step(p):
+            for l in range(wl.L):
+                ssd.ssd_dense_decode_attn(data["q"][p, l], Kd[l], Vd[l], outd, wl.B, wl.H, wl.d, wl.dtype, n, p + 1, 0.0,
+                                          None, None, 1, 0, 32, ws)
+        for p in range(n - reps - 2, n - reps):
+            dense_step(p)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for p in range(n - reps, n):
+            dense_step(p)
+        torch.cuda.synchronize()
+        dtd = (time.perf_counter() - t0) / reps
+        row = wl.d * (2 if wl.dtype == "bf16" else 4)
+        dense_bytes = wl.L * wl.B * wl.H * ((n - reps / 2) * 2 * row + 2 * row)
+        result["dense_baseline"] = {"value": wl.prompts / dtd, "unit": "tokens/s", "ms_per_step": dtd * 1e3,
+                                    "algorithmic_GB_per_step": dense_bytes / 1e9, "GBps": dense_bytes / 1e9 / dtd,
+                                    "frac_of_hbm_peak": dense_bytes / 1e9 / dtd / HBM_PEAK_GBS, "steps": reps,
+                                    "kind": "hand-written HIP split-K decode attention over all n rows, append not included",
+                                    "speedup_of_compressed": dtd / (dt / K_steps)}
+        result["setup_s"]["dense_layout"] = round(t_dense_setup, 2)
+        del Kd, Vd
+
+    # ---- CPU oracle on a sample of units ------------------------------------------------------------------
+    if not args.no_cpu:
+        import oracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from harness import sample_units
+        cores = min(16, os.cpu_count() or 1)
+        units = sample_units(wl, ht, args.cpu_units, seed=1)
+        host = []
+        for (l, b, h) in units:
+            host.append(tuple(np.ascontiguousarray(data[x][:, l, b, h, :].float().cpu().numpy()) for x in "qkv"))
+
+        def run_unit(i):
+            l, b, h = units[i]
+            u = oracle.Unit(ht[l, h] == workload.SEMANTIC, wl.W, wl.S, wl.M, wl.R, wl.C)
+            q_, k_, v_ = host[i]
+            u.run(q_, k_, v_, wl.scale, sched)
+            return 0
+
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(cores) as ex:
+            list(ex.map(run_unit, range(len(units))))
+        t_cpu = time.perf_counter() - t0
+        unit_steps_per_s = len(units) * wl.n_total / t_cpu
+        units_per_step = wl.L * wl.B * wl.H
+        result["cpu_baseline"] = {"value": wl.prompts * unit_steps_per_s / units_per_step, "unit": "tokens/s", "cores": cores,
+                                  "kind": "oracle",
+                                  "sample": "%d of %d (layer, sequence, head) units decoded over all %d tokens in %.1f s, "
+                                            "extrapolated to all units (units are independent)" % (
+                                                len(units), units_per_step, wl.n_total, t_cpu)}
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -15,12 +15,11 @@
  * Conventions that hold for every entry point
  *   - "dev" pointers are device (HBM) addresses owned by the caller; "host"
  *     pointers are ordinary host memory.  The library allocates no device
- *     memory and frees none.  Tensors are dense, row-major, innermost
+ *     memory and frees none; it keeps nothing on the device besides the
+ *     caller's cache memory (layout tables travel as kernel arguments).  Tensors are dense, row-major, innermost
  *     dimension last, 16-byte aligned.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
- *     Calls only enqueue work on it and never wait for the device, with one
- *     exception: the first launching call on a cache copies a few KB of
- *     layout tables to the device with a blocking host-to-device copy.
+ *     Calls only enqueue work on it and never wait for the device.
  *   - Return value: 0 (SSD_OK) or a negative ssd_status.  Argument, range,
  *     ordering and overflow errors are found from host-side counters before
  *     anything is enqueued and leave the cache unchanged.  The text of the
@@ -36,6 +35,7 @@
  *
  * Call order per generated token and layer:
  *     ssd_append_token -> ssd_decode_attn -> (ssd_compress_kv when due)
+ * or the same three fused into one launch: ssd_decode_step.
  * Compressing after every token is Algorithm 1; compressing every 24 tokens
  * (one grid row) is Algorithm 2.  The row buffer holds C tokens, so at most
  * C - R tokens can be appended between two compressions.
@@ -71,7 +71,7 @@ typedef enum ssd_status {
 typedef struct ssd_config {
     int32_t n_layers;      /* L                                                            */
     int32_t n_seqs;        /* B = 2 x prompts                                              */
-    int32_t n_heads;       /* H, one query row per KV head (plain multi-head attention)     */
+    int32_t n_heads;       /* H <= 128, one query row per KV head (plain multi-head attention) */
     int32_t head_dim;      /* d: 64 or 128                                                 */
     int32_t dtype;         /* ssd_dtype of q, k, v, the cache rows and the output          */
     int32_t window;        /* W >= 1: ring slots of a spatial head, counts the new token   */
@@ -186,6 +186,20 @@ int ssd_decode_attn(ssd_cache *cache, int layer_begin, int layer_end,
 int ssd_compress_kv(ssd_cache *cache, int layer_begin, int layer_end,
                     const void *K_src, const void *V_src, const float *score_src,
                     int n_src, void *stream);
+
+/*
+ * One whole decode step of the layers in a single launch per layer group:
+ * ssd_append_token, then ssd_decode_attn, then (compress != 0) the in-place
+ * mode of ssd_compress_kv, with exactly their results.  Each (sequence, head)
+ * is handled by one workgroup from append to selection, so the three steps
+ * of Algorithm 1 cost one pass over the head's rows.
+ *   q, k_new, v_new, out : dev [layer_end - layer_begin, B, H, d], cache dtype
+ * Errors as for the three separate calls (overflow is checked first and
+ * leaves every layer unchanged).
+ */
+int ssd_decode_step(ssd_cache *cache, int layer_begin, int layer_end, const void *q,
+                    const void *k_new, const void *v_new, void *out,
+                    int accumulate_scores, int compress, void *stream);
 
 /*
  * Test / benchmark export of one layer's index table.

@@ -56,6 +56,8 @@ lib.ssd_append_token.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp]
 lib.ssd_append_token.restype = C.c_int
 lib.ssd_decode_attn.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, C.c_int, _vp]
 lib.ssd_decode_attn.restype = C.c_int
+lib.ssd_decode_step.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp, _vp, C.c_int, C.c_int, _vp]
+lib.ssd_decode_step.restype = C.c_int
 lib.ssd_compress_kv.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp, C.c_int, _vp]
 lib.ssd_compress_kv.restype = C.c_int
 lib.ssd_cache_export_slots.argtypes = [_vp]
@@ -207,6 +209,12 @@ def ssd_decode_attn(cache: Cache, layer_begin: int, layer_end: int, q, out, accu
                     stream=None) -> None:
     _check(lib.ssd_decode_attn(cache.handle, layer_begin, layer_end, _ptr(q), _ptr(out), int(bool(accumulate_scores)),
                                _stream(stream)), "ssd_decode_attn")
+
+
+def ssd_decode_step(cache: Cache, layer_begin: int, layer_end: int, q, k_new, v_new, out, accumulate_scores: bool = True,
+                    compress: bool = True, stream=None) -> None:
+    _check(lib.ssd_decode_step(cache.handle, layer_begin, layer_end, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                               int(bool(accumulate_scores)), int(bool(compress)), _stream(stream)), "ssd_decode_step")
 
 
 def ssd_compress_kv(cache: Cache, layer_begin: int, layer_end: int, K_src=None, V_src=None, score_src=None,

@@ -21,7 +21,7 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
-]
+] + (["-DSSD_PROBE"] if os.environ.get("SSD_PROBE") else [])
 
 
 def sources():

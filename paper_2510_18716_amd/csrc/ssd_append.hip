@@ -9,9 +9,9 @@ namespace ssd {
 
 struct AppendArgs {
     Geom g;
+    LaunchMeta lm;
     const char *k_new;
     const char *v_new;
-    int layer_begin;     // absolute index of the first layer of this launch
     int layer_off;       // index of that layer inside k_new / v_new
     int n_units;         // layers * B * H
     int lpr;             // 16-byte fragments per row
@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
     const int lrel = unit / BH;
     const int rem = unit % BH;
     const int b = rem / a.g.H, h = rem % a.g.H;
-    const UnitRef u = unit_ref(a.g, a.layer_begin + lrel, b, h);
+    const UnitRef u = unit_ref(a.g, a.lm.layer[lrel], b, h);
     const size_t src_row = ((size_t)(a.layer_off + lrel) * BH + rem) * (size_t)a.g.row_bytes;
     const char *src = (kv ? a.v_new : a.k_new) + src_row + (size_t)sub * 16u;
     const int slot = u.sem ? a.slot_se : a.slot_sp;
@@ -59,14 +59,10 @@ extern "C" int ssd_append_token(ssd_cache *cache, int layer_begin, int layer_end
     const ssd_config &cf = cache->cfg;
     // a full row buffer in any layer refuses the whole call (nothing is appended anywhere)
     for (int l = layer_begin; l < layer_end; ++l)
-        if (cache->lmeta[l].n_se > 0 && cache->st[l].c >= cf.stage_cap)
+        if (cache->ldesc[l].n_se > 0 && cache->st[l].c >= cf.stage_cap)
             return fail(SSD_ERR_STAGE_OVERFLOW, "row buffer overflow: layer %d already buffers %d tokens (C=%d); call ssd_compress_kv",
                         l, cache->st[l].c, cf.stage_cap);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (cache->launch_enabled) {
-        rc = ensure_meta(cache, s);
-        if (rc != SSD_OK) return rc;
-    }
     const int BH = cf.n_seqs * cf.n_heads;
     for (int lb = layer_begin; lb < layer_end;) {
         const int le = same_state_run(cache, lb, layer_end);
@@ -76,7 +72,7 @@ extern "C" int ssd_append_token(ssd_cache *cache, int layer_begin, int layer_end
             a.g = make_geom(cache);
             a.k_new = static_cast<const char *>(k_new);
             a.v_new = static_cast<const char *>(v_new);
-            a.layer_begin = lb;
+            fill_launch_meta(cache, lb, le, &a.lm);
             a.layer_off = lb - layer_begin;
             a.n_units = (le - lb) * BH;
             a.lpr = a.g.row_bytes / 16;
@@ -91,7 +87,7 @@ extern "C" int ssd_append_token(ssd_cache *cache, int layer_begin, int layer_end
         }
         for (int l = lb; l < le; ++l) {
             cache->st[l].n += 1;
-            if (cache->lmeta[l].n_se > 0) cache->st[l].c += 1;   // a layer without semantic heads has no row buffer
+            if (cache->ldesc[l].n_se > 0) cache->st[l].c += 1;   // a layer without semantic heads has no row buffer
         }
         lb = le;
     }

@@ -3,7 +3,6 @@
 //
 // HBM layout of a cache (all regions 256-byte aligned), chosen so that everything one
 // (layer, sequence, head) unit reads in a decode step is one contiguous run:
-//   [ tables : LayerMeta[L], head_info[L*H] ]
 //   per layer l:
 //     spatial units  [B][Hs_l] : K plane (S+W rows) then V plane (S+W rows)
 //     semantic units [B][Hm_l] : K plane (M+C rows) then V plane (M+C rows)
@@ -48,8 +47,8 @@ static int esize_of(int dtype) { return dtype == SSD_F32 ? 4 : dtype == SSD_BF16
 static int validate(const ssd_config *c, const uint8_t *head_type) {
     if (!c || !head_type) return fail(SSD_ERR_INVALID_ARG, "config or head_type is NULL");
     if (c->n_layers < 1 || c->n_layers > 1024) return fail(SSD_ERR_INVALID_ARG, "n_layers=%d outside 1..1024", c->n_layers);
-    if (c->n_seqs < 1 || c->n_seqs > (1 << 20)) return fail(SSD_ERR_INVALID_ARG, "n_seqs=%d outside 1..2^20", c->n_seqs);
-    if (c->n_heads < 1 || c->n_heads > 1024) return fail(SSD_ERR_INVALID_ARG, "n_heads=%d outside 1..1024", c->n_heads);
+    if (c->n_seqs < 1 || c->n_seqs > 65535) return fail(SSD_ERR_INVALID_ARG, "n_seqs=%d outside 1..65535", c->n_seqs);
+    if (c->n_heads < 1 || c->n_heads > 128) return fail(SSD_ERR_INVALID_ARG, "n_heads=%d outside 1..128", c->n_heads);
     if (c->head_dim != 64 && c->head_dim != 128) return fail(SSD_ERR_INVALID_ARG, "head_dim=%d, supported: 64, 128", c->head_dim);
     if (esize_of(c->dtype) == 0) return fail(SSD_ERR_INVALID_ARG, "dtype=%d is neither SSD_F32 nor SSD_BF16", c->dtype);
     if (c->window < 1) return fail(SSD_ERR_INVALID_ARG, "window W=%d must be >= 1", c->window);
@@ -68,45 +67,38 @@ static int validate(const ssd_config *c, const uint8_t *head_type) {
     return SSD_OK;
 }
 
-// Fills lmeta/hinfo (if non-null) and returns the total byte size.
-static size_t plan_layout(const ssd_config *c, const uint8_t *head_type, std::vector<LayerMeta> *lmeta,
-                          std::vector<uint32_t> *hinfo, size_t *meta_bytes, int *n_sp_total, int *n_se_total) {
+// Fills ldesc (if non-null) and returns the total byte size.
+static size_t plan_layout(const ssd_config *c, const uint8_t *head_type, std::vector<LayerDesc> *ldesc) {
     const int L = c->n_layers, H = c->n_heads;
     const size_t row = (size_t)c->head_dim * esize_of(c->dtype);
     const size_t unit_sp = 2 * (size_t)(c->n_init_sink + c->window) * row;
     const size_t unit_se = 2 * (size_t)(c->budget + c->stage_cap) * row;
     const size_t slots = (size_t)c->budget + c->stage_cap;
-    size_t off = align_up(sizeof(LayerMeta) * (size_t)L, 256);
-    off = align_up(off + sizeof(uint32_t) * (size_t)L * H, 256);
-    if (meta_bytes) *meta_bytes = off;
-    if (lmeta) lmeta->resize(L);
-    if (hinfo) hinfo->resize((size_t)L * H);
-    int sp_tot = 0, se_tot = 0;
+    size_t off = 0;
+    if (ldesc) ldesc->resize(L);
     for (int l = 0; l < L; ++l) {
-        int n_sp = 0, n_se = 0;
+        LayerDesc m;
+        m.sem_mask[0] = m.sem_mask[1] = 0;
+        m.n_sp = m.n_se = 0;
         for (int h = 0; h < H; ++h) {
-            const bool sem = head_type[(size_t)l * H + h] == SSD_SEMANTIC;
-            const uint32_t local = sem ? n_se++ : n_sp++;
-            if (hinfo) (*hinfo)[(size_t)l * H + h] = local | (sem ? HEAD_SEM_BIT : 0u);
+            if (head_type[(size_t)l * H + h] == SSD_SEMANTIC) {
+                m.sem_mask[h >> 6] |= 1ull << (h & 63);
+                m.n_se++;
+            } else {
+                m.n_sp++;
+            }
         }
-        LayerMeta m;
-        m.n_sp = n_sp;
-        m.n_se = n_se;
         m.off_sp = off;
-        off = align_up(off + (size_t)c->n_seqs * n_sp * unit_sp, 256);
+        off = align_up(off + (size_t)c->n_seqs * m.n_sp * unit_sp, 256);
         m.off_se = off;
-        off = align_up(off + (size_t)c->n_seqs * n_se * unit_se, 256);
+        off = align_up(off + (size_t)c->n_seqs * m.n_se * unit_se, 256);
         m.off_score = off;
-        off = align_up(off + (size_t)c->n_seqs * n_se * slots * sizeof(float), 256);
+        off = align_up(off + (size_t)c->n_seqs * m.n_se * slots * sizeof(float), 256);
         m.off_pos = off;
-        off = align_up(off + (size_t)c->n_seqs * n_se * slots * sizeof(int32_t), 256);
-        if (lmeta) (*lmeta)[l] = m;
-        sp_tot += n_sp;
-        se_tot += n_se;
+        off = align_up(off + (size_t)c->n_seqs * m.n_se * slots * sizeof(int32_t), 256);
+        if (ldesc) (*ldesc)[l] = m;
     }
-    if (n_sp_total) *n_sp_total = sp_tot;
-    if (n_se_total) *n_se_total = se_tot;
-    return off;
+    return off > 0 ? off : 256;
 }
 
 int check_layers(const ssd_cache *c, int lb, int le) {
@@ -116,25 +108,9 @@ int check_layers(const ssd_cache *c, int lb, int le) {
     return SSD_OK;
 }
 
-int ensure_meta(ssd_cache *c, hipStream_t s) {
-    if (c->meta_uploaded) return SSD_OK;
-    // Blocking copies from pageable memory: the host buffers may be reused as soon as they return.
-    // Ordered before any later kernel on `s` because they complete before this function returns.
-    (void)s;
-    hipError_t e = hipMemcpy(c->dev, c->lmeta.data(), sizeof(LayerMeta) * c->lmeta.size(), hipMemcpyHostToDevice);
-    if (e != hipSuccess) return hip_fail(e, "upload of the layer table");
-    const size_t hoff = align_up(sizeof(LayerMeta) * c->lmeta.size(), 256);
-    e = hipMemcpy(c->dev + hoff, c->hinfo.data(), sizeof(uint32_t) * c->hinfo.size(), hipMemcpyHostToDevice);
-    if (e != hipSuccess) return hip_fail(e, "upload of the head table");
-    c->meta_uploaded = true;
-    return SSD_OK;
-}
-
 Geom make_geom(const ssd_cache *c) {
     Geom g;
     g.base = c->dev;
-    g.lmeta = reinterpret_cast<const LayerMeta *>(c->dev);
-    g.hinfo = reinterpret_cast<const uint32_t *>(c->dev + align_up(sizeof(LayerMeta) * c->lmeta.size(), 256));
     g.B = c->cfg.n_seqs;
     g.H = c->cfg.n_heads;
     g.S = c->cfg.n_init_sink;
@@ -145,6 +121,11 @@ Geom make_geom(const ssd_cache *c) {
     g.unit_sp_bytes = 2u * (uint32_t)(g.S + g.W) * (uint32_t)g.row_bytes;
     g.unit_se_bytes = 2u * (uint32_t)(g.M + g.C) * (uint32_t)g.row_bytes;
     return g;
+}
+
+void fill_launch_meta(const ssd_cache *c, int lb, int le, LaunchMeta *out) {
+    for (int l = lb; l < le; ++l) out->layer[l - lb] = c->ldesc[l];
+    for (int i = le - lb; i < LMAX; ++i) out->layer[i] = c->ldesc[lb];   // never indexed; keeps the bytes defined
 }
 
 Segs spatial_segs(const ssd_cache *c, const LayerState &st) {
@@ -170,19 +151,31 @@ Segs semantic_segs(const ssd_cache *c, const LayerState &st) {
     return s;
 }
 
+Segs spatial_segs_without(const ssd_cache *c, const LayerState &st, int skip) {
+    Segs s = spatial_segs(c, st);
+    const int end = s.len[0];
+    if (skip < 0 || skip >= end) return s;
+    s.start[0] = 0;        s.len[0] = skip;
+    s.start[1] = skip + 1; s.len[1] = end - skip - 1;
+    s.total = end - 1;
+    return s;
+}
+
 int same_state_run(const ssd_cache *c, int lb, int le) {
     int l = lb + 1;
-    while (l < le && c->st[l] == c->st[lb]) ++l;
+    // layers with and without semantic heads never share a launch: only the former have a row buffer
+    const bool has_se = c->ldesc[lb].n_se > 0;
+    while (l < le && l - lb < LMAX && c->st[l] == c->st[lb] && (c->ldesc[l].n_se > 0) == has_se) ++l;
     return l;
 }
 
 // ---- export ---------------------------------------------------------------
 
-__global__ void export_kernel(Geom g, int layer, LayerState st, Segs se, int slots, int32_t *pos_out,
+__global__ void export_kernel(Geom g, LayerDesc ld, LayerState st, Segs se, int slots, int32_t *pos_out,
                               int32_t *count_out, float *score_out) {
     const int unit = blockIdx.x;   // b*H + h
     const int b = unit / g.H, h = unit % g.H;
-    const UnitRef u = unit_ref(g, layer, b, h);
+    const UnitRef u = unit_ref(g, ld, b, h);
     const size_t o = (size_t)unit * (size_t)slots;
     int count;
     if (u.sem) {
@@ -224,7 +217,7 @@ extern "C" {
 size_t ssd_cache_bytes(const ssd_config *cfg, const uint8_t *head_type) {
     clear_error();
     if (validate(cfg, head_type) != SSD_OK) return 0;
-    return plan_layout(cfg, head_type, nullptr, nullptr, nullptr, nullptr, nullptr);
+    return plan_layout(cfg, head_type, nullptr);
 }
 
 int ssd_cache_init(const ssd_config *cfg, const uint8_t *head_type, void *dev_mem, size_t bytes, ssd_cache **out) {
@@ -241,14 +234,13 @@ int ssd_cache_init(const ssd_config *cfg, const uint8_t *head_type, void *dev_me
     c->esize = esize_of(cfg->dtype);
     c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
     c->head_type.assign(head_type, head_type + (size_t)cfg->n_layers * cfg->n_heads);
-    const size_t need = plan_layout(cfg, head_type, &c->lmeta, &c->hinfo, &c->meta_bytes, &c->n_sp_total, &c->n_se_total);
+    const size_t need = plan_layout(cfg, head_type, &c->ldesc);
     if (bytes < need) {
         delete c;
         return fail(SSD_ERR_INVALID_ARG, "dev_mem holds %zu bytes, the cache needs %zu", bytes, need);
     }
     c->dev = static_cast<char *>(dev_mem);
     c->bytes = bytes;
-    c->meta_uploaded = false;
     c->launch_enabled = true;
     c->st.assign(cfg->n_layers, LayerState{0, 0, 0, 0});
     *out = c;
@@ -294,12 +286,10 @@ int ssd_cache_export(ssd_cache *cache, int layer, int32_t *pos, int32_t *count, 
     if (!aligned(pos, 4) || !aligned(count, 4) || !aligned(score, 4)) return fail(SSD_ERR_INVALID_ARG, "misaligned output");
     if (!cache->launch_enabled) return SSD_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    rc = ensure_meta(cache, s);
-    if (rc != SSD_OK) return rc;
     const LayerState st = cache->st[layer];
     const Segs se = semantic_segs(cache, st);
     const int units = cache->cfg.n_seqs * cache->cfg.n_heads;
-    hipLaunchKernelGGL(export_kernel, dim3(units), dim3(64), 0, s, make_geom(cache), layer, st, se,
+    hipLaunchKernelGGL(export_kernel, dim3(units), dim3(64), 0, s, make_geom(cache), cache->ldesc[layer], st, se,
                        ssd_cache_export_slots(cache), pos, count, score);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "export launch");

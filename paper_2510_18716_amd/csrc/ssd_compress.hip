@@ -1,40 +1,14 @@
 // ssd_compress_kv: top-M selection by accumulated score and the gather into the compact cache
 // (Algorithm 1 "IndicesOfTopM" / "SelectAndAppend"; Algorithm 2 "Compress semantic cache
-// (heavy-hitter) ... Reset row buffer" and its prefill branch).
-//
-// Selection is exact integer work: a candidate's (score, position) pair becomes one 64-bit key
-//   key = score_bits << 32 | (0xFFFFFFFF - position)
-// Scores are sums of probabilities, hence non-negative floats, whose IEEE bit patterns order like
-// the numbers; the inverted position makes the lower position win a tie.  Keys are distinct, so
-// rank(i) = #{j : key_j > key_i} is a total order and "rank < M" is the kept set -- the same set
-// any correct sort would give, bit for bit.  The candidates of one head (at most M + C, or n_src
-// in dense-source mode) live in LDS and every thread counts ranks for its own candidates; the
-// inner loop reads one LDS word per step as a broadcast, so there are no bank conflicts.
-//
-// In-place consolidation is slot-stable: a heavy token that survives stays where it is; buffered
-// tokens that are promoted fill the slots of evicted (or never used) heavy slots, so the rows
-// moved per compression are only the newly promoted ones.  The row buffer is a ring, so the R
-// protected newest tokens stay put as well.
-#include "ssd_device.h"
+// (heavy-hitter) ... Reset row buffer" and its prefill branch).  The selection itself is in
+// ssd_select.h; this file holds the stand-alone in-place kernel and the dense-source kernel.
+#include "ssd_select.h"
 
 namespace ssd {
 
-static __device__ __forceinline__ unsigned long long make_key(float score, int pos) {
-    return ((unsigned long long)__float_as_uint(score) << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)pos);
-}
-
-// Exclusive prefix count of `flag` over the threads of one wave, plus the wave total.
-static __device__ __forceinline__ int wave_prefix(bool flag, int &total) {
-    const unsigned long long mask = __ballot(flag);
-    const int lane = threadIdx.x & 63;
-    total = __popcll(mask);
-    return __popcll(mask & ((1ull << lane) - 1ull));
-}
-
 struct CompressArgs {
     Geom g;
-    int layer_begin;
-    int n_units;       // layers * B * Hm (semantic units only; all layers of a launch share Hm? no: see unit table)
+    LaunchMeta lm;
     int m;             // heavy slots in use
     int c;             // buffered tokens
     int base;          // ring index of the oldest buffered token
@@ -43,109 +17,34 @@ struct CompressArgs {
 };
 
 // One workgroup per (layer, sequence, head); spatial heads return at once.
-// LDS: keys[n_cand] (u64) | dest[M] (int) | flags
 template <int THREADS>
 __global__ __launch_bounds__(THREADS) void compress_inplace_kernel(CompressArgs a) {
-    extern __shared__ unsigned long long smem_u64[];
+    extern __shared__ __align__(16) unsigned char lds[];
     const int BH = a.g.B * a.g.H;
     const int unit = blockIdx.x;
     const int lrel = unit / BH;
     const int rem = unit % BH;
-    const UnitRef u = unit_ref(a.g, a.layer_begin + lrel, rem / a.g.H, rem % a.g.H);
+    const UnitRef u = unit_ref(a.g, a.lm.layer[lrel], rem / a.g.H, rem % a.g.H);
     if (!u.sem) return;                       // uniform for the whole workgroup
-
-    const int M = a.g.M, C = a.g.C;
     const int n_old = a.c - a.R;              // buffered tokens that become candidates (> 0, checked on the host)
     const int n_cand = a.m + n_old;
-    unsigned long long *keys = smem_u64;                         // [n_cand]
-    int *dest = reinterpret_cast<int *>(keys + n_cand);          // [M]   free heavy slots in ascending order
-    int *src = dest + M;                                         // [n_old] promoted buffered tokens (their slots)
-    __shared__ int s_counts[2];
-    const int tid = threadIdx.x;
-
-    // candidate i: i < m -> heavy slot i; else buffered token j = i - m (oldest first)
-    for (int i = tid; i < n_cand; i += THREADS) {
-        const int slot = i < a.m ? i : M + (a.base + (i - a.m)) % C;
+    unsigned long long *keys = reinterpret_cast<unsigned long long *>(lds);
+    for (int i = threadIdx.x; i < n_cand; i += THREADS) {
+        const int slot = i < a.m ? i : a.g.M + (a.base + (i - a.m)) % a.g.C;
         keys[i] = make_key(u.score[slot], u.pos[slot]);
     }
     __syncthreads();
-
-    // rank by counting; keep[i] = rank < M.  Up to ITEMS candidates per thread, flags in registers.
-    constexpr int ITEMS = (4096 + THREADS - 1) / THREADS;
-    unsigned long long keepbits = 0;          // bit k = candidate tid + k*THREADS is kept
-    static_assert(ITEMS <= 64, "one 64-bit mask per thread");
-    if (n_cand <= M) {
-        keepbits = ~0ull;
-    } else {
-        for (int k = 0; k * THREADS + tid < n_cand; ++k) {
-            const unsigned long long mine = keys[k * THREADS + tid];
-            int rank = 0;
-            for (int j = 0; j < n_cand; ++j) rank += keys[j] > mine ? 1 : 0;
-            if (rank < M) keepbits |= 1ull << k;
-        }
-    }
-    __syncthreads();   // every key has been read; keys' storage is not reused, but dest/src are written next
-
-    // wave 0 turns the flags into two compact lists.  Flags travel through LDS bytes placed after src.
-    unsigned char *flag = reinterpret_cast<unsigned char *>(src + (n_old > 0 ? n_old : 0));   // [M + n_old]
-    // flag[s] for heavy slot s < M: 1 = free after compression (evicted, or never used)
-    for (int s = tid; s < M; s += THREADS) flag[s] = 0;
-    __syncthreads();
-    for (int k = 0; k * THREADS + tid < n_cand; ++k) {
-        const int i = k * THREADS + tid;
-        const bool keep = (keepbits >> k) & 1ull;
-        if (i < a.m) flag[i] = keep ? 0 : 1;
-        else flag[M + (i - a.m)] = keep ? 1 : 0;              // promoted
-    }
-    for (int s = a.m + tid; s < M; s += THREADS) flag[s] = 1;  // unused heavy slots are free
-    __syncthreads();
-    if (tid < 64) {
-        int nfree = 0;
-        for (int s0 = 0; s0 < M; s0 += 64) {
-            const int s = s0 + tid;
-            const bool f = s < M && flag[s] != 0;
-            int tot;
-            const int pre = wave_prefix(f, tot);
-            if (f) dest[nfree + pre] = s;
-            nfree += tot;
-        }
-        int nmove = 0;
-        for (int j0 = 0; j0 < n_old; j0 += 64) {
-            const int j = j0 + tid;
-            const bool f = j < n_old && flag[M + j] != 0;
-            int tot;
-            const int pre = wave_prefix(f, tot);
-            if (f) src[nmove + pre] = M + (a.base + j) % C;
-            nmove += tot;
-        }
-        if (tid == 0) { s_counts[0] = nfree; s_counts[1] = nmove; }
-    }
-    __syncthreads();
-    const int nmove = s_counts[1];            // <= nfree by construction
-    // move the promoted tokens: 2*lpr fragments per token (K row, V row), then its pos and score
-    const int frag_per_tok = 2 * a.lpr;
-    for (int t = tid; t < nmove * frag_per_tok; t += THREADS) {
-        const int k = t / frag_per_tok;
-        const int f = t % frag_per_tok;
-        const int kv = f / a.lpr, sub = f % a.lpr;
-        char *plane = kv ? u.V : u.K;
-        const uint4 v = *reinterpret_cast<const uint4 *>(plane + (size_t)src[k] * a.g.row_bytes + (size_t)sub * 16u);
-        *reinterpret_cast<uint4 *>(plane + (size_t)dest[k] * a.g.row_bytes + (size_t)sub * 16u) = v;
-    }
-    for (int k = tid; k < nmove; k += THREADS) {
-        u.pos[dest[k]] = u.pos[src[k]];
-        u.score[dest[k]] = u.score[src[k]];
-    }
+    select_and_move<THREADS, false>(a.g, u, lds, n_cand, a.m, n_old, a.base, a.lpr, threadIdx.x);
 }
 
 // ---- dense-source mode -------------------------------------------------------
 
 struct DenseSrcArgs {
     Geom g;
+    LaunchMeta lm;
     const char *K_src;      // [L', B, H, n_src, d]
     const char *V_src;
     const float *score_src; // [L', B, H, n_src] or NULL
-    int layer_begin;
     int layer_off;
     int n_src;
     int R;
@@ -159,7 +58,7 @@ __global__ __launch_bounds__(THREADS) void compress_dense_kernel(DenseSrcArgs a)
     const int unit = blockIdx.x;
     const int lrel = unit / BH;
     const int rem = unit % BH;
-    const UnitRef u = unit_ref(a.g, a.layer_begin + lrel, rem / a.g.H, rem % a.g.H);
+    const UnitRef u = unit_ref(a.g, a.lm.layer[lrel], rem / a.g.H, rem % a.g.H);
     const size_t src_unit = (size_t)(a.layer_off + lrel) * BH + rem;
     const char *Ks = a.K_src + src_unit * (size_t)a.n_src * a.g.row_bytes;
     const char *Vs = a.V_src + src_unit * (size_t)a.n_src * a.g.row_bytes;
@@ -240,6 +139,30 @@ __global__ __launch_bounds__(THREADS) void compress_dense_kernel(DenseSrcArgs a)
     }
 }
 
+// In-place compression of layers [lb, le), which all hold the state `st` (st.c - R > 0).
+int launch_compress_inplace(const ssd_cache *cache, int lb, int le, const LayerState &st, hipStream_t s) {
+    const ssd_config &cf = cache->cfg;
+    const int n_old = st.c - cf.recent;
+    CompressArgs a;
+    a.g = make_geom(cache);
+    fill_launch_meta(cache, lb, le, &a.lm);
+    a.m = st.m;
+    a.c = st.c;
+    a.base = st.base;
+    a.R = cf.recent;
+    a.lpr = cf.head_dim * cache->esize / 16;
+    const int n_cand = st.m + n_old;
+    const unsigned units = (unsigned)((le - lb) * cf.n_seqs * cf.n_heads);
+    const size_t lds = select_lds_bytes(cf.budget, n_cand, n_old);
+    if (n_cand <= 192)
+        hipLaunchKernelGGL((compress_inplace_kernel<64>), dim3(units), dim3(64), lds, s, a);
+    else
+        hipLaunchKernelGGL((compress_inplace_kernel<256>), dim3(units), dim3(256), lds, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "compression launch");
+    return SSD_OK;
+}
+
 }  // namespace ssd
 
 using namespace ssd;
@@ -262,62 +185,43 @@ extern "C" int ssd_compress_kv(ssd_cache *cache, int layer_begin, int layer_end,
         const int n_rec = n_src < cf.recent ? n_src : cf.recent;
         const int n_cand = n_src - n_rec;
         if (cache->launch_enabled) {
-            rc = ensure_meta(cache, s);
-            if (rc != SSD_OK) return rc;
-            DenseSrcArgs a;
-            a.g = make_geom(cache);
-            a.K_src = static_cast<const char *>(K_src);
-            a.V_src = static_cast<const char *>(V_src);
-            a.score_src = score_src;
-            a.layer_begin = layer_begin;
-            a.layer_off = 0;
-            a.n_src = n_src;
-            a.R = cf.recent;
-            a.lpr = lpr;
-            const size_t lds = sizeof(unsigned long long) * (size_t)n_cand + sizeof(int) * (size_t)cf.budget + (size_t)n_cand + 16;
-            hipLaunchKernelGGL((compress_dense_kernel<256>), dim3((unsigned)((layer_end - layer_begin) * BH)), dim3(256), lds, s, a);
-            hipError_t e = hipGetLastError();
-            if (e != hipSuccess) return hip_fail(e, "dense-source compression launch");
+            for (int lb = layer_begin; lb < layer_end; lb += LMAX) {
+                const int le = lb + LMAX < layer_end ? lb + LMAX : layer_end;
+                DenseSrcArgs a;
+                a.g = make_geom(cache);
+                fill_launch_meta(cache, lb, le, &a.lm);
+                a.K_src = static_cast<const char *>(K_src);
+                a.V_src = static_cast<const char *>(V_src);
+                a.score_src = score_src;
+                a.layer_off = lb - layer_begin;
+                a.n_src = n_src;
+                a.R = cf.recent;
+                a.lpr = lpr;
+                const size_t lds = sizeof(unsigned long long) * (size_t)n_cand + sizeof(int) * (size_t)cf.budget + (size_t)n_cand + 16;
+                hipLaunchKernelGGL((compress_dense_kernel<256>), dim3((unsigned)((le - lb) * BH)), dim3(256), lds, s, a);
+                hipError_t e = hipGetLastError();
+                if (e != hipSuccess) return hip_fail(e, "dense-source compression launch");
+            }
         }
         for (int l = layer_begin; l < layer_end; ++l) {
             LayerState &st = cache->st[l];
             st.n = n_src;
-            st.m = cache->lmeta[l].n_se > 0 ? (n_cand < cf.budget ? n_cand : cf.budget) : 0;
-            st.c = cache->lmeta[l].n_se > 0 ? n_rec : 0;
+            st.m = cache->ldesc[l].n_se > 0 ? (n_cand < cf.budget ? n_cand : cf.budget) : 0;
+            st.c = cache->ldesc[l].n_se > 0 ? n_rec : 0;
             st.base = 0;
         }
         return SSD_OK;
     }
 
     if (score_src) return fail(SSD_ERR_INVALID_ARG, "score_src without K_src / V_src");
-    if (cache->launch_enabled) {
-        rc = ensure_meta(cache, s);
-        if (rc != SSD_OK) return rc;
-    }
     for (int lb = layer_begin; lb < layer_end;) {
         const int le = same_state_run(cache, lb, layer_end);
         const LayerState st = cache->st[lb];
         const int n_old = st.c - cf.recent;
         if (n_old > 0) {            // otherwise nothing is due in these layers (also: no semantic heads, c == 0)
             if (cache->launch_enabled) {
-                CompressArgs a;
-                a.g = make_geom(cache);
-                a.layer_begin = lb;
-                a.n_units = (le - lb) * BH;
-                a.m = st.m;
-                a.c = st.c;
-                a.base = st.base;
-                a.R = cf.recent;
-                a.lpr = lpr;
-                const int n_cand = st.m + n_old;
-                const size_t lds = sizeof(unsigned long long) * (size_t)n_cand + sizeof(int) * (size_t)(cf.budget + n_old) +
-                                   (size_t)(cf.budget + n_old) + 16;
-                if (n_cand <= 192)
-                    hipLaunchKernelGGL((compress_inplace_kernel<64>), dim3((unsigned)a.n_units), dim3(64), lds, s, a);
-                else
-                    hipLaunchKernelGGL((compress_inplace_kernel<256>), dim3((unsigned)a.n_units), dim3(256), lds, s, a);
-                hipError_t e = hipGetLastError();
-                if (e != hipSuccess) return hip_fail(e, "compression launch");
+                rc = launch_compress_inplace(cache, lb, le, st, s);
+                if (rc != SSD_OK) return rc;
             }
             for (int l = lb; l < le; ++l) {
                 LayerState &x = cache->st[l];

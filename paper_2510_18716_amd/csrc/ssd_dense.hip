@@ -36,7 +36,7 @@ template <typename T, int D, int CH, int WPB>
 __global__ __launch_bounds__(WPB * 64) void dense_kernel(DenseArgs a) {
     constexpr int VEC = Elem<T>::VEC;
     constexpr int LPR = D / VEC;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int sub = lane % LPR;
     const long long item = (long long)blockIdx.x * WPB + wave;       // unit * splits + split
@@ -44,13 +44,7 @@ __global__ __launch_bounds__(WPB * 64) void dense_kernel(DenseArgs a) {
     const int unit = (int)(item / a.splits);
     const int split = (int)(item % a.splits);
     const size_t qoff = (size_t)unit * a.row_bytes + (size_t)sub * 16u;
-    float q[VEC];
-    {
-        const uint4 qr = *reinterpret_cast<const uint4 *>(a.q + qoff);
-        Elem<T>::unpack(qr, q);
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) q[e] *= a.qscale;
-    }
+    const typename Elem<T>::Q q = Elem<T>::load_q(*reinterpret_cast<const uint4 *>(a.q + qoff));
     const char *Kb = a.K + (size_t)unit * (size_t)a.n_cap * (size_t)a.row_bytes;
     const char *Vb = a.V + (size_t)unit * (size_t)a.n_cap * (size_t)a.row_bytes;
     Segs sg = {{0, 0, 0}, {a.n, 0, 0}, a.n};
@@ -60,7 +54,7 @@ __global__ __launch_bounds__(WPB * 64) void dense_kernel(DenseArgs a) {
     Softmax<VEC> sm;
     sm.init();
     if (r_begin < r_end)
-        stream_rows<T, D, CH, false, true>(Kb, Vb, a.row_bytes, sg, r_begin, r_end, q, sm, nullptr, a.vis_start, a.far_last);
+        stream_rows<T, D, CH, false, true>(Kb, Vb, a.row_bytes, sg, r_begin, r_end, 0, 1, q, a.qscale, sm, nullptr, a.vis_start, a.far_last);
     merge_groups<VEC, LPR, true>(sm);
     if (a.splits == 1) {
         const float inv_l = sm.l > 0.f ? 1.0f / sm.l : 0.f;

@@ -23,16 +23,35 @@ static constexpr float LOG2E = 1.4426950408889634f;
 
 struct bf16_t { uint16_t bits; };   // tag type: storage is a raw bfloat16
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// Elem<T>: how a 16-byte fragment of T is turned into arithmetic.
+//   Q       : register form of this lane's query fragment
+//   dot     : fp32 dot product of the query fragment with a raw K fragment
+//   unpack  : raw fragment -> VEC floats (for the p * V accumulation)
 template <typename T> struct Elem;
 
 template <> struct Elem<float> {
     static constexpr int VEC = 4;
+    struct Q { float f[4]; };
     static __device__ __forceinline__ void unpack(const uint4 &r, float (&f)[4]) {
         f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
         f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
     }
     static __device__ __forceinline__ uint4 pack(const float (&f)[4]) {
         return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+    }
+    static __device__ __forceinline__ Q load_q(const uint4 &r) {
+        Q q;
+        unpack(r, q.f);
+        return q;
+    }
+    static __device__ __forceinline__ float dot(const Q &q, const uint4 &k) {
+        float d = q.f[0] * __uint_as_float(k.x);
+        d = fmaf(q.f[1], __uint_as_float(k.y), d);
+        d = fmaf(q.f[2], __uint_as_float(k.z), d);
+        d = fmaf(q.f[3], __uint_as_float(k.w), d);
+        return d;
     }
 };
 
@@ -46,6 +65,7 @@ static __device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
 
 template <> struct Elem<bf16_t> {
     static constexpr int VEC = 8;
+    struct Q { uint4 r; };      // the query stays packed: v_dot2_f32_bf16 multiplies bf16 pairs exactly into fp32
     static __device__ __forceinline__ void unpack(const uint4 &r, float (&f)[8]) {
         f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
         f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
@@ -57,6 +77,17 @@ template <> struct Elem<bf16_t> {
                           f32_to_bf16_bits(f[2]) | (f32_to_bf16_bits(f[3]) << 16),
                           f32_to_bf16_bits(f[4]) | (f32_to_bf16_bits(f[5]) << 16),
                           f32_to_bf16_bits(f[6]) | (f32_to_bf16_bits(f[7]) << 16));
+    }
+    static __device__ __forceinline__ Q load_q(const uint4 &r) { return Q{r}; }
+    static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+    }
+    static __device__ __forceinline__ float dot(const Q &q, const uint4 &k) {
+        float d = dot2(q.r.x, k.x, 0.f);
+        d = dot2(q.r.y, k.y, d);
+        d = dot2(q.r.z, k.z, d);
+        d = dot2(q.r.w, k.w, d);
+        return d;
     }
 };
 
@@ -90,12 +121,11 @@ template <int G> static __device__ __forceinline__ float across_groups_max(float
 
 static __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// slot of the r-th valid row of a unit
+// slot of the r-th valid row of a unit (branch-free: two compares and selects)
 static __device__ __forceinline__ int seg_slot(const Segs &s, int r) {
-    if (r < s.len[0]) return s.start[0] + r;
-    r -= s.len[0];
-    if (r < s.len[1]) return s.start[1] + r;
-    return s.start[2] + (r - s.len[1]);
+    const int e0 = s.len[0], e1 = s.len[0] + s.len[1];
+    const int a0 = s.start[0], a1 = s.start[1] - e0, a2 = s.start[2] - e1;
+    return r + (r < e0 ? a0 : (r < e1 ? a1 : a2));
 }
 
 // ---- the streaming loop ----------------------------------------------------
@@ -111,53 +141,67 @@ template <int VEC> struct Softmax {
     }
 };
 
-// Stream the valid rows [row_begin, row_end) of one unit.
-//   Kb, Vb    : first K / V row of the unit (slot 0)
+// Stream valid rows of one unit.  Rows are taken RPW at a time ("iterations", one wave-wide 1 KB
+// load of K and one of V); this wave handles iterations first_iter, first_iter + iter_stride, ...
+// counted from row_begin, so the waves that share a unit read adjacent 1 KB pieces at the same
+// time.  CH iterations form a chunk; the loads of the next chunk are issued before the arithmetic
+// of the current one (two register buffers), so a wave always has requests in flight.
+//   Kb, Vb    : first K / V row of the unit (slot 0); wave-uniform
 //   sg        : valid-slot runs; row index r means the r-th valid row
-//   q         : this lane's VEC query elements, already multiplied by scale * log2(e)
-//   zbuf      : wave-private LDS, receives the logit of every row (index r) when ZBUF
+//   q, qscale : this lane's query fragment and softmax scale * log2(e)
+//   zbuf      : LDS, receives the scaled logit of every row (index r) when ZBUF
 //   MASS      : also accumulate the probability mass of rows >= vis_start (tot) and of rows in
 //               [vis_start, far_last] (far)
-template <typename T, int D, int CH, bool ZBUF, bool MASS>
+// first_iter and iter_stride must be wave-uniform (scalar) values.
+template <typename T, int D, int CH, bool ZBUF, bool MASS, bool PF = true>
 static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, const char *__restrict__ Vb,
                                                   int row_bytes, const Segs &sg, int row_begin, int row_end,
-                                                  const float (&q)[Elem<T>::VEC], Softmax<Elem<T>::VEC> &sm,
-                                                  float *zbuf, int vis_start, int far_last) {
+                                                  int first_iter, int iter_stride,
+                                                  const typename Elem<T>::Q &q, float qscale,
+                                                  Softmax<Elem<T>::VEC> &sm, float *zbuf, int vis_start, int far_last,
+                                                  int g_probe = 0) {
     constexpr int VEC = Elem<T>::VEC;
     constexpr int LPR = D / VEC;
     constexpr int RPW = 64 / LPR;
     const int lane = threadIdx.x & 63;
     const int grp = lane / LPR;
-    const int sub = lane % LPR;
+    const uint32_t lane_off = (uint32_t)(lane % LPR) * 16u;
+    const int n_iter = (row_end - row_begin + RPW - 1) / RPW;
+    const int chunk_iters = CH * iter_stride;
 
-    for (int r0 = row_begin; r0 < row_end; r0 += RPW * CH) {
-        uint4 kr[CH], vr[CH];
-        bool ok[CH];
+    // issue the loads of the chunk that starts at iteration it0 (clamped rows reload the last row:
+    // same cache line as a neighbouring lane's, so no extra HBM traffic)
+    auto load = [&](int it0, uint4 (&kr)[CH], uint4 (&vr)[CH]) {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const int r = r0 + i * RPW + grp;
-            ok[i] = r < row_end;
-            const int slot = seg_slot(sg, ok[i] ? r : row_begin);
-            const size_t off = (size_t)slot * (size_t)row_bytes + (size_t)sub * 16u;
-            if (ok[i]) {
+            const int it = it0 + i * iter_stride;
+            if (it < n_iter) {                                   // wave-uniform
+                int r = row_begin + it * RPW + grp;
+                r = r < row_end ? r : row_end - 1;
+                const uint32_t off = (uint32_t)seg_slot(sg, r) * (uint32_t)row_bytes + lane_off;
                 kr[i] = *reinterpret_cast<const uint4 *>(Kb + off);
                 vr[i] = *reinterpret_cast<const uint4 *>(Vb + off);
-            } else {
-                kr[i] = make_uint4(0, 0, 0, 0);
-                vr[i] = make_uint4(0, 0, 0, 0);
             }
         }
+    };
+    auto compute = [&](int it0, const uint4 (&kr)[CH], const uint4 (&vr)[CH]) {
+#ifdef SSD_PROBE
+        if (g_probe == 1) {      // probe: loads only, trivial arithmetic
+#pragma unroll
+            for (int i = 0; i < CH; ++i) sm.acc[0] += __uint_as_float(kr[i].x ^ kr[i].y ^ kr[i].z ^ kr[i].w ^ vr[i].x ^ vr[i].y ^ vr[i].z ^ vr[i].w);
+            sm.l = 1.f;
+            return;
+        }
+#endif
         float z[CH];
         float mx = NEG_BIG;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            float kf[VEC];
-            Elem<T>::unpack(kr[i], kf);
-            float dot = 0.f;
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) dot = fmaf(q[e], kf[e], dot);
-            dot = group_sum<LPR>(dot);
-            z[i] = ok[i] ? dot : NEG_BIG;
+            const int it = it0 + i * iter_stride;
+            const int r = row_begin + it * RPW + grp;
+            const bool ok = it < n_iter && r < row_end;
+            const float dot = group_sum<LPR>(Elem<T>::dot(q, kr[i]));
+            z[i] = ok ? dot * qscale : NEG_BIG;
             mx = fmaxf(mx, z[i]);
         }
         const float m_new = fmaxf(sm.m, mx);
@@ -168,20 +212,53 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
         for (int e = 0; e < VEC; ++e) sm.acc[e] *= alpha;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const int r = r0 + i * RPW + grp;
-            const float p = ok[i] ? fast_exp2(z[i] - m_new) : 0.f;
-            sm.l += p;
-            float vf[VEC];
-            Elem<T>::unpack(vr[i], vf);
+            const int it = it0 + i * iter_stride;
+            if (it < n_iter) {                                   // wave-uniform
+                const int r = row_begin + it * RPW + grp;
+                const bool ok = r < row_end;
+                const float p = ok ? fast_exp2(z[i] - m_new) : 0.f;
+                sm.l += p;
+                float vf[VEC];
+                Elem<T>::unpack(vr[i], vf);
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) sm.acc[e] = fmaf(p, vf[e], sm.acc[e]);
-            if (ZBUF) { if (ok[i] && sub == 0) zbuf[r] = z[i]; }
-            if (MASS) {
-                sm.tot += (r >= vis_start) ? p : 0.f;
-                sm.far += (r >= vis_start && r <= far_last) ? p : 0.f;
+                for (int e = 0; e < VEC; ++e) sm.acc[e] = fmaf(p, vf[e], sm.acc[e]);
+                if (ZBUF) { if (ok && lane_off == 0) zbuf[r] = z[i]; }
+                if (MASS) {
+                    sm.tot += (r >= vis_start) ? p : 0.f;
+                    sm.far += (r >= vis_start && r <= far_last) ? p : 0.f;
+                }
             }
         }
         sm.m = m_new;
+    };
+
+    int it = first_iter;
+    if (it >= n_iter) return;
+    if (!PF) {                  // one buffer: issue a chunk, wait, compute
+        uint4 k1[CH], v1[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) { k1[i] = v1[i] = make_uint4(0, 0, 0, 0); }
+        for (; it < n_iter; it += chunk_iters) {
+            load(it, k1, v1);
+            compute(it, k1, v1);
+        }
+        return;
+    }
+    uint4 ka[CH], va[CH], kb[CH], vb[CH];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) { ka[i] = va[i] = kb[i] = vb[i] = make_uint4(0, 0, 0, 0); }
+    load(it, ka, va);
+    for (;;) {
+        int nxt = it + chunk_iters;
+        if (nxt < n_iter) load(nxt, kb, vb);
+        compute(it, ka, va);
+        if (nxt >= n_iter) break;
+        it = nxt;
+        nxt = it + chunk_iters;
+        if (nxt < n_iter) load(nxt, ka, va);
+        compute(it, kb, vb);
+        if (nxt >= n_iter) break;
+        it = nxt;
     }
 }
 
@@ -209,21 +286,24 @@ struct UnitRef {
     int32_t *pos;     // semantic only: [M+C]
 };
 
-static __device__ __forceinline__ UnitRef unit_ref(const Geom &g, int layer, int b, int h) {
+// ld: the layer's entry of the launch's LaunchMeta (kernel-argument memory, scalar loads)
+static __device__ __forceinline__ UnitRef unit_ref(const Geom &g, const LayerDesc &ld, int b, int h) {
     UnitRef u;
-    const uint32_t info = g.hinfo[layer * g.H + h];
-    const LayerMeta lm = g.lmeta[layer];
-    const uint32_t hl = info & ~HEAD_SEM_BIT;
-    u.sem = (info & HEAD_SEM_BIT) != 0;
+    const uint64_t m0 = ld.sem_mask[0], m1 = ld.sem_mask[1];
+    const uint64_t word = h < 64 ? m0 : m1;
+    const uint64_t below = (1ull << (h & 63)) - 1ull;
+    u.sem = ((word >> (h & 63)) & 1ull) != 0;
+    // semantic heads with a lower index than h
+    const int sem_below = h < 64 ? __popcll(m0 & below) : __popcll(m0) + __popcll(m1 & below);
     if (u.sem) {
-        const size_t idx = (size_t)b * (size_t)lm.n_se + hl;
-        u.K = g.base + lm.off_se + idx * (size_t)g.unit_se_bytes;
+        const size_t idx = (size_t)b * (size_t)ld.n_se + (size_t)sem_below;
+        u.K = g.base + ld.off_se + idx * (size_t)g.unit_se_bytes;
         u.V = u.K + (size_t)(g.M + g.C) * (size_t)g.row_bytes;
-        u.score = reinterpret_cast<float *>(g.base + lm.off_score) + idx * (size_t)(g.M + g.C);
-        u.pos = reinterpret_cast<int32_t *>(g.base + lm.off_pos) + idx * (size_t)(g.M + g.C);
+        u.score = reinterpret_cast<float *>(g.base + ld.off_score) + idx * (size_t)(g.M + g.C);
+        u.pos = reinterpret_cast<int32_t *>(g.base + ld.off_pos) + idx * (size_t)(g.M + g.C);
     } else {
-        const size_t idx = (size_t)b * (size_t)lm.n_sp + hl;
-        u.K = g.base + lm.off_sp + idx * (size_t)g.unit_sp_bytes;
+        const size_t idx = (size_t)b * (size_t)ld.n_sp + (size_t)(h - sem_below);
+        u.K = g.base + ld.off_sp + idx * (size_t)g.unit_sp_bytes;
         u.V = u.K + (size_t)(g.S + g.W) * (size_t)g.row_bytes;
         u.score = nullptr;
         u.pos = nullptr;

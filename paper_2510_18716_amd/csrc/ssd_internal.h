@@ -12,25 +12,30 @@
 
 namespace ssd {
 
-// ---- device-resident layout tables (uploaded once per cache) ---------------
+// ---- layout description handed to kernels by value (kernel arguments) -------
+//
+// Everything a wave needs to find its unit arrives in the kernel-argument segment, so address
+// computation is scalar arithmetic and the first K/V loads of a wave depend on no earlier load.
 
-struct LayerMeta {
-    uint64_t off_sp;     // byte offset of the spatial heads' K/V units of this layer
-    uint64_t off_se;     // byte offset of the semantic heads' K/V units
-    uint64_t off_score;  // float [B, Hm_l, M+C]
-    uint64_t off_pos;    // int32 [B, Hm_l, M+C]
-    int32_t n_sp;        // Hs_l
-    int32_t n_se;        // Hm_l
+static constexpr int LMAX = 32;   // layers one launch can cover
+
+struct LayerDesc {
+    uint64_t off_sp;        // byte offset of the spatial heads' K/V units of this layer
+    uint64_t off_se;        // byte offset of the semantic heads' K/V units
+    uint64_t off_score;     // float [B, Hm_l, M+C]
+    uint64_t off_pos;       // int32 [B, Hm_l, M+C]
+    uint64_t sem_mask[2];   // bit h set = head h of this layer is a semantic head (H <= 128)
+    int32_t n_sp;           // Hs_l
+    int32_t n_se;           // Hm_l
 };
 
-// head_info[l*H + h]: bit 31 = head is semantic, bits 0..30 = index among the heads of its type in layer l
-static constexpr uint32_t HEAD_SEM_BIT = 0x80000000u;
+struct LaunchMeta {
+    LayerDesc layer[LMAX];
+};
 
-// Geometry handed to every kernel by value.
+// Geometry common to all layers.
 struct Geom {
     char *base;               // device memory of the cache
-    const LayerMeta *lmeta;   // [L]
-    const uint32_t *hinfo;    // [L*H]
     int32_t B, H, S, W, M, C;
     int32_t row_bytes;        // d * element size
     uint32_t unit_sp_bytes;   // 2 * (S+W) * row_bytes : K plane then V plane
@@ -60,15 +65,11 @@ struct ssd_cache {
     float scale;
     int esize;
     std::vector<uint8_t> head_type;           // [L*H]
-    std::vector<ssd::LayerMeta> lmeta;        // host copy of the device tables
-    std::vector<uint32_t> hinfo;
+    std::vector<ssd::LayerDesc> ldesc;        // [L]
     std::vector<ssd::LayerState> st;          // [L]
     char *dev;
     size_t bytes;
-    size_t meta_bytes;                        // size of the table region at the start of dev
-    bool meta_uploaded;
     bool launch_enabled;
-    int n_sp_total, n_se_total;               // heads of each type over all layers
 };
 
 namespace ssd {
@@ -80,12 +81,17 @@ void clear_error();
 
 // host helpers implemented in ssd_cache.hip
 int check_layers(const ssd_cache *c, int lb, int le);
-int ensure_meta(ssd_cache *c, hipStream_t s);       // uploads the tables on first use
 Geom make_geom(const ssd_cache *c);
+void fill_launch_meta(const ssd_cache *c, int lb, int le, LaunchMeta *out);   // le - lb <= LMAX
 Segs spatial_segs(const ssd_cache *c, const LayerState &st);
 Segs semantic_segs(const ssd_cache *c, const LayerState &st);
-// first layer index > lb (and <= le) whose state differs from layer lb's
+// Same, but leaving out slot `skip` (the slot a fused append is about to write).
+Segs spatial_segs_without(const ssd_cache *c, const LayerState &st_after_append, int skip);
+// end of the run of layers starting at lb that share layer lb's state, at most LMAX long
 int same_state_run(const ssd_cache *c, int lb, int le);
+
+// implemented in ssd_compress.hip
+int launch_compress_inplace(const ssd_cache *cache, int lb, int le, const LayerState &st, hipStream_t s);
 
 static inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 

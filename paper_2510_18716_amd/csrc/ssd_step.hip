@@ -1,0 +1,359 @@
+// ssd_decode_attn and ssd_decode_step: single-token attention over the compressed cache, the
+// running-score update of semantic heads (Algorithm 1: "AttentionScores",
+// "AggregateAttentionScores"), and -- in the fused entry point -- the append before it and the
+// compression after it, all by the one workgroup that owns the (layer, sequence, head) unit.
+//
+// One wave64 per unit, a few units per workgroup.  A unit is small (S+W or m+c rows, ~33 KB at
+// W = M = 64, d = 128, bf16) and contiguous in HBM, so the kernel is a pure stream: every byte is
+// read once, straight into registers (nothing is reused, so there is nothing for LDS staging to
+// serve), and a launch exposes thousands of independent units to cover HBM latency.  Spatial and
+// semantic units share one launch; they differ only in where their valid rows are.  Because one
+// wave owns a unit from the append to the selection, no step needs a workgroup barrier or an atomic.
+//
+// Roofline: HBM.  Algorithmic bytes per unit and step = rows * 2 * d * e (K and V) + 2 * d * e
+// (q in, out) + 8 * rows for a semantic unit's score read-modify-write.
+#include "ssd_select.h"
+
+namespace ssd {
+
+struct StepArgs {
+    Geom g;
+    LaunchMeta lm;
+    const char *q;
+    char *out;
+    const char *k_new;   // fused append only
+    const char *v_new;
+    int layer_off;       // index of the launch's first layer inside q / out / k_new / v_new
+    Segs sp, se;         // rows streamed from the cache (fused append: without the new token's slot)
+    int new_slot_sp;     // fused append: destination slots and position of the new token
+    int new_slot_se;
+    int new_pos;
+    float qscale;        // softmax scale * log2(e)
+    int accumulate;
+    int zcap;            // floats of LDS per wave for the logits of a semantic unit
+    int wave_lds;        // bytes of LDS per wave (logits + selection scratch)
+    int do_compress;     // run the selection after the attention (semantic units)
+    int m, c, base, R;   // row-buffer state the selection works on (c counts a fused new token)
+    int lpr;
+    int probe;           // SSD_PROBE builds only
+};
+
+// One wave per unit, WPB units (consecutive heads of one sequence and layer) per workgroup;
+// grid = (ceil(H / WPB), B, layers of the launch).  Nothing below needs a workgroup barrier.
+template <typename T, int D, int CH, int WPB, bool FUSED>
+__global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
+    constexpr int VEC = Elem<T>::VEC;
+    constexpr int LPR = D / VEC;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: everything per-unit stays uniform
+    const int lane = threadIdx.x & 63;
+    const int sub = lane % LPR;
+    const int h = blockIdx.x * WPB + w;
+    if (h >= a.g.H) return;
+    const int lrel = blockIdx.z;
+    const int rem = blockIdx.y * a.g.H + h;
+    const UnitRef u = unit_ref(a.g, a.lm.layer[lrel], blockIdx.y, h);
+    const Segs &sg = u.sem ? a.se : a.sp;
+    const size_t qoff = ((size_t)(a.layer_off + lrel) * (size_t)(a.g.B * a.g.H) + rem) * (size_t)a.g.row_bytes + (size_t)sub * 16u;
+    unsigned char *region = lds_raw + (size_t)w * a.wave_lds;
+    float *zbuf = reinterpret_cast<float *>(region);                    // [zcap]
+    unsigned char *sel = region + (size_t)a.zcap * 4;                   // selection scratch
+
+    const typename Elem<T>::Q q = Elem<T>::load_q(*reinterpret_cast<const uint4 *>(a.q + qoff));
+    Softmax<VEC> sm;
+    sm.init();
+    const bool want_z = u.sem && a.accumulate;
+
+    // Everything the tail of this wave will need is requested now, ahead of the K/V stream, so that no
+    // memory round trip is left exposed after the last row: the new token's fragments (fused append) and
+    // the running scores / positions of the first 128 rows (one or two per lane).
+    const bool compress = a.do_compress != 0;
+    const bool tail = u.sem && (a.accumulate || compress || FUSED);
+    uint4 new_k = make_uint4(0, 0, 0, 0), new_v = make_uint4(0, 0, 0, 0);
+    if (FUSED && lane < LPR) {
+        new_k = *reinterpret_cast<const uint4 *>(a.k_new + qoff);
+        new_v = *reinterpret_cast<const uint4 *>(a.v_new + qoff);
+    }
+    float pre_score[2] = {0.f, 0.f};
+    int pre_pos[2] = {0, 0};
+    if (tail) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int r = lane + 64 * k;
+            if (r < sg.total) {
+                const int slot = seg_slot(sg, r);
+                pre_score[k] = u.score[slot];
+                if (compress) pre_pos[k] = u.pos[slot];
+            }
+        }
+    }
+
+#ifdef SSD_PROBE
+    if (a.probe >= 2) { sm.l = 1.f; } else
+#endif
+    if (want_z)
+        stream_rows<T, D, CH, true, false>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, zbuf, 0, 0, a.probe);
+    else
+        stream_rows<T, D, CH, false, false>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, nullptr, 0, 0, a.probe);
+    if (FUSED) {
+        // The new token: stored into its slot and, from the same registers, folded into lane group 0's
+        // softmax as one more row (index sg.total).
+        const int slot = u.sem ? a.new_slot_se : a.new_slot_sp;
+        if (lane < LPR) {
+            const size_t off = (size_t)slot * (size_t)a.g.row_bytes + (size_t)sub * 16u;
+            *reinterpret_cast<uint4 *>(u.K + off) = new_k;
+            *reinterpret_cast<uint4 *>(u.V + off) = new_v;
+        }
+        const float z = group_sum<LPR>(Elem<T>::dot(q, new_k)) * a.qscale;
+        if (lane < LPR) {
+            const float m_new = fmaxf(sm.m, z);
+            const float alpha = fast_exp2(sm.m - m_new);
+            const float p = fast_exp2(z - m_new);
+            float vf[VEC];
+            Elem<T>::unpack(new_v, vf);
+            sm.l = sm.l * alpha + p;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) sm.acc[e] = fmaf(p, vf[e], sm.acc[e] * alpha);
+            sm.m = m_new;
+            if (want_z && lane == 0) zbuf[sg.total] = z;
+        }
+    }
+    merge_groups<VEC, LPR, false>(sm);
+    const float m_all = sm.m;
+    const float inv_l = sm.l > 0.f ? 1.0f / sm.l : 0.f;
+#ifdef SSD_PROBE
+    if (a.probe >= 3) return;
+#endif
+    if (lane < LPR) {
+        float o[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) o[e] = sm.acc[e] * inv_l;
+        *reinterpret_cast<uint4 *>(a.out + qoff) = Elem<T>::pack(o);
+    }
+
+    if (!tail) return;
+    wave_sync();                                          // the logits written by the group leaders
+    const int M = a.g.M, C = a.g.C;
+    const int n_old = a.c - a.R;                          // buffered tokens that become candidates
+    const int n_cand = a.m + n_old;
+    const int n_evict = n_cand - M;                       // <= 0: everything is kept
+    unsigned long long *keys = reinterpret_cast<unsigned long long *>(sel);
+    unsigned long long min_key = ~0ull;
+    const int total = sg.total + (FUSED ? 1 : 0);
+    for (int r = lane, k = 0; r < total; r += 64, ++k) {
+        const bool is_new = FUSED && r == sg.total;
+        const int slot = is_new ? a.new_slot_se : seg_slot(sg, r);
+        const float p = a.accumulate ? fast_exp2(zbuf[r] - m_all) * inv_l : 0.f;
+        const float s_old = is_new ? 0.f : (k == 0 ? pre_score[0] : k == 1 ? pre_score[1] : u.score[slot]);
+        const float s = s_old + p;
+        if (a.accumulate || is_new) u.score[slot] = s;
+        int pos;
+        if (is_new) { pos = a.new_pos; u.pos[slot] = pos; }
+        else pos = !compress ? 0 : (k == 0 ? pre_pos[0] : k == 1 ? pre_pos[1] : u.pos[slot]);
+        if (compress && r < n_cand) {
+            const unsigned long long key = make_key(s, pos);
+            keys[r] = key;
+            min_key = key < min_key ? key : min_key;
+        }
+    }
+    if (!compress) return;
+    wave_sync();
+    if (n_evict >= 2) {                                   // general case: rank every candidate
+        select_and_move<64, true>(a.g, u, sel, n_cand, a.m, n_old, a.base, a.lpr, lane);
+        return;
+    }
+    // At most one eviction (always the case when compressing after every token): the promoted buffered
+    // tokens and the slots they go to follow from the index of the single evicted candidate.
+    int e_idx = -1;                                       // evicted candidate, -1 if none
+    if (n_evict == 1) {
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const unsigned long long o = __shfl_xor(min_key, off);
+            min_key = o < min_key ? o : min_key;
+        }
+        int *e_store = reinterpret_cast<int *>(keys + n_cand);
+        for (int r = lane; r < n_cand; r += 64)
+            if (keys[r] == min_key) *e_store = r;
+        wave_sync();
+        e_idx = *e_store;
+    }
+    const bool ev_heavy = e_idx >= 0 && e_idx < a.m;
+    const bool ev_staged = e_idx >= a.m;
+    const int n_move = n_old - (ev_staged ? 1 : 0);
+    const int frag_per_tok = 2 * a.lpr;
+    // k-th promoted candidate (oldest first) and k-th free heavy slot
+    auto src_idx = [&](int k) { return a.m + k + ((ev_staged && k >= e_idx - a.m) ? 1 : 0); };
+    auto dst_slot = [&](int k) { return ev_heavy ? (k == 0 ? e_idx : a.m + k - 1) : a.m + k; };
+    for (int t = lane; t < n_move * frag_per_tok; t += 64) {
+        const int k = t / frag_per_tok;
+        const int f = t % frag_per_tok;
+        const int kv = f / a.lpr, fs = f % a.lpr;
+        char *plane = kv ? u.V : u.K;
+        const int from = M + (a.base + (src_idx(k) - a.m)) % C;
+        const uint4 v = *reinterpret_cast<const uint4 *>(plane + (size_t)from * a.g.row_bytes + (size_t)fs * 16u);
+        *reinterpret_cast<uint4 *>(plane + (size_t)dst_slot(k) * a.g.row_bytes + (size_t)fs * 16u) = v;
+    }
+    for (int k = lane; k < n_move; k += 64) {
+        const unsigned long long key = keys[src_idx(k)];
+        u.pos[dst_slot(k)] = key_pos(key);
+        u.score[dst_slot(k)] = key_score(key);
+    }
+}
+
+struct Tuning {
+    int ch;      // wave-wide loads of K (and of V) per chunk; two chunks are in flight per wave (0 = by launch size)
+    int wpb;     // units (waves) per workgroup
+};
+
+static int g_probe = 0;
+static constexpr Tuning DEFAULT_TUNE = {0, 4};
+static Tuning g_tune = DEFAULT_TUNE;
+
+// Largest candidate count the fused entry point ranks with a single wave; beyond it the stand-alone
+// compression kernel (a whole workgroup per head) runs after the attention.
+static constexpr int FUSED_SELECT_MAX = 1024;
+
+template <typename T, int D, int CH, int WPB>
+static void launch_one(const StepArgs &a, dim3 blocks, size_t lds, bool fused, hipStream_t s) {
+    if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true>), blocks, dim3(WPB * 64), lds, s, a);
+    else hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, false>), blocks, dim3(WPB * 64), lds, s, a);
+}
+
+template <typename T, int D>
+static hipError_t launch_step(StepArgs &a, int H, int B, int layers, bool fused, int M, hipStream_t s) {
+    const int n_old = a.c - a.R, n_cand = a.m + n_old;
+    // Few units (one layer of a modest batch): every wave is resident at once and shallow queues finish
+    // sooner; many units: waves come and go, deeper per-wave queues keep HBM busier.
+    int ch = g_tune.ch ? g_tune.ch : ((long long)H * B * layers <= 16384 ? 2 : 4);
+    int wpb = g_tune.wpb;
+    a.wave_lds = (int)(((size_t)a.zcap * 4 + (a.do_compress ? select_lds_bytes(M, n_cand, n_old) + 16 : 0) + 15) / 16 * 16);
+    while (wpb > 1 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;
+    const size_t lds = (size_t)wpb * a.wave_lds;
+    const dim3 blocks((unsigned)((H + wpb - 1) / wpb), (unsigned)B, (unsigned)layers);
+#define SSD_CASE(CH_, WPB_) if (ch == CH_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_>(a, blocks, lds, fused, s); return hipGetLastError(); }
+    if constexpr (sizeof(T) == 2 && D == 128) {       // the shape the sweeps are run on has every variant
+        SSD_CASE(1, 1) SSD_CASE(2, 1) SSD_CASE(4, 1)
+        SSD_CASE(1, 2) SSD_CASE(2, 2) SSD_CASE(4, 2)
+        SSD_CASE(1, 4) SSD_CASE(2, 4) SSD_CASE(4, 4)
+    } else {
+        if (ch == 1) ch = 2;
+        SSD_CASE(2, 1) SSD_CASE(4, 1) SSD_CASE(2, 2) SSD_CASE(4, 2) SSD_CASE(2, 4) SSD_CASE(4, 4)
+    }
+#undef SSD_CASE
+    return hipErrorInvalidValue;
+}
+
+// Shared by ssd_decode_attn (k_new == NULL, compress == 0) and ssd_decode_step.
+static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new, const void *v_new,
+                    void *out, int accumulate, int compress, void *stream, const char *what) {
+    const ssd_config &cf = cache->cfg;
+    const bool fused = k_new != nullptr;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int lb = layer_begin; lb < layer_end;) {
+        const int le = same_state_run(cache, lb, layer_end);
+        const LayerState before = cache->st[lb];
+        const bool has_se = cache->ldesc[lb].n_se > 0;
+        // all layers of a run share their counters; whether a layer has semantic heads may differ, and the
+        // row-buffer counter only moves in layers that have them -- such layers never share a run for long
+        LayerState at = before;                      // state the attention sees
+        if (fused) { at.n += 1; if (has_se) at.c += 1; }
+        const int n_old = at.c - cf.recent;
+        const bool do_compress = compress && has_se && n_old > 0;
+        const bool in_kernel = do_compress && at.m + n_old <= FUSED_SELECT_MAX;
+        if (cache->launch_enabled) {
+            StepArgs a;
+            a.g = make_geom(cache);
+            fill_launch_meta(cache, lb, le, &a.lm);
+            a.q = static_cast<const char *>(q);
+            a.out = static_cast<char *>(out);
+            a.k_new = static_cast<const char *>(k_new);
+            a.v_new = static_cast<const char *>(v_new);
+            a.layer_off = lb - layer_begin;
+            a.new_pos = before.n;
+            a.new_slot_sp = before.n < cf.n_init_sink ? before.n : cf.n_init_sink + (before.n - cf.n_init_sink) % cf.window;
+            a.new_slot_se = cf.budget + (before.base + before.c) % cf.stage_cap;
+            if (fused) {
+                a.sp = spatial_segs_without(cache, at, a.new_slot_sp);
+                a.se = semantic_segs(cache, before);
+            } else {
+                a.sp = spatial_segs(cache, at);
+                a.se = semantic_segs(cache, at);
+            }
+            a.qscale = cache->scale * LOG2E;
+            a.accumulate = accumulate ? 1 : 0;
+            a.zcap = ((a.se.total + 1 + 63) / 64) * 64;
+            a.do_compress = in_kernel ? 1 : 0;
+            a.m = at.m; a.c = at.c; a.base = at.base; a.R = cf.recent;
+            a.lpr = a.g.row_bytes / 16;
+            a.probe = g_probe;
+            hipError_t e;
+            if (cf.dtype == SSD_BF16)
+                e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(a, cf.n_heads, cf.n_seqs, le - lb, fused, cf.budget, s)
+                                       : launch_step<bf16_t, 64>(a, cf.n_heads, cf.n_seqs, le - lb, fused, cf.budget, s);
+            else
+                e = cf.head_dim == 128 ? launch_step<float, 128>(a, cf.n_heads, cf.n_seqs, le - lb, fused, cf.budget, s)
+                                       : launch_step<float, 64>(a, cf.n_heads, cf.n_seqs, le - lb, fused, cf.budget, s);
+            if (e != hipSuccess) return hip_fail(e, what);
+            if (do_compress && !in_kernel) {
+                const int rc = launch_compress_inplace(cache, lb, le, at, s);
+                if (rc != SSD_OK) return rc;
+            }
+        }
+        for (int l = lb; l < le; ++l) {
+            LayerState &x = cache->st[l];
+            if (fused) { x.n += 1; if (cache->ldesc[l].n_se > 0) x.c += 1; }
+            if (compress && cache->ldesc[l].n_se > 0 && x.c - cf.recent > 0) {
+                const int old = x.c - cf.recent;
+                const int tot = x.m + old;
+                x.m = tot < cf.budget ? tot : cf.budget;
+                x.base = (x.base + old) % cf.stage_cap;
+                x.c = cf.recent;
+            }
+        }
+        lb = le;
+    }
+    return SSD_OK;
+}
+
+}  // namespace ssd
+
+using namespace ssd;
+
+// Launch-shape knobs for benchmarking sweeps (not part of the documented ABI): wave-wide loads per
+// chunk (1, 2, 4; 0 = chosen from the launch size) and units per workgroup (1, 2, 4); (0, 0) restores
+// the default.
+extern "C" int ssd_tune_attend(int ch, int wpb, int probe) {
+    g_probe = probe;
+    if (ch == 0 && wpb == 0) { g_tune = DEFAULT_TUNE; return SSD_OK; }
+    if ((ch != 0 && ch != 1 && ch != 2 && ch != 4) || (wpb != 1 && wpb != 2 && wpb != 4)) return SSD_ERR_INVALID_ARG;
+    g_tune.ch = ch; g_tune.wpb = wpb;
+    return SSD_OK;
+}
+
+extern "C" int ssd_decode_attn(ssd_cache *cache, int layer_begin, int layer_end, const void *q, void *out,
+                               int accumulate_scores, void *stream) {
+    clear_error();
+    int rc = check_layers(cache, layer_begin, layer_end);
+    if (rc != SSD_OK) return rc;
+    if (!q || !out) return fail(SSD_ERR_INVALID_ARG, "q or out is NULL");
+    if (!aligned(q, 16) || !aligned(out, 16)) return fail(SSD_ERR_INVALID_ARG, "q / out must be 16-byte aligned");
+    for (int l = layer_begin; l < layer_end; ++l)
+        if (cache->st[l].n < 1) return fail(SSD_ERR_ORDER, "layer %d holds no token: call ssd_append_token first", l);
+    return run_step(cache, layer_begin, layer_end, q, nullptr, nullptr, out, accumulate_scores, 0, stream, "attention launch");
+}
+
+extern "C" int ssd_decode_step(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new,
+                               const void *v_new, void *out, int accumulate_scores, int compress, void *stream) {
+    clear_error();
+    int rc = check_layers(cache, layer_begin, layer_end);
+    if (rc != SSD_OK) return rc;
+    if (!q || !out || !k_new || !v_new) return fail(SSD_ERR_INVALID_ARG, "q, k_new, v_new or out is NULL");
+    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(k_new, 16) || !aligned(v_new, 16))
+        return fail(SSD_ERR_INVALID_ARG, "q / k_new / v_new / out must be 16-byte aligned");
+    for (int l = layer_begin; l < layer_end; ++l)
+        if (cache->ldesc[l].n_se > 0 && cache->st[l].c >= cache->cfg.stage_cap)
+            return fail(SSD_ERR_STAGE_OVERFLOW, "row buffer overflow: layer %d already buffers %d tokens (C=%d); call ssd_compress_kv",
+                        l, cache->st[l].c, cache->cfg.stage_cap);
+    return run_step(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, stream, "decode step launch");
+}

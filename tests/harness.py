@@ -59,7 +59,7 @@ def sample_units(wl: workload.Workload, ht: np.ndarray, k: int, seed: int = 0) -
 def gpu_decode(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.ndarray, schedule: np.ndarray,
                units: Sequence[Tuple[int, int, int]], layers_per_call: Optional[int] = None,
                export_steps: Optional[Sequence[int]] = None, p_end: Optional[int] = None,
-               cache: Optional[ssd.Cache] = None, p_begin: int = 0, accumulate: bool = True):
+               cache: Optional[ssd.Cache] = None, p_begin: int = 0, accumulate: bool = True, fused: bool = False):
     """Decode positions [p_begin, p_end) on the GPU.  Returns
          outs   float32 numpy [steps, len(units), d]  outputs of the sampled units
          exports {step: {"pre": (pos, score) or None, "post": (pos, score)}} numpy [len(layers), B, H, slots]
@@ -87,15 +87,21 @@ def gpu_decode(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.ndar
 
     for p in range(p_begin, p_end):
         q, k, v = data["q"][p], data["k"][p], data["v"][p]
+        # the fused entry point does append + attend + compress in one launch (no look at the tables between
+        # attention and compression is possible then: "pre" exports exist only on the three-call path)
+        fuse_now = fused
         for lb in range(0, wl.L, lpc):
             le = min(wl.L, lb + lpc)
-            ssd.ssd_append_token(cache, lb, le, k[lb:le], v[lb:le])
-            ssd.ssd_decode_attn(cache, lb, le, q[lb:le], out[lb:le], accumulate)
+            if fuse_now:
+                ssd.ssd_decode_step(cache, lb, le, q[lb:le], k[lb:le], v[lb:le], out[lb:le], accumulate, bool(schedule[p]))
+            else:
+                ssd.ssd_append_token(cache, lb, le, k[lb:le], v[lb:le])
+                ssd.ssd_decode_attn(cache, lb, le, q[lb:le], out[lb:le], accumulate)
         outs[p - p_begin] = out.view(-1, wl.d)[idx].float()
         rec = {"pre": None, "post": None}
-        if p in export_steps and schedule[p]:
+        if p in export_steps and schedule[p] and not fuse_now:
             rec["pre"] = export_layers()
-        if schedule[p]:
+        if schedule[p] and not fuse_now:
             for lb in range(0, wl.L, lpc):
                 le = min(wl.L, lb + lpc)
                 ssd.ssd_compress_kv(cache, lb, le)

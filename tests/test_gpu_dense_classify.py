@@ -26,7 +26,7 @@ def _dense_case(B, H, d, dtype, n_cap, n, splits, seed, vis_start=0, w=32):
     assert ssd.lib.ssd_tune_dense(splits) == 0
     try:
         ssd.ssd_dense_decode_attn(q.cuda(), K.cuda(), V.cuda(), out, B, H, d, dtype, n_cap, n, 0.0,
-                                  far[:, :, 1:], tot[:, :, 1:], 3, vis_start, w, ws)
+                                  far[:, :, 1:].data_ptr(), tot[:, :, 1:].data_ptr(), 3, vis_start, w, ws)
         torch.cuda.synchronize()
     finally:
         ssd.lib.ssd_tune_dense(0)
@@ -77,7 +77,7 @@ def test_classification_recovers_planted_head_types():
         n = wl.n0 + t
         for l in range(L):
             ssd.ssd_dense_decode_attn(dev["q"][n - 1, l], K[l], V[l], out, P, H, wl.d, wl.dtype, wl.n_total, n, 0.0,
-                                      far[l, :, :, t - 1:], tot[l, :, :, t - 1:], T, wl.n0, w, ws)
+                                      far[l, :, :, t - 1:].data_ptr(), tot[l, :, :, t - 1:].data_ptr(), T, wl.n0, w, ws)
     s_gpu = torch.zeros((L, H), device="cuda")
     ty_gpu = torch.zeros((L, H), dtype=torch.uint8, device="cuda")
     tau = 0.3

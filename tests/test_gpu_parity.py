@@ -20,11 +20,11 @@ def _to_cuda(data):
     return {k: v.cuda() for k, v in data.items()}
 
 
-def _full_compare(wl, ht=None, lpc=None, k_units=10 ** 9, export_every=1, seed=0, device_gen=False):
+def _full_compare(wl, ht=None, lpc=None, k_units=10 ** 9, export_every=1, seed=0, device_gen=False, fused=False):
     ht = workload.head_map(wl) if ht is None else ht
     schedule = workload.compress_schedule(wl)
-    say("case", wl.name, wl.dtype, "L%d B%d H%d d%d n0=%d N=%d W%d S%d M%d R%d C%d cadence%d lpc=%s" % (
-        wl.L, wl.B, wl.H, wl.d, wl.n0, wl.N, wl.W, wl.S, wl.M, wl.R, wl.C, wl.cadence, lpc))
+    say("case", wl.name, wl.dtype, "L%d B%d H%d d%d n0=%d N=%d W%d S%d M%d R%d C%d cadence%d lpc=%s fused=%s" % (
+        wl.L, wl.B, wl.H, wl.d, wl.n0, wl.N, wl.W, wl.S, wl.M, wl.R, wl.C, wl.cadence, lpc, fused))
     if device_gen:
         dev_data = workload.generate(wl, device="cuda", head_type=ht)
     else:
@@ -36,7 +36,7 @@ def _full_compare(wl, ht=None, lpc=None, k_units=10 ** 9, export_every=1, seed=0
     else:
         comp = [p for p in range(wl.n_total) if schedule[p]]
         steps = sorted(set(range(0, wl.n_total, export_every)) | {wl.n_total - 1} | set(comp[:: max(1, len(comp) // 8)]))
-    outs, exports, cache = gpu_decode(wl, dev_data, ht, schedule, units, layers_per_call=lpc, export_steps=steps)
+    outs, exports, cache = gpu_decode(wl, dev_data, ht, schedule, units, layers_per_call=lpc, export_steps=steps, fused=fused)
     say("  gpu decode done: %d units, %d exported steps" % (len(units), len(exports)))
     # sampled units back on the host: the oracle sees the very same bits
     layers = sorted(set(l for (l, _, _) in units))
@@ -69,49 +69,58 @@ def _full_compare(wl, ht=None, lpc=None, k_units=10 ** 9, export_every=1, seed=0
 
 # ------------------------------------------------------------------ tiny, every unit, every step ----
 
+FUSED = pytest.mark.parametrize("fused", [False, True], ids=["three-calls", "fused-step"])
+
+
+@FUSED
 @pytest.mark.parametrize("S,cadence", [(1, 1), (0, 1), (1, 8)])
-def test_config1_every_unit_every_step(S, cadence):
+def test_config1_every_unit_every_step(S, cadence, fused):
     wl = workload.config(1).replace(S=S, cadence=cadence, C=1 + cadence)
-    _full_compare(wl)
+    _full_compare(wl, fused=fused)
 
 
-def test_config1_plain_gaussian_inputs():
+@FUSED
+def test_config1_plain_gaussian_inputs(fused):
     # no planted structure: every retained row carries weight, so a wrong row shows in the output
     wl = workload.config(1).replace(plain=True, name="cfg1-plain")
-    _full_compare(wl)
+    _full_compare(wl, fused=fused)
 
 
+@FUSED
 @pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128), ("f32", 64)])
-def test_small_shapes_all_dtypes(dtype, d):
+def test_small_shapes_all_dtypes(dtype, d, fused):
     wl = workload.Workload("small-%s-%d" % (dtype, d), L=3, prompts=2, H=6, d=d, dtype=dtype, n0=9, grid_h=7,
                            grid_w=9, W=13, M=10, S=2, R=2, C=7, cadence=5, spatial_frac=0.5, seed=77,
                            plain=True)
-    _full_compare(wl)
-    _full_compare(wl.replace(name=wl.name + "-perlayer"), lpc=1)
+    _full_compare(wl, fused=fused)
+    _full_compare(wl.replace(name=wl.name + "-perlayer"), lpc=1, fused=fused)
 
 
-def test_ragged_sizes_and_long_row_buffer():
+@FUSED
+def test_ragged_sizes_and_long_row_buffer(fused):
     # row counts that are not multiples of the rows-per-load (4) or the chunk (16); a row buffer that wraps
     wl = workload.Workload("ragged", L=2, prompts=1, H=5, d=128, dtype="bf16", n0=3, grid_h=9, grid_w=11, W=67,
                            M=33, S=3, R=5, C=41, cadence=36, spatial_frac=0.4, seed=5, plain=True)
-    _full_compare(wl)
+    _full_compare(wl, fused=fused)
 
 
-def test_all_spatial_and_all_semantic_head_maps():
+@FUSED
+def test_all_spatial_and_all_semantic_head_maps(fused):
     # the two special cases the paper compares against: window + sink tokens only, heavy hitters only
     wl = workload.Workload("all-spatial", L=2, prompts=1, H=4, d=64, dtype="bf16", n0=4, grid_h=6, grid_w=6, W=8,
                            M=6, S=1, R=1, C=2, cadence=1, seed=9, plain=True)
-    _full_compare(wl, ht=np.zeros((2, 4), np.uint8))
-    _full_compare(wl.replace(name="all-semantic"), ht=np.ones((2, 4), np.uint8))
+    _full_compare(wl, ht=np.zeros((2, 4), np.uint8), fused=fused)
+    _full_compare(wl.replace(name="all-semantic"), ht=np.ones((2, 4), np.uint8), fused=fused)
     mixed = np.array([[0, 0, 0, 0], [1, 1, 1, 1]], np.uint8)      # head lists that differ per layer
-    _full_compare(wl.replace(name="layerwise-types"), ht=mixed)
+    _full_compare(wl.replace(name="layerwise-types"), ht=mixed, fused=fused)
 
 
-def test_degenerate_parameters():
+@FUSED
+def test_degenerate_parameters(fused):
     base = dict(L=1, prompts=1, H=4, d=64, dtype="f32", n0=2, grid_h=5, grid_w=5, seed=3, plain=True)
-    _full_compare(workload.Workload("W1-M1", W=1, M=1, S=0, R=1, C=2, cadence=1, **base))
-    _full_compare(workload.Workload("R0", W=2, M=3, S=1, R=0, C=1, cadence=1, **base))
-    _full_compare(workload.Workload("S-exceeds-n0", W=4, M=4, S=6, R=3, C=4, cadence=1, **base))
+    _full_compare(workload.Workload("W1-M1", W=1, M=1, S=0, R=1, C=2, cadence=1, **base), fused=fused)
+    _full_compare(workload.Workload("R0", W=2, M=3, S=1, R=0, C=1, cadence=1, **base), fused=fused)
+    _full_compare(workload.Workload("S-exceeds-n0", W=4, M=4, S=6, R=3, C=4, cadence=1, **base), fused=fused)
 
 
 def test_unbounded_window_and_budget_equal_dense_kernel():
@@ -133,19 +142,41 @@ def test_unbounded_window_and_budget_equal_dense_kernel():
 
 # ------------------------------------------------------------------ paper-shaped, full size ----------
 
-def test_config2_full_size_sampled_units():
+@FUSED
+def test_config2_full_size_sampled_units(fused):
     wl = workload.config(2)
-    _full_compare(wl, k_units=48, export_every=64, device_gen=True)
+    _full_compare(wl, k_units=48, export_every=64, device_gen=True, fused=fused)
 
 
-def test_config2_per_layer_launches():
+@FUSED
+def test_config2_per_layer_launches(fused):
     wl = workload.config(2).replace(name="cfg2-perlayer", L=4)
-    _full_compare(wl, lpc=1, k_units=24, export_every=96, device_gen=True)
+    _full_compare(wl, lpc=1, k_units=24, export_every=96, device_gen=True, fused=fused)
 
 
-def test_config4_high_resolution_row_buffer():
+@FUSED
+def test_config4_high_resolution_row_buffer(fused):
     wl = workload.config(4)
-    _full_compare(wl, k_units=32, export_every=256, device_gen=True)
+    _full_compare(wl, k_units=32, export_every=256, device_gen=True, fused=fused)
+
+
+def test_config3_headline_shape_per_layer_fused_sampled_units():
+    # the configuration and launch shape bench.py times: 7B-shaped, one fused launch per layer
+    wl = workload.config(3)
+    _full_compare(wl, lpc=1, k_units=64, export_every=128, device_gen=True, fused=True)
+
+
+@pytest.mark.parametrize("ch,wpu", [(1, 1), (2, 1), (4, 1), (1, 2), (2, 2), (4, 2), (1, 4), (2, 4), (4, 4)])
+def test_every_launch_shape_variant(ch, wpu):
+    # all kernel variants the tuning knobs can select must give the same results
+    wl = workload.Workload("variant", L=2, prompts=1, H=6, d=128, dtype="bf16", n0=7, grid_h=9, grid_w=10, W=37,
+                           M=21, S=2, R=2, C=9, cadence=6, seed=13, plain=True)
+    assert ssd.lib.ssd_tune_attend(ch, wpu, 0) == 0
+    try:
+        _full_compare(wl, fused=False)
+        _full_compare(wl, fused=True)
+    finally:
+        assert ssd.lib.ssd_tune_attend(0, 0, 0) == 0
 
 
 def test_determinism_same_inputs_same_bits():

@@ -190,3 +190,37 @@ def test_dense_and_classify_argument_checks():
     assert lib.ssd_classify_heads(None, FAKE, 1, 1, 1, 1, 0.5, FAKE, FAKE, None) == ssd.SSD_ERR_INVALID_ARG
     assert lib.ssd_classify_heads(FAKE, FAKE, 1, 0, 1, 1, 0.5, FAKE, FAKE, None) == ssd.SSD_ERR_INVALID_ARG
     assert lib.ssd_classify_heads(FAKE, FAKE, 1, 1, 1, 1, 0.5, None, None, None) == ssd.SSD_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_fused_step_counters_equal_the_three_calls(seed):
+    r = np.random.default_rng(50 + seed)
+    M, R = int(r.integers(1, 9)), int(r.integers(0, 4))
+    C_ = R + int(r.integers(1, 7))
+    cfg = make_config(3, 2, 4, 64, "f32", 5, 1, M, R, C_)
+    ht = np.array([[0, 0, 1, 1], [0, 0, 0, 0], [1, 1, 1, 1]], np.uint8)     # one layer has no row buffer
+    a = ssd.Cache(cfg, ht, device=None)
+    b = ssd.Cache(cfg, ht, device=None)
+    for step in range(50):
+        full = a.layer_state(0)[2] >= C_
+        comp = bool(r.random() < 0.5) or a.layer_state(0)[2] + 1 >= C_
+        if full:
+            with pytest.raises(ssd.SsdError) as e:
+                ssd.ssd_decode_step(a, 0, 3, FAKE, FAKE, FAKE, FAKE, True, comp)
+            assert e.value.code == ssd.SSD_ERR_STAGE_OVERFLOW
+            ssd.ssd_compress_kv(a, 0, 3); ssd.ssd_compress_kv(b, 0, 3)
+        ssd.ssd_decode_step(a, 0, 3, FAKE, FAKE, FAKE, FAKE, True, comp)
+        ssd.ssd_append_token(b, 0, 3, FAKE, FAKE)
+        ssd.ssd_decode_attn(b, 0, 3, FAKE, FAKE, True)
+        if comp:
+            ssd.ssd_compress_kv(b, 0, 3)
+        for l in range(3):
+            assert a.layer_state(l) == b.layer_state(l), (step, l)
+    assert a.layer_state(1)[1:] == (0, 0, 0)
+    for args in [(None, FAKE, FAKE, FAKE), (FAKE, None, FAKE, FAKE), (FAKE, FAKE, FAKE, None), (FAKE, FAKE + 8, FAKE, FAKE)]:
+        with pytest.raises(ssd.SsdError) as e:
+            ssd.ssd_decode_step(a, 0, 3, *args)
+        assert e.value.code == ssd.SSD_ERR_INVALID_ARG
+    with pytest.raises(ssd.SsdError) as e:
+        ssd.ssd_decode_step(a, 1, 4, FAKE, FAKE, FAKE, FAKE)
+    assert e.value.code == ssd.SSD_ERR_LAYER_RANGE

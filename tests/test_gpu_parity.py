@@ -190,3 +190,62 @@ def test_determinism_same_inputs_same_bits():
     np.testing.assert_array_equal(a, b)
     for k in (0, 1):
         np.testing.assert_array_equal(ea[wl.n_total - 1]["post"][k], eb[wl.n_total - 1]["post"][k])
+
+
+@pytest.mark.parametrize("frac,W,M", [(0.25, 32, 128), (0.5, 64, 64), (0.75, 128, 32)])
+def test_config5_large_batch_online_classification_then_decode(frac, W, M):
+    """Large-batch shape (B = 512, 32 heads) with the head types found online: a dense profiling run on a
+    16-sequence sub-batch feeds ssd_classify_heads, the resulting table drives the compressed decode of the
+    whole batch.  Two layers keep the test short; a per-layer launch has the full configuration's shape."""
+    import oracle as orc
+    wl = workload.config(5).replace(name="cfg5-%d-%d-%d" % (int(frac * 100), W, M), L=2, spatial_frac=frac, W=W, M=M)
+    planted = workload.head_map(wl)
+    say("case", wl.name, "B", wl.B)
+    data = workload.generate(wl, device="cuda", head_type=planted)
+    P, T, w = 16, wl.N, wl.w_metric
+    far = torch.zeros((wl.L, P, wl.H, T), device="cuda")
+    tot = torch.zeros_like(far)
+    outd = torch.empty((P, wl.H, wl.d), dtype=wl.torch_dtype, device="cuda")
+    ws = torch.empty(ssd.ssd_dense_workspace_bytes(P, wl.H, wl.d, wl.n_total), dtype=torch.uint8, device="cuda")
+    sub = {x: data[x][:, :, :P].contiguous() for x in "qkv"}
+    Kd = workload.dense_layout(sub["k"])
+    Vd = workload.dense_layout(sub["v"])
+    for t in range(1, T + 1):
+        n = wl.n0 + t
+        for l in range(wl.L):
+            ssd.ssd_dense_decode_attn(sub["q"][n - 1, l], Kd[l], Vd[l], outd, P, wl.H, wl.d, wl.dtype, wl.n_total, n, 0.0,
+                                      far[l, :, :, t - 1:].data_ptr(), tot[l, :, :, t - 1:].data_ptr(), T, wl.n0, w, ws)
+    s_gpu = torch.zeros((wl.L, wl.H), device="cuda")
+    ty_gpu = torch.zeros((wl.L, wl.H), dtype=torch.uint8, device="cuda")
+    ssd.ssd_classify_heads(far, tot, wl.L, P, wl.H, T, 0.5, s_gpu, ty_gpu)
+    torch.cuda.synchronize()
+    ht = ty_gpu.cpu().numpy()
+    np.testing.assert_array_equal(ht, planted)
+    far_h, tot_h = far.cpu().numpy(), tot.cpu().numpy()
+    s_ref, ty_ref = orc.classify(far_h, tot_h, 0.5)                 # the oracle's reduction on the same masses
+    np.testing.assert_array_equal(ty_ref, ht)
+    np.testing.assert_allclose(s_gpu.cpu().numpy(), s_ref, atol=1e-5, rtol=1e-4)
+    assert (np.abs(s_ref - 0.5) > 0.1).all()
+    r = np.random.default_rng(5)
+    for _ in range(12):                                             # the masses themselves, on sampled units
+        l, p, h = int(r.integers(wl.L)), int(r.integers(P)), int(r.integers(wl.H))
+        q_, K_, V_ = workload.unit_arrays(sub, l, p, h)
+        f_o, t_o = orc.profile_unit(q_, K_, V_, wl.n0, T, w, wl.scale)
+        np.testing.assert_allclose(far_h[l, p, h], f_o, atol=2e-5, rtol=2e-4)
+        np.testing.assert_allclose(tot_h[l, p, h], t_o, atol=2e-5, rtol=2e-4)
+    del Kd, Vd, sub
+    # compressed decode of the full batch with the classified table, fused per-layer launches
+    schedule = workload.compress_schedule(wl)
+    units = sample_units(wl, ht, 40, seed=2)
+    steps = sorted(set(range(0, wl.n_total, 160)) | {wl.n_total - 1})
+    outs, exports, _ = gpu_decode(wl, data, ht, schedule, units, layers_per_call=1, export_steps=steps, fused=True)
+    layers = sorted(set(l for (l, _, _) in units))
+    worst = 0.0
+    for ui, unit in enumerate(units):
+        l, b, h = unit
+        host = {x: data[x][:, l:l + 1, b:b + 1, h:h + 1].cpu() for x in "qkv"}
+        o_ref, hl, gl, _ = oracle_unit(wl, host, ht[l:l + 1, h:h + 1], schedule, (0, 0, 0))
+        div = compare_unit_sets(wl, ht, unit, layers.index(l), exports, hl, gl, schedule)
+        upto = wl.n_total if div is None else div + 1
+        worst = max(worst, check_outputs(outs[:upto, ui], o_ref[:upto], wl.dtype, "unit %s" % (unit,)))
+    say("  max abs output error %.3e" % worst)

@@ -80,7 +80,12 @@ typedef struct ssd_config {
     int32_t recent;        /* R >= 0: newest tokens a semantic head never evicts           */
     int32_t stage_cap;     /* C > R: row-buffer slots of a semantic head; M + C <= 4096    */
     float   softmax_scale; /* 0 selects 1/sqrt(d)                                          */
-    int32_t reserved[5];   /* must be 0                                                    */
+    int32_t spatial_row_buffer; /* 0: a spatial head keeps exactly its S sinks and the W newest tokens
+                                   (Algorithm 1).  1: Algorithm 2 -- it attends to the sinks, the W
+                                   newest tokens as of the last compression, and every token appended
+                                   since (the row buffer), so its window grows from W to W + C - R between
+                                   compressions; ssd_compress_kv re-cuts the window.  Requires S+W+C <= 65536 */
+    int32_t reserved[4];   /* must be 0                                                    */
 } ssd_config;
 
 /* Host-side descriptor of a cache: layout, per-layer head lists, token counters. */
@@ -113,6 +118,9 @@ int ssd_cache_reset(ssd_cache *cache);
  * use, c row-buffer slots in use, ring index of the oldest row-buffer slot }.
  */
 int ssd_cache_layer_state(const ssd_cache *cache, int layer, int32_t out4[4]);
+
+/* Token count of the layer at its last compression (the start of a spatial head's row buffer). */
+int ssd_cache_layer_window(const ssd_cache *cache, int layer, int32_t *n_at_last_compress);
 
 /*
  * Test hook: with enable == 0 every later call on this cache does all of its
@@ -171,7 +179,10 @@ int ssd_decode_attn(ssd_cache *cache, int layer_begin, int layer_end,
  * candidates with the highest accumulated score stay (ties: lower position
  * first; all stay if there are at most M), the rest are dropped with their
  * scores; the R newest tokens remain in the row buffer.  Spatial heads need
- * nothing.  A layer with at most R buffered tokens is left as it is.
+ * no data movement: under Algorithm 1 their ring evicts by itself, under
+ * Algorithm 2 (spatial_row_buffer) the call re-cuts their window to the W
+ * newest tokens.  A layer with at most R buffered tokens keeps its semantic
+ * heads as they are.
  *
  * Dense-source mode (K_src != NULL): rebuild the layers from a full cache
  * segment (the prefill branch of Algorithm 2).

@@ -61,6 +61,8 @@ _lib.ssd_oracle_unit_new.argtypes = [C.c_int] * 6
 _lib.ssd_oracle_unit_new.restype = _vp
 _lib.ssd_oracle_unit_free.argtypes = [_vp]
 _lib.ssd_oracle_unit_free.restype = None
+_lib.ssd_oracle_unit_set_buffered.argtypes = [_vp, C.c_int]
+_lib.ssd_oracle_unit_set_buffered.restype = None
 _lib.ssd_oracle_unit_append.argtypes = [_vp]
 _lib.ssd_oracle_unit_append.restype = C.c_int
 _lib.ssd_oracle_unit_n.argtypes = [_vp]
@@ -149,10 +151,14 @@ def top_m(score, pos, M):
 class Unit:
     """O4: the cache policy of one (layer, sequence, head) over dense K, V held by the caller."""
 
-    def __init__(self, is_semantic, W, S, M, R, C_):
+    def __init__(self, is_semantic, W, S, M, R, C_, buffered_spatial=False):
+        """buffered_spatial: a spatial head follows Algorithm 2 (window frozen at the last compression plus
+        the row buffer) instead of Algorithm 1 (exact sliding window)."""
         self.is_semantic = bool(is_semantic)
         self.W, self.S, self.M, self.R, self.C = int(W), int(S), int(M), int(R), int(C_)
         self._h = _lib.ssd_oracle_unit_new(int(self.is_semantic), self.W, self.S, self.M, self.R, self.C)
+        if buffered_spatial:
+            _lib.ssd_oracle_unit_set_buffered(self._h, 1)
 
     def __del__(self):
         if getattr(self, "_h", None):

@@ -23,7 +23,9 @@
  *   O4  the per-head cache policy of Algorithm 1 with the additions the text
  *       of Sec. 3.3 makes (initial sink token for spatial heads, reserved
  *       recent window R for semantic heads) and the deferred-compression
- *       cadence of Algorithm 2 (row buffer, overflow error).
+ *       cadence of Algorithm 2 (row buffer, overflow error), including
+ *       Algorithm 2's treatment of spatial heads (cached window as of the
+ *       last compression, plus the row buffer).
  *
  * Readings of points the paper leaves open (identical on the GPU side):
  *   - softmax scale is a caller-supplied number (1/sqrt(d) by default);
@@ -235,6 +237,9 @@ int ssd_oracle_top_m(const float *score, const int32_t *pos, int n, int M,
 typedef struct ssd_oracle_unit {
     int is_semantic;
     int W, S, M, R, C;
+    int buffered;        /* spatial head under Algorithm 2: window frozen at the last compression + row buffer */
+    int n_c;             /* buffered spatial head: token count at the last compression                        */
+    int n_buf;           /* buffered spatial head: tokens in the row buffer (same counting as a semantic head) */
     int n;               /* tokens appended so far; positions 0..n-1 */
     /* semantic heads only: retained positions with their running scores */
     int n_heavy;  int32_t *heavy_pos;  float *heavy_score;   /* cap M        */
@@ -282,6 +287,10 @@ static void staged_reserve(ssd_oracle_unit *u, int need)
  */
 int ssd_oracle_unit_append(ssd_oracle_unit *u)
 {
+    if (!u->is_semantic && u->buffered) {
+        if (u->n_buf >= u->C) return -1;
+        u->n_buf += 1;
+    }
     if (u->is_semantic) {
         if (u->n_staged >= u->C) return -1;
         u->staged_pos[u->n_staged] = u->n;
@@ -295,8 +304,16 @@ int ssd_oracle_unit_append(ssd_oracle_unit *u)
 int ssd_oracle_unit_n(const ssd_oracle_unit *u) { return u->n; }
 
 /*
+ * Algorithm 2 for spatial heads (off by default): the head attends to its cached entries -- the sink tokens
+ * and the W most recent tokens as of the last compression -- concatenated with the row buffer, i.e. every
+ * token appended since; a compression re-cuts the window ("Compress spatial cache (sink + recent)").
+ */
+void ssd_oracle_unit_set_buffered(ssd_oracle_unit *u, int on) { u->buffered = on; }
+
+/*
  * Retained positions in ascending order; returns the count.
- * Spatial: {0..min(S,n)-1} U {max(S, n-W)..n-1}.
+ * Spatial: {0..min(S,n)-1} U {max(S, n-W)..n-1}; under Algorithm 2 the window starts at max(S, n_c-W)
+ * with n_c the token count at the last compression.
  * Semantic: Heavy U Staged (every heavy position is older than every staged
  * one, and both lists are kept ascending).
  */
@@ -305,7 +322,7 @@ int ssd_oracle_unit_retained(const ssd_oracle_unit *u, int32_t *pos_out)
     int c = 0, p;
     if (!u->is_semantic) {
         int s_end = u->S < u->n ? u->S : u->n;
-        int w_begin = u->n - u->W;
+        int w_begin = (u->buffered ? u->n_c : u->n) - u->W;
         if (w_begin < u->S) w_begin = u->S;
         for (p = 0; p < s_end; ++p) pos_out[c++] = p;
         for (p = w_begin; p < u->n; ++p) pos_out[c++] = p;
@@ -318,7 +335,7 @@ int ssd_oracle_unit_retained(const ssd_oracle_unit *u, int32_t *pos_out)
 
 int ssd_oracle_unit_max_retained(const ssd_oracle_unit *u)
 {
-    return u->is_semantic ? u->M + u->staged_cap : u->S + u->W;
+    return u->is_semantic ? u->M + u->staged_cap : u->S + u->W + (u->buffered ? u->C : 0);
 }
 
 /*
@@ -362,7 +379,13 @@ int ssd_oracle_unit_compress(ssd_oracle_unit *u, double *gap_out)
     int n_old, n_cand, i, kept, keep_recent;
     float *cs; int32_t *cp, *keep;
     if (gap_out) *gap_out = -1.0;
-    if (!u->is_semantic) return 0;
+    if (!u->is_semantic) {
+        if (u->buffered) {          /* re-cut the window, empty the row buffer down to the R newest */
+            u->n_c = u->n;
+            if (u->n_buf > u->R) u->n_buf = u->R;
+        }
+        return 0;
+    }
     keep_recent = u->R < u->n_staged ? u->R : u->n_staged;
     n_old = u->n_staged - keep_recent;          /* staged tokens that become candidates */
     if (n_old <= 0) return u->n_heavy;
@@ -394,7 +417,11 @@ int ssd_oracle_unit_load_dense(ssd_oracle_unit *u, int n_src,
 {
     int i;
     u->n = n_src;
-    if (!u->is_semantic) return 0;
+    if (!u->is_semantic) {
+        u->n_c = n_src;
+        u->n_buf = u->R < n_src ? u->R : n_src;
+        return 0;
+    }
     staged_reserve(u, n_src > 0 ? n_src : 1);
     u->n_heavy = 0;
     u->n_staged = n_src;

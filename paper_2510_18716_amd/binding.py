@@ -33,7 +33,8 @@ class SsdConfig(C.Structure):
     _fields_ = [
         ("n_layers", C.c_int32), ("n_seqs", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
         ("dtype", C.c_int32), ("window", C.c_int32), ("n_init_sink", C.c_int32), ("budget", C.c_int32),
-        ("recent", C.c_int32), ("stage_cap", C.c_int32), ("softmax_scale", C.c_float), ("reserved", C.c_int32 * 5),
+        ("recent", C.c_int32), ("stage_cap", C.c_int32), ("softmax_scale", C.c_float), ("spatial_row_buffer", C.c_int32),
+        ("reserved", C.c_int32 * 4),
     ]
 
 
@@ -48,6 +49,8 @@ lib.ssd_cache_reset.argtypes = [_vp]
 lib.ssd_cache_reset.restype = C.c_int
 lib.ssd_cache_layer_state.argtypes = [_vp, C.c_int, C.POINTER(C.c_int32 * 4)]
 lib.ssd_cache_layer_state.restype = C.c_int
+lib.ssd_cache_layer_window.argtypes = [_vp, C.c_int, C.POINTER(C.c_int32)]
+lib.ssd_cache_layer_window.restype = C.c_int
 lib.ssd_cache_set_launch.argtypes = [_vp, C.c_int]
 lib.ssd_cache_set_launch.restype = C.c_int
 lib.ssd_classify_heads.argtypes = [_vp, _vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, _vp, _vp, _vp]
@@ -125,12 +128,13 @@ def _dtype_code(dt) -> int:
     raise ValueError("unsupported dtype %r" % (dt,))
 
 
-def make_config(L, B, H, d, dtype, W, S, M, R, C_, softmax_scale=0.0) -> SsdConfig:
+def make_config(L, B, H, d, dtype, W, S, M, R, C_, softmax_scale=0.0, spatial_row_buffer=0) -> SsdConfig:
     cfg = SsdConfig()
     cfg.n_layers, cfg.n_seqs, cfg.n_heads, cfg.head_dim = L, B, H, d
     cfg.dtype = _dtype_code(dtype)
     cfg.window, cfg.n_init_sink, cfg.budget, cfg.recent, cfg.stage_cap = W, S, M, R, C_
     cfg.softmax_scale = softmax_scale
+    cfg.spatial_row_buffer = int(spatial_row_buffer)
     return cfg
 
 
@@ -184,6 +188,11 @@ class Cache:
         out = (C.c_int32 * 4)()
         _check(lib.ssd_cache_layer_state(self._h, layer, C.byref(out)), "ssd_cache_layer_state")
         return tuple(out)
+
+    def layer_window(self, layer: int) -> int:
+        out = C.c_int32(0)
+        _check(lib.ssd_cache_layer_window(self._h, layer, C.byref(out)), "ssd_cache_layer_window")
+        return out.value
 
     @property
     def export_slots(self) -> int:

@@ -59,7 +59,7 @@ extern "C" int ssd_append_token(ssd_cache *cache, int layer_begin, int layer_end
     const ssd_config &cf = cache->cfg;
     // a full row buffer in any layer refuses the whole call (nothing is appended anywhere)
     for (int l = layer_begin; l < layer_end; ++l)
-        if (cache->ldesc[l].n_se > 0 && cache->st[l].c >= cf.stage_cap)
+        if (has_buffer(cache, l) && cache->st[l].c >= cf.stage_cap)
             return fail(SSD_ERR_STAGE_OVERFLOW, "row buffer overflow: layer %d already buffers %d tokens (C=%d); call ssd_compress_kv",
                         l, cache->st[l].c, cf.stage_cap);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -77,7 +77,7 @@ extern "C" int ssd_append_token(ssd_cache *cache, int layer_begin, int layer_end
             a.n_units = (le - lb) * BH;
             a.lpr = a.g.row_bytes / 16;
             a.pos = st.n;
-            a.slot_sp = st.n < cf.n_init_sink ? st.n : cf.n_init_sink + (st.n - cf.n_init_sink) % cf.window;
+            a.slot_sp = spatial_slot(cache, st.n);
             a.slot_se = cf.budget + (st.base + st.c) % cf.stage_cap;
             const long long threads = (long long)a.n_units * 2 * a.lpr;
             const unsigned blocks = (unsigned)((threads + 255) / 256);
@@ -87,7 +87,7 @@ extern "C" int ssd_append_token(ssd_cache *cache, int layer_begin, int layer_end
         }
         for (int l = lb; l < le; ++l) {
             cache->st[l].n += 1;
-            if (cache->ldesc[l].n_se > 0) cache->st[l].c += 1;   // a layer without semantic heads has no row buffer
+            if (has_buffer(cache, l)) cache->st[l].c += 1;       // a layer of Algorithm-1 spatial heads only has no row buffer
         }
         lb = le;
     }

@@ -57,9 +57,11 @@ static int validate(const ssd_config *c, const uint8_t *head_type) {
     if (c->recent < 0) return fail(SSD_ERR_INVALID_ARG, "recent R=%d must be >= 0", c->recent);
     if (c->stage_cap <= c->recent) return fail(SSD_ERR_INVALID_ARG, "stage_cap C=%d must exceed recent R=%d", c->stage_cap, c->recent);
     if ((int64_t)c->budget + c->stage_cap > 4096) return fail(SSD_ERR_INVALID_ARG, "M + C = %lld exceeds 4096", (long long)c->budget + c->stage_cap);
-    if ((int64_t)c->n_init_sink + c->window > 65536) return fail(SSD_ERR_INVALID_ARG, "S + W exceeds 65536");
+    if (c->spatial_row_buffer != 0 && c->spatial_row_buffer != 1) return fail(SSD_ERR_INVALID_ARG, "spatial_row_buffer must be 0 or 1");
+    if ((int64_t)c->n_init_sink + c->window + (c->spatial_row_buffer ? c->stage_cap : 0) > 65536)
+        return fail(SSD_ERR_INVALID_ARG, "a spatial head would need more than 65536 slots");
     if (!(c->softmax_scale >= 0.f) || !std::isfinite(c->softmax_scale)) return fail(SSD_ERR_INVALID_ARG, "softmax_scale must be finite and >= 0");
-    for (int i = 0; i < 5; ++i)
+    for (int i = 0; i < 4; ++i)
         if (c->reserved[i] != 0) return fail(SSD_ERR_INVALID_ARG, "reserved[%d] must be 0", i);
     const size_t n = (size_t)c->n_layers * c->n_heads;
     for (size_t i = 0; i < n; ++i)
@@ -71,7 +73,7 @@ static int validate(const ssd_config *c, const uint8_t *head_type) {
 static size_t plan_layout(const ssd_config *c, const uint8_t *head_type, std::vector<LayerDesc> *ldesc) {
     const int L = c->n_layers, H = c->n_heads;
     const size_t row = (size_t)c->head_dim * esize_of(c->dtype);
-    const size_t unit_sp = 2 * (size_t)(c->n_init_sink + c->window) * row;
+    const size_t unit_sp = 2 * (size_t)(c->n_init_sink + c->window + (c->spatial_row_buffer ? c->stage_cap : 0)) * row;
     const size_t unit_se = 2 * (size_t)(c->budget + c->stage_cap) * row;
     const size_t slots = (size_t)c->budget + c->stage_cap;
     size_t off = 0;
@@ -117,8 +119,9 @@ Geom make_geom(const ssd_cache *c) {
     g.W = c->cfg.window;
     g.M = c->cfg.budget;
     g.C = c->cfg.stage_cap;
+    g.RW = g.W + (c->cfg.spatial_row_buffer ? g.C : 0);
     g.row_bytes = c->cfg.head_dim * c->esize;
-    g.unit_sp_bytes = 2u * (uint32_t)(g.S + g.W) * (uint32_t)g.row_bytes;
+    g.unit_sp_bytes = 2u * (uint32_t)(g.S + g.RW) * (uint32_t)g.row_bytes;
     g.unit_se_bytes = 2u * (uint32_t)(g.M + g.C) * (uint32_t)g.row_bytes;
     return g;
 }
@@ -128,12 +131,48 @@ void fill_launch_meta(const ssd_cache *c, int lb, int le, LaunchMeta *out) {
     for (int i = le - lb; i < LMAX; ++i) out->layer[i] = c->ldesc[lb];   // never indexed; keeps the bytes defined
 }
 
+bool has_buffer(const ssd_cache *c, int l) { return c->ldesc[l].n_se > 0 || c->cfg.spatial_row_buffer != 0; }
+
+void apply_compress_counters(ssd_cache *c, int l) {
+    LayerState &x = c->st[l];
+    const ssd_config &cf = c->cfg;
+    if (cf.spatial_row_buffer) x.nc = x.n;             // spatial heads: the window is re-cut to the W newest tokens
+    const int old = x.c - cf.recent;                   // buffered tokens that leave the row buffer
+    if (!has_buffer(c, l) || old <= 0) return;
+    if (c->ldesc[l].n_se > 0) {
+        const int tot = x.m + old;
+        x.m = tot < cf.budget ? tot : cf.budget;
+    }
+    x.base = (x.base + old) % cf.stage_cap;
+    x.c = cf.recent;
+}
+
+int spatial_slot(const ssd_cache *c, int p) {
+    const int S = c->cfg.n_init_sink;
+    const int RW = c->cfg.window + (c->cfg.spatial_row_buffer ? c->cfg.stage_cap : 0);
+    return p < S ? p : S + (p - S) % RW;
+}
+
 Segs spatial_segs(const ssd_cache *c, const LayerState &st) {
-    // the ring fills front to back, so the valid slots are always a prefix
     Segs s = {{0, 0, 0}, {0, 0, 0}, 0};
-    const int cap = c->cfg.n_init_sink + c->cfg.window;
-    s.len[0] = st.n < cap ? st.n : cap;
-    s.total = s.len[0];
+    const int S = c->cfg.n_init_sink, W = c->cfg.window;
+    if (!c->cfg.spatial_row_buffer) {
+        // Algorithm 1: the ring fills front to back, so the valid slots are always a prefix
+        const int cap = S + W;
+        s.len[0] = st.n < cap ? st.n : cap;
+        s.total = s.len[0];
+        return s;
+    }
+    // Algorithm 2: sinks, then positions [max(S, nc - W), n) in a ring of W + C slots
+    const int RW = W + c->cfg.stage_cap;
+    s.len[0] = st.n < S ? st.n : S;
+    const int lo = st.nc - W > S ? st.nc - W : S;
+    const int count = st.n > lo ? st.n - lo : 0;
+    const int start = S + (lo - S) % RW;
+    const int first = count < S + RW - start ? count : S + RW - start;
+    s.start[1] = start; s.len[1] = first;
+    s.start[2] = S;     s.len[2] = count - first;
+    s.total = s.len[0] + s.len[1] + s.len[2];
     return s;
 }
 
@@ -151,12 +190,14 @@ Segs semantic_segs(const ssd_cache *c, const LayerState &st) {
     return s;
 }
 
-Segs spatial_segs_without(const ssd_cache *c, const LayerState &st, int skip) {
-    Segs s = spatial_segs(c, st);
+Segs spatial_segs_fused(const ssd_cache *c, const LayerState &before, const LayerState &after, int new_slot) {
+    if (c->cfg.spatial_row_buffer) return spatial_segs(c, before);   // the new token's slot is never a retained one
+    // Algorithm 1: the new token overwrites the oldest ring slot; stream the prefix around it
+    Segs s = spatial_segs(c, after);
     const int end = s.len[0];
-    if (skip < 0 || skip >= end) return s;
-    s.start[0] = 0;        s.len[0] = skip;
-    s.start[1] = skip + 1; s.len[1] = end - skip - 1;
+    if (new_slot < 0 || new_slot >= end) return s;
+    s.start[0] = 0;            s.len[0] = new_slot;
+    s.start[1] = new_slot + 1; s.len[1] = end - new_slot - 1;
     s.total = end - 1;
     return s;
 }
@@ -164,14 +205,14 @@ Segs spatial_segs_without(const ssd_cache *c, const LayerState &st, int skip) {
 int same_state_run(const ssd_cache *c, int lb, int le) {
     int l = lb + 1;
     // layers with and without semantic heads never share a launch: only the former have a row buffer
-    const bool has_se = c->ldesc[lb].n_se > 0;
-    while (l < le && l - lb < LMAX && c->st[l] == c->st[lb] && (c->ldesc[l].n_se > 0) == has_se) ++l;
+    const bool buf = has_buffer(c, lb), has_se = c->ldesc[lb].n_se > 0;
+    while (l < le && l - lb < LMAX && c->st[l] == c->st[lb] && has_buffer(c, l) == buf && (c->ldesc[l].n_se > 0) == has_se) ++l;
     return l;
 }
 
 // ---- export ---------------------------------------------------------------
 
-__global__ void export_kernel(Geom g, LayerDesc ld, LayerState st, Segs se, int slots, int32_t *pos_out,
+__global__ void export_kernel(Geom g, LayerDesc ld, LayerState st, Segs se, int lo, int slots, int32_t *pos_out,
                               int32_t *count_out, float *score_out) {
     const int unit = blockIdx.x;   // b*H + h
     const int b = unit / g.H, h = unit % g.H;
@@ -187,19 +228,21 @@ __global__ void export_kernel(Geom g, LayerDesc ld, LayerState st, Segs se, int 
             if (score_out) score_out[o + s] = valid ? u.score[s] : 0.f;
         }
     } else {
-        const int cap = g.S + g.W;
-        count = st.n < cap ? st.n : cap;
+        // retained: sinks and positions [lo, n); lo was computed on the host
+        const int n_sink = st.n < g.S ? st.n : g.S;
+        const int n_win = st.n > lo ? st.n - lo : 0;
+        count = n_sink + n_win;
         for (int s = threadIdx.x; s < slots; s += blockDim.x) {
             int p = -1;
             if (s < g.S) {
                 p = s < st.n ? s : -1;
-            } else if (s < cap && st.n > g.S) {
+            } else if (s < g.S + g.RW && n_win > 0) {
                 // newest position whose ring slot is s
                 const int j = s - g.S;
                 const int last = st.n - 1;
-                const int kl = (last - g.S) % g.W;
-                const int cand = last - ((kl - j + g.W) % g.W);
-                p = cand >= g.S ? cand : -1;
+                const int kl = (last - g.S) % g.RW;
+                const int cand = last - ((kl - j + g.RW) % g.RW);
+                p = cand >= lo ? cand : -1;
             }
             if (pos_out) pos_out[o + s] = p;
             if (score_out) score_out[o + s] = 0.f;
@@ -242,7 +285,7 @@ int ssd_cache_init(const ssd_config *cfg, const uint8_t *head_type, void *dev_me
     c->dev = static_cast<char *>(dev_mem);
     c->bytes = bytes;
     c->launch_enabled = true;
-    c->st.assign(cfg->n_layers, LayerState{0, 0, 0, 0});
+    c->st.assign(cfg->n_layers, LayerState{0, 0, 0, 0, 0});
     *out = c;
     return SSD_OK;
 }
@@ -252,7 +295,7 @@ void ssd_cache_free(ssd_cache *cache) { delete cache; }
 int ssd_cache_reset(ssd_cache *cache) {
     clear_error();
     if (!cache) return fail(SSD_ERR_INVALID_ARG, "cache is NULL");
-    cache->st.assign(cache->cfg.n_layers, LayerState{0, 0, 0, 0});
+    cache->st.assign(cache->cfg.n_layers, LayerState{0, 0, 0, 0, 0});
     return SSD_OK;
 }
 
@@ -266,6 +309,15 @@ int ssd_cache_layer_state(const ssd_cache *cache, int layer, int32_t out4[4]) {
     return SSD_OK;
 }
 
+int ssd_cache_layer_window(const ssd_cache *cache, int layer, int32_t *n_at_last_compress) {
+    clear_error();
+    int rc = check_layers(cache, layer, layer + 1);
+    if (rc != SSD_OK) return rc;
+    if (!n_at_last_compress) return fail(SSD_ERR_INVALID_ARG, "output pointer is NULL");
+    *n_at_last_compress = cache->st[layer].nc;
+    return SSD_OK;
+}
+
 int ssd_cache_set_launch(ssd_cache *cache, int enable) {
     clear_error();
     if (!cache) return fail(SSD_ERR_INVALID_ARG, "cache is NULL");
@@ -275,7 +327,8 @@ int ssd_cache_set_launch(ssd_cache *cache, int enable) {
 
 int ssd_cache_export_slots(const ssd_cache *cache) {
     if (!cache) return 0;
-    const int a = cache->cfg.n_init_sink + cache->cfg.window, b = cache->cfg.budget + cache->cfg.stage_cap;
+    const int a = cache->cfg.n_init_sink + cache->cfg.window + (cache->cfg.spatial_row_buffer ? cache->cfg.stage_cap : 0);
+    const int b = cache->cfg.budget + cache->cfg.stage_cap;
     return a > b ? a : b;
 }
 
@@ -289,7 +342,10 @@ int ssd_cache_export(ssd_cache *cache, int layer, int32_t *pos, int32_t *count, 
     const LayerState st = cache->st[layer];
     const Segs se = semantic_segs(cache, st);
     const int units = cache->cfg.n_seqs * cache->cfg.n_heads;
-    hipLaunchKernelGGL(export_kernel, dim3(units), dim3(64), 0, s, make_geom(cache), cache->ldesc[layer], st, se,
+    const int S = cache->cfg.n_init_sink, W = cache->cfg.window;
+    const int ref = cache->cfg.spatial_row_buffer ? st.nc : st.n;      // Algorithm 1: the window always ends at n
+    const int lo = ref - W > S ? ref - W : S;
+    hipLaunchKernelGGL(export_kernel, dim3(units), dim3(64), 0, s, make_geom(cache), cache->ldesc[layer], st, se, lo,
                        ssd_cache_export_slots(cache), pos, count, score);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "export launch");

@@ -67,7 +67,7 @@ __global__ __launch_bounds__(THREADS) void compress_dense_kernel(DenseSrcArgs a)
 
     if (!u.sem) {
         // positions {0..S-1} and the last W: destination slot as in ssd_append_token
-        const int S = a.g.S, W = a.g.W;
+        const int S = a.g.S, W = a.g.W, RW = a.g.RW;
         const int n_sink = a.n_src < S ? a.n_src : S;
         const int w_begin = a.n_src - W > S ? a.n_src - W : S;
         const int n_win = a.n_src > w_begin ? a.n_src - w_begin : 0;
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(THREADS) void compress_dense_kernel(DenseSrcArgs a)
             const int f = t % frag_per_tok;
             const int kv = f / a.lpr, sub = f % a.lpr;
             const int p = k < n_sink ? k : w_begin + (k - n_sink);
-            const int slot = p < S ? p : S + (p - S) % W;
+            const int slot = p < S ? p : S + (p - S) % RW;
             const uint4 v = *reinterpret_cast<const uint4 *>((kv ? Vs : Ks) + (size_t)p * a.g.row_bytes + (size_t)sub * 16u);
             *reinterpret_cast<uint4 *>((kv ? u.V : u.K) + (size_t)slot * a.g.row_bytes + (size_t)sub * 16u) = v;
         }
@@ -207,8 +207,9 @@ extern "C" int ssd_compress_kv(ssd_cache *cache, int layer_begin, int layer_end,
             LayerState &st = cache->st[l];
             st.n = n_src;
             st.m = cache->ldesc[l].n_se > 0 ? (n_cand < cf.budget ? n_cand : cf.budget) : 0;
-            st.c = cache->ldesc[l].n_se > 0 ? n_rec : 0;
+            st.c = has_buffer(cache, l) ? n_rec : 0;
             st.base = 0;
+            st.nc = n_src;
         }
         return SSD_OK;
     }
@@ -218,19 +219,13 @@ extern "C" int ssd_compress_kv(ssd_cache *cache, int layer_begin, int layer_end,
         const int le = same_state_run(cache, lb, layer_end);
         const LayerState st = cache->st[lb];
         const int n_old = st.c - cf.recent;
-        if (n_old > 0) {            // otherwise nothing is due in these layers (also: no semantic heads, c == 0)
-            if (cache->launch_enabled) {
-                rc = launch_compress_inplace(cache, lb, le, st, s);
-                if (rc != SSD_OK) return rc;
-            }
-            for (int l = lb; l < le; ++l) {
-                LayerState &x = cache->st[l];
-                const int total = x.m + n_old;
-                x.m = total < cf.budget ? total : cf.budget;
-                x.base = (x.base + n_old) % cf.stage_cap;
-                x.c = cf.recent;
-            }
+        // kernels run only where semantic heads have candidates; the counters (and the spatial window of
+        // Algorithm 2) move in every layer of the range
+        if (n_old > 0 && cache->ldesc[lb].n_se > 0 && cache->launch_enabled) {
+            rc = launch_compress_inplace(cache, lb, le, st, s);
+            if (rc != SSD_OK) return rc;
         }
+        for (int l = lb; l < le; ++l) apply_compress_counters(cache, l);
         lb = le;
     }
     return SSD_OK;

@@ -304,7 +304,7 @@ static __device__ __forceinline__ UnitRef unit_ref(const Geom &g, const LayerDes
     } else {
         const size_t idx = (size_t)b * (size_t)ld.n_sp + (size_t)(h - sem_below);
         u.K = g.base + ld.off_sp + idx * (size_t)g.unit_sp_bytes;
-        u.V = u.K + (size_t)(g.S + g.W) * (size_t)g.row_bytes;
+        u.V = u.K + (size_t)(g.S + g.RW) * (size_t)g.row_bytes;
         u.score = nullptr;
         u.pos = nullptr;
     }

@@ -37,8 +37,9 @@ struct LaunchMeta {
 struct Geom {
     char *base;               // device memory of the cache
     int32_t B, H, S, W, M, C;
+    int32_t RW;               // ring slots of a spatial head: W, or W + C when spatial heads use the row buffer
     int32_t row_bytes;        // d * element size
-    uint32_t unit_sp_bytes;   // 2 * (S+W) * row_bytes : K plane then V plane
+    uint32_t unit_sp_bytes;   // 2 * (S+RW) * row_bytes : K plane then V plane
     uint32_t unit_se_bytes;   // 2 * (M+C) * row_bytes
 };
 
@@ -48,7 +49,8 @@ struct LayerState {
     int32_t m;      // heavy slots in use: slots [0, m)
     int32_t c;      // row-buffer slots in use
     int32_t base;   // ring index (0..C-1) of the oldest row-buffer slot
-    bool operator==(const LayerState &o) const { return n == o.n && m == o.m && c == o.c && base == o.base; }
+    int32_t nc;     // tokens held at the last compression (start of the spatial row buffer, Algorithm 2)
+    bool operator==(const LayerState &o) const { return n == o.n && m == o.m && c == o.c && base == o.base && nc == o.nc; }
 };
 
 // Up to three runs of consecutive valid slots of a unit, in slot space.
@@ -85,8 +87,15 @@ Geom make_geom(const ssd_cache *c);
 void fill_launch_meta(const ssd_cache *c, int lb, int le, LaunchMeta *out);   // le - lb <= LMAX
 Segs spatial_segs(const ssd_cache *c, const LayerState &st);
 Segs semantic_segs(const ssd_cache *c, const LayerState &st);
-// Same, but leaving out slot `skip` (the slot a fused append is about to write).
-Segs spatial_segs_without(const ssd_cache *c, const LayerState &st_after_append, int skip);
+// Rows a fused append + attention streams from a spatial unit: everything retained after the append except
+// the new token itself (which the kernel holds in registers); new_slot is where that token goes.
+Segs spatial_segs_fused(const ssd_cache *c, const LayerState &before, const LayerState &after, int new_slot);
+// slot of position p in a spatial unit
+int spatial_slot(const ssd_cache *c, int p);
+// host bookkeeping of one in-place compression of layer l (the kernels' effect on the counters)
+void apply_compress_counters(ssd_cache *c, int l);
+// does layer l keep a row buffer (semantic heads, or spatial heads under Algorithm 2)
+bool has_buffer(const ssd_cache *c, int l);
 // end of the run of layers starting at lb that share layer lb's state, at most LMAX long
 int same_state_run(const ssd_cache *c, int lb, int le);
 

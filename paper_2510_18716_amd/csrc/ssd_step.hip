@@ -253,11 +253,10 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
     for (int lb = layer_begin; lb < layer_end;) {
         const int le = same_state_run(cache, lb, layer_end);
         const LayerState before = cache->st[lb];
-        const bool has_se = cache->ldesc[lb].n_se > 0;
-        // all layers of a run share their counters; whether a layer has semantic heads may differ, and the
-        // row-buffer counter only moves in layers that have them -- such layers never share a run for long
+        const bool has_se = cache->ldesc[lb].n_se > 0;     // uniform over the run, like the row-buffer flag
+        const bool has_buf = has_buffer(cache, lb);
         LayerState at = before;                      // state the attention sees
-        if (fused) { at.n += 1; if (has_se) at.c += 1; }
+        if (fused) { at.n += 1; if (has_buf) at.c += 1; }
         const int n_old = at.c - cf.recent;
         const bool do_compress = compress && has_se && n_old > 0;
         const bool in_kernel = do_compress && at.m + n_old <= FUSED_SELECT_MAX;
@@ -271,10 +270,10 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.v_new = static_cast<const char *>(v_new);
             a.layer_off = lb - layer_begin;
             a.new_pos = before.n;
-            a.new_slot_sp = before.n < cf.n_init_sink ? before.n : cf.n_init_sink + (before.n - cf.n_init_sink) % cf.window;
+            a.new_slot_sp = spatial_slot(cache, before.n);
             a.new_slot_se = cf.budget + (before.base + before.c) % cf.stage_cap;
             if (fused) {
-                a.sp = spatial_segs_without(cache, at, a.new_slot_sp);
+                a.sp = spatial_segs_fused(cache, before, at, a.new_slot_sp);
                 a.se = semantic_segs(cache, before);
             } else {
                 a.sp = spatial_segs(cache, at);
@@ -302,14 +301,8 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
         }
         for (int l = lb; l < le; ++l) {
             LayerState &x = cache->st[l];
-            if (fused) { x.n += 1; if (cache->ldesc[l].n_se > 0) x.c += 1; }
-            if (compress && cache->ldesc[l].n_se > 0 && x.c - cf.recent > 0) {
-                const int old = x.c - cf.recent;
-                const int tot = x.m + old;
-                x.m = tot < cf.budget ? tot : cf.budget;
-                x.base = (x.base + old) % cf.stage_cap;
-                x.c = cf.recent;
-            }
+            if (fused) { x.n += 1; if (has_buf) x.c += 1; }
+            if (compress) apply_compress_counters(cache, l);
         }
         lb = le;
     }
@@ -352,7 +345,7 @@ extern "C" int ssd_decode_step(ssd_cache *cache, int layer_begin, int layer_end,
     if (!aligned(q, 16) || !aligned(out, 16) || !aligned(k_new, 16) || !aligned(v_new, 16))
         return fail(SSD_ERR_INVALID_ARG, "q / k_new / v_new / out must be 16-byte aligned");
     for (int l = layer_begin; l < layer_end; ++l)
-        if (cache->ldesc[l].n_se > 0 && cache->st[l].c >= cache->cfg.stage_cap)
+        if (has_buffer(cache, l) && cache->st[l].c >= cache->cfg.stage_cap)
             return fail(SSD_ERR_STAGE_OVERFLOW, "row buffer overflow: layer %d already buffers %d tokens (C=%d); call ssd_compress_kv",
                         l, cache->st[l].c, cache->cfg.stage_cap);
     return run_step(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, stream, "decode step launch");

@@ -30,7 +30,7 @@ def say(*a):
 
 
 def make_cache(wl: workload.Workload, ht: np.ndarray, device="cuda") -> ssd.Cache:
-    cfg = make_config(wl.L, wl.B, wl.H, wl.d, wl.dtype, wl.W, wl.S, wl.M, wl.R, wl.C, 0.0)
+    cfg = make_config(wl.L, wl.B, wl.H, wl.d, wl.dtype, wl.W, wl.S, wl.M, wl.R, wl.C, 0.0, int(wl.alg2))
     return ssd.Cache(cfg, ht, device=device)
 
 
@@ -117,7 +117,7 @@ def oracle_unit(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.nda
     """Oracle decode of one unit: (o [steps,d], heavy_log, gap_log, Unit)."""
     l, b, h = unit
     q, K, V = workload.unit_arrays(data, l, b, h)
-    u = oracle.Unit(ht[l, h] == workload.SEMANTIC, wl.W, wl.S, wl.M, wl.R, wl.C)
+    u = oracle.Unit(ht[l, h] == workload.SEMANTIC, wl.W, wl.S, wl.M, wl.R, wl.C, buffered_spatial=wl.alg2)
     o, hl, gl = u.run(q, K, V, wl.scale, schedule, p_end=p_end, log=True)
     return o, hl, gl, u
 
@@ -132,8 +132,11 @@ def check_outputs(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str):
     return float(err.max())
 
 
-def spatial_positions(wl: workload.Workload, n: int) -> List[int]:
-    return sorted(set(range(min(wl.S, n))) | set(range(max(wl.S, n - wl.W), n)))
+def spatial_positions(wl: workload.Workload, n: int, n_c: Optional[int] = None) -> List[int]:
+    """Closed form of a spatial head's retained set after n tokens; under Algorithm 2 the window is cut at
+    n_c, the token count at the last compression."""
+    ref = n if not wl.alg2 else n_c
+    return sorted(set(range(min(wl.S, n))) | set(range(max(wl.S, ref - wl.W), n)))
 
 
 def compare_unit_sets(wl, ht, unit, layer_index, exports, heavy_log, gap_log, schedule):
@@ -147,7 +150,8 @@ def compare_unit_sets(wl, ht, unit, layer_index, exports, heavy_log, gap_log, sc
         got = sorted(int(x) for x in row if x >= 0)
         n = p + 1
         if not sem:
-            assert got == spatial_positions(wl, n), ("spatial set", unit, p)
+            n_c = max([s + 1 for s in range(p + 1) if schedule[s]], default=0)
+            assert got == spatial_positions(wl, n, n_c), ("spatial set", unit, p)
             continue
         heavy_gpu = sorted(int(x) for x in row[: wl.M] if x >= 0)
         staged_gpu = sorted(int(x) for x in row[wl.M:] if x >= 0)

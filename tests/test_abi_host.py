@@ -224,3 +224,23 @@ def test_fused_step_counters_equal_the_three_calls(seed):
     with pytest.raises(ssd.SsdError) as e:
         ssd.ssd_decode_step(a, 1, 4, FAKE, FAKE, FAKE, FAKE)
     assert e.value.code == ssd.SSD_ERR_LAYER_RANGE
+
+
+def test_algorithm2_mode_counters_and_limits():
+    cfg = make_config(2, 2, 4, 64, "f32", 6, 1, 4, 0, 3, 0.0, 1)
+    ht = np.array([[0, 0, 0, 0], [0, 0, 1, 1]], np.uint8)
+    c = ssd.Cache(cfg, ht, device=None)
+    u = oracle.Unit(False, 6, 1, 4, 0, 3, buffered_spatial=True)
+    assert c.export_slots == 1 + 6 + 3
+    for step in range(20):
+        if u.append() != 0:
+            with pytest.raises(ssd.SsdError) as e:
+                ssd.ssd_append_token(c, 0, 2, FAKE, FAKE)          # the all-spatial layer has a row buffer too
+            assert e.value.code == ssd.SSD_ERR_STAGE_OVERFLOW
+            u.compress(); ssd.ssd_compress_kv(c, 0, 2)
+            assert c.layer_window(0) == c.layer_state(0)[0] == u.n
+            assert u.append() == 0
+        ssd.ssd_append_token(c, 0, 2, FAKE, FAKE)
+        assert c.layer_state(0)[0] == u.n and c.layer_state(0)[2] == c.layer_state(1)[2]
+    cfg.spatial_row_buffer = 2
+    assert ssd.ssd_cache_bytes(cfg, ht) == 0

@@ -123,6 +123,19 @@ def test_degenerate_parameters(fused):
     _full_compare(workload.Workload("S-exceeds-n0", W=4, M=4, S=6, R=3, C=4, cadence=1, **base), fused=fused)
 
 
+@FUSED
+def test_algorithm2_spatial_heads_read_the_row_buffer(fused):
+    # Algorithm 2 as printed: row buffer of C tokens shared by both head types, emptied at each compression
+    # (R = 0), compression when it is full; and a variant that keeps R recent tokens and compresses early
+    base = dict(L=2, prompts=1, H=6, d=128, dtype="bf16", n0=5, grid_h=8, grid_w=12, seed=17, plain=True, alg2=True)
+    _full_compare(workload.Workload("alg2-literal", W=16, M=12, S=1, R=0, C=12, cadence=12, **base), fused=fused)
+    _full_compare(workload.Workload("alg2-recent", W=9, M=7, S=2, R=3, C=10, cadence=5, **base), fused=fused)
+    _full_compare(workload.Workload("alg2-all-spatial", W=6, M=4, S=1, R=0, C=4, cadence=4, **base),
+                  ht=np.zeros((2, 6), np.uint8), fused=fused)
+    wl = workload.config(2).replace(name="cfg2-alg2", L=2, prompts=4, alg2=True, R=0, C=24, cadence=24)
+    _full_compare(wl, k_units=32, export_every=50, device_gen=True, fused=fused)
+
+
 def test_unbounded_window_and_budget_equal_dense_kernel():
     wl = workload.Workload("unbounded", L=1, prompts=1, H=4, d=128, dtype="bf16", n0=5, grid_h=6, grid_w=7, W=64,
                            M=64, S=0, R=1, C=2, cadence=1, seed=11, plain=True)

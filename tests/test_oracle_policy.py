@@ -234,3 +234,57 @@ def test_planted_sinks_are_kept_on_the_tiny_config():
             assert len(hp) == wl.M
             checked += 1
     assert checked == wl.B * wl.H // 2
+
+
+# ------------------------------------------------ Algorithm 2: spatial heads read the row buffer too ----
+
+def _alg2_spatial_lists(n_tokens, S, W, R, C, compress_after):
+    """Algorithm 2 as written, with explicit lists: `cached` (sink + recent as of the last compression) and
+    `buf` (row buffer); the head attends to their concatenation; a compression rebuilds cached from all
+    tokens seen so far and resets the buffer (keeping the R newest buffered, as semantic heads do)."""
+    cached, buf, out = [], [], []
+    for p in range(n_tokens):
+        assert len(buf) < C
+        buf.append(p)
+        out.append(sorted(set(cached) | set(buf)))
+        if compress_after[p]:
+            seen = list(range(p + 1))
+            cached = sorted(set(seen[:S]) | set(seen[S:][-W:] if W > 0 else []))
+            buf = buf[len(buf) - min(R, len(buf)):]
+    return out
+
+
+@pytest.mark.parametrize("S,W,R,C,cadence", [(1, 4, 0, 3, 3), (1, 8, 0, 24, 24), (0, 5, 2, 6, 4), (2, 3, 1, 2, 1), (1, 6, 0, 1, 1)])
+def test_algorithm2_spatial_row_buffer(S, W, R, C, cadence):
+    n = 70
+    ca = [(p + 1) % cadence == 0 for p in range(n)]
+    want = _alg2_spatial_lists(n, S, W, R, C, ca)
+    u = oracle.Unit(False, W=W, S=S, M=0, R=R, C_=C, buffered_spatial=True)
+    sizes = set()
+    for p in range(n):
+        assert u.append() == 0
+        assert u.retained().tolist() == want[p], p
+        sizes.add(len(want[p]))
+        if ca[p]:
+            u.compress()
+    if cadence > 1:
+        assert max(sizes) == S + W + cadence          # the window breathes between W+1 and W+cadence
+    if cadence == 1 and R == 0:
+        # compressing after every token makes Algorithm 2 keep W older tokens plus the new one
+        plain = oracle.Unit(False, W=W + 1, S=S, M=0, R=0, C_=0)
+        for p in range(n):
+            plain.append()
+        assert want[n - 1] == plain.retained().tolist()
+
+
+def test_algorithm2_spatial_overflow_and_dense_source():
+    u = oracle.Unit(False, W=4, S=1, M=0, R=0, C_=3, buffered_spatial=True)
+    assert [u.append() for _ in range(4)] == [0, 0, 0, -1]
+    u.compress()
+    assert u.append() == 0
+    assert u.retained().tolist() == [0, 1, 2, 3]
+    v = oracle.Unit(False, W=4, S=1, M=0, R=0, C_=3, buffered_spatial=True)
+    v.load_dense(20)
+    assert v.retained().tolist() == [0, 16, 17, 18, 19]
+    v.append(); v.append()
+    assert v.retained().tolist() == [0, 16, 17, 18, 19, 20, 21]

@@ -44,6 +44,7 @@ class Workload:
     R: int = 1                # protected recent tokens of a semantic head
     C: int = 2                # row-buffer (staging) capacity, C > R
     cadence: int = 1          # compress after every `cadence` tokens
+    alg2: bool = False        # spatial heads follow Algorithm 2 (window as of the last compression + row buffer)
     spatial_frac: float = 0.5
     sink_rows: Optional[Sequence[int]] = None   # grid rows whose column-0 token is a sink (None = all)
     beta: float = 2.5         # query gain of spatial heads

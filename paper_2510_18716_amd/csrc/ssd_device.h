@@ -107,15 +107,59 @@ template <int G> static __device__ __forceinline__ float group_sum(float v) {
     return v;
 }
 
+// Exchange with the lane 16 (resp. 32) positions away, as two VALU swaps instead of LDS-crossbar
+// permutes: v_permlane16_swap trades the odd 16-lane rows of its first operand with the even rows of
+// its second, v_permlane32_swap the upper half of the first with the lower half of the second.  Fed the
+// same value twice, the two results hold, in every lane, the value of its own row (half) and of the
+// partner row (half).
+typedef unsigned uint2v_t __attribute__((ext_vector_type(2)));
+static __device__ __forceinline__ void rows_pair(float v, float &a, float &b) {
+    const uint2v_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    a = __uint_as_float(r.x); b = __uint_as_float(r.y);
+}
+static __device__ __forceinline__ void halves_pair(float v, float &a, float &b) {
+    const uint2v_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    a = __uint_as_float(r.x); b = __uint_as_float(r.y);
+}
+
 // Combine the values held by the 64/G groups of a wave (lanes equal inside a group on entry).
 template <int G> static __device__ __forceinline__ float across_groups_sum(float v) {
-#pragma unroll
-    for (int off = G; off < 64; off <<= 1) v += __shfl_xor(v, off);
-    return v;
+    float a, b;
+    if (G <= 8) v += dpp_f<0x128>(v);                  // row_ror:8 = the lane 8 away inside a 16-lane row
+    if (G <= 16) { rows_pair(v, a, b); v = a + b; }
+    halves_pair(v, a, b);
+    return a + b;
 }
 template <int G> static __device__ __forceinline__ float across_groups_max(float v) {
-#pragma unroll
-    for (int off = G; off < 64; off <<= 1) v = fmaxf(v, __shfl_xor(v, off));
+    float a, b;
+    if (G <= 8) v = fmaxf(v, dpp_f<0x128>(v));
+    if (G <= 16) { rows_pair(v, a, b); v = fmaxf(a, b); }
+    halves_pair(v, a, b);
+    return fmaxf(a, b);
+}
+
+// Minimum of a 64-bit key over the 64 lanes of a wave; every lane gets it.
+template <int CTRL> static __device__ __forceinline__ unsigned long long dpp_u64(unsigned long long v) {
+    const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)v, CTRL, 0xF, 0xF, false);
+    const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(v >> 32), CTRL, 0xF, 0xF, false);
+    return ((unsigned long long)hi << 32) | lo;
+}
+static __device__ __forceinline__ unsigned long long min_u64(unsigned long long a, unsigned long long b) { return a < b ? a : b; }
+static __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v) {
+    v = min_u64(v, dpp_u64<0xB1>(v));      // quad_perm [1,0,3,2]
+    v = min_u64(v, dpp_u64<0x4E>(v));      // quad_perm [2,3,0,1]
+    v = min_u64(v, dpp_u64<0x141>(v));     // row_half_mirror
+    v = min_u64(v, dpp_u64<0x140>(v));     // row_mirror: 16 lanes done
+    {
+        const uint2v_t lo = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+        const uint2v_t hi = __builtin_amdgcn_permlane16_swap((unsigned)(v >> 32), (unsigned)(v >> 32), false, false);
+        v = min_u64(((unsigned long long)hi.x << 32) | lo.x, ((unsigned long long)hi.y << 32) | lo.y);
+    }
+    {
+        const uint2v_t lo = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+        const uint2v_t hi = __builtin_amdgcn_permlane32_swap((unsigned)(v >> 32), (unsigned)(v >> 32), false, false);
+        v = min_u64(((unsigned long long)hi.x << 32) | lo.x, ((unsigned long long)hi.y << 32) | lo.y);
+    }
     return v;
 }
 
@@ -153,13 +197,17 @@ template <int VEC> struct Softmax {
 //   MASS      : also accumulate the probability mass of rows >= vis_start (tot) and of rows in
 //               [vis_start, far_last] (far)
 // first_iter and iter_stride must be wave-uniform (scalar) values.
-template <typename T, int D, int CH, bool ZBUF, bool MASS, bool PF = true>
+// after_first_issue() runs once, right after the loads of the first chunk have been issued: work that
+// needs data requested before the stream (and so returned before it) can go there without delaying it.
+struct NoHook { __device__ __forceinline__ void operator()() const {} };
+
+template <typename T, int D, int CH, bool ZBUF, bool MASS, bool PF = true, typename Hook = NoHook>
 static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, const char *__restrict__ Vb,
                                                   int row_bytes, const Segs &sg, int row_begin, int row_end,
                                                   int first_iter, int iter_stride,
                                                   const typename Elem<T>::Q &q, float qscale,
                                                   Softmax<Elem<T>::VEC> &sm, float *zbuf, int vis_start, int far_last,
-                                                  int g_probe = 0) {
+                                                  int g_probe = 0, Hook after_first_issue = Hook()) {
     constexpr int VEC = Elem<T>::VEC;
     constexpr int LPR = D / VEC;
     constexpr int RPW = 64 / LPR;
@@ -186,7 +234,7 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
     };
     auto compute = [&](int it0, const uint4 (&kr)[CH], const uint4 (&vr)[CH]) {
 #ifdef SSD_PROBE
-        if (g_probe == 1) {      // probe: loads only, trivial arithmetic
+        if (g_probe == 1 || g_probe == 11) {      // probe: loads only, trivial arithmetic
 #pragma unroll
             for (int i = 0; i < CH; ++i) sm.acc[0] += __uint_as_float(kr[i].x ^ kr[i].y ^ kr[i].z ^ kr[i].w ^ vr[i].x ^ vr[i].y ^ vr[i].z ^ vr[i].w);
             sm.l = 1.f;
@@ -233,13 +281,14 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
     };
 
     int it = first_iter;
-    if (it >= n_iter) return;
+    if (it >= n_iter) { after_first_issue(); return; }
     if (!PF) {                  // one buffer: issue a chunk, wait, compute
         uint4 k1[CH], v1[CH];
 #pragma unroll
         for (int i = 0; i < CH; ++i) { k1[i] = v1[i] = make_uint4(0, 0, 0, 0); }
-        for (; it < n_iter; it += chunk_iters) {
+        for (bool first = true; it < n_iter; it += chunk_iters, first = false) {
             load(it, k1, v1);
+            if (first) after_first_issue();
             compute(it, k1, v1);
         }
         return;
@@ -248,6 +297,7 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
 #pragma unroll
     for (int i = 0; i < CH; ++i) { ka[i] = va[i] = kb[i] = vb[i] = make_uint4(0, 0, 0, 0); }
     load(it, ka, va);
+    after_first_issue();
     for (;;) {
         int nxt = it + chunk_iters;
         if (nxt < n_iter) load(nxt, kb, vb);

@@ -27,15 +27,24 @@ static __device__ __forceinline__ float key_score(unsigned long long k) { return
 static __device__ __forceinline__ int key_pos(unsigned long long k) { return (int)(0xFFFFFFFFu - (uint32_t)(k & 0xFFFFFFFFull)); }
 
 // Make LDS writes of this wave's lanes visible to its other lanes (a unit handled by one wave needs no
-// workgroup barrier).
-static __device__ __forceinline__ void wave_sync() {
+// workgroup barrier).  LDS only: it does not wait for this wave's outstanding global stores, which would
+// put a full memory round trip into the tail of every unit.
+static __device__ __forceinline__ void lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Order this wave's earlier global stores before its later global loads and stores (rows, scores and
+// positions that one lane wrote and another lane of the same wave is about to read or overwrite).
+static __device__ __forceinline__ void wave_global_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
 template <bool WAVE> static __device__ __forceinline__ void unit_sync() {
-    if (WAVE) wave_sync();
+    if (WAVE) lds_sync();
     else __syncthreads();
 }
 
@@ -116,6 +125,7 @@ static __device__ __forceinline__ void select_and_move(const Geom &g, const Unit
     }
     unit_sync<WAVE>();
     const int nmove = counts[1];              // <= counts[0] by construction
+    if (WAVE) wave_global_sync();             // rows / scores stored earlier by other lanes of this wave
     // move the promoted tokens: 2*lpr 16-byte fragments per token (K row, V row) ...
     const int frag_per_tok = 2 * lpr;
     for (int t = tid; t < nmove * frag_per_tok; t += THREADS) {

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
     const int lrel = blockIdx.z;
     const int rem = blockIdx.y * a.g.H + h;
     const UnitRef u = unit_ref(a.g, a.lm.layer[lrel], blockIdx.y, h);
-    const Segs &sg = u.sem ? a.se : a.sp;
+    const Segs sg = u.sem ? a.se : a.sp;       // by value: the runs stay in scalar registers to the end
     const size_t qoff = ((size_t)(a.layer_off + lrel) * (size_t)(a.g.B * a.g.H) + rem) * (size_t)a.g.row_bytes + (size_t)sub * 16u;
     unsigned char *region = lds_raw + (size_t)w * a.wave_lds;
     float *zbuf = reinterpret_cast<float *>(region);                    // [zcap]
@@ -89,22 +89,26 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
         }
     }
 
-#ifdef SSD_PROBE
-    if (a.probe >= 2) { sm.l = 1.f; } else
-#endif
-    if (want_z)
-        stream_rows<T, D, CH, true, false>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, zbuf, 0, 0, a.probe);
-    else
-        stream_rows<T, D, CH, false, false>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, nullptr, 0, 0, a.probe);
-    if (FUSED) {
-        // The new token: stored into its slot and, from the same registers, folded into lane group 0's
-        // softmax as one more row (index sg.total).
-        const int slot = u.sem ? a.new_slot_se : a.new_slot_sp;
-        if (lane < LPR) {
+    // Fused append: the new token's rows go to their slot as soon as the stream's first loads are in
+    // flight, so these stores drain during the stream instead of in the tail of the unit.
+    auto store_new = [&]() {
+        if (FUSED && lane < LPR) {
+            const int slot = u.sem ? a.new_slot_se : a.new_slot_sp;
             const size_t off = (size_t)slot * (size_t)a.g.row_bytes + (size_t)sub * 16u;
             *reinterpret_cast<uint4 *>(u.K + off) = new_k;
             *reinterpret_cast<uint4 *>(u.V + off) = new_v;
         }
+    };
+#ifdef SSD_PROBE
+    if (a.probe == 2 || a.probe == 3 || a.probe >= 10) { sm.l = 1.f; store_new(); } else
+#endif
+    if (want_z)
+        stream_rows<T, D, CH, true, false, true>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, zbuf, 0, 0, a.probe, store_new);
+    else
+        stream_rows<T, D, CH, false, false, true>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, nullptr, 0, 0, a.probe, store_new);
+    if (FUSED) {
+        // The new token, from the registers it was loaded into, is folded into lane group 0's softmax as
+        // one more row (index sg.total).
         const float z = group_sum<LPR>(Elem<T>::dot(q, new_k)) * a.qscale;
         if (lane < LPR) {
             const float m_new = fmaxf(sm.m, z);
@@ -123,7 +127,7 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
     const float m_all = sm.m;
     const float inv_l = sm.l > 0.f ? 1.0f / sm.l : 0.f;
 #ifdef SSD_PROBE
-    if (a.probe >= 3) return;
+    if (a.probe % 10 == 3) return;
 #endif
     if (lane < LPR) {
         float o[VEC];
@@ -133,54 +137,73 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
     }
 
     if (!tail) return;
-    wave_sync();                                          // the logits written by the group leaders
+#ifdef SSD_PROBE
+    if (a.probe % 10 == 4) return;
+#endif
+    lds_sync();                                           // the logits written by the group leaders
     const int M = a.g.M, C = a.g.C;
     const int n_old = a.c - a.R;                          // buffered tokens that become candidates
     const int n_cand = a.m + n_old;
     const int n_evict = n_cand - M;                       // <= 0: everything is kept
+    // At most one eviction among at most 128 candidates (always the case when compressing after every
+    // token) is settled in registers; anything else ranks all candidates through LDS.
+    const bool general = compress && (n_evict >= 2 || n_cand > 128);
     unsigned long long *keys = reinterpret_cast<unsigned long long *>(sel);
-    unsigned long long min_key = ~0ull;
+    unsigned long long my_key[2] = {~0ull, ~0ull};        // keys of rows lane and lane + 64, if candidates
     const int total = sg.total + (FUSED ? 1 : 0);
-    for (int r = lane, k = 0; r < total; r += 64, ++k) {
+    // One row's share: add the probability to its running score, note position and key.
+    auto score_row = [&](int r, float s_old, int pos_old) -> unsigned long long {
         const bool is_new = FUSED && r == sg.total;
         const int slot = is_new ? a.new_slot_se : seg_slot(sg, r);
         const float p = a.accumulate ? fast_exp2(zbuf[r] - m_all) * inv_l : 0.f;
-        const float s_old = is_new ? 0.f : (k == 0 ? pre_score[0] : k == 1 ? pre_score[1] : u.score[slot]);
-        const float s = s_old + p;
+        const float s = (is_new ? 0.f : s_old) + p;
         if (a.accumulate || is_new) u.score[slot] = s;
-        int pos;
-        if (is_new) { pos = a.new_pos; u.pos[slot] = pos; }
-        else pos = !compress ? 0 : (k == 0 ? pre_pos[0] : k == 1 ? pre_pos[1] : u.pos[slot]);
+        if (is_new) u.pos[slot] = a.new_pos;
+        unsigned long long key = ~0ull;
         if (compress && r < n_cand) {
-            const unsigned long long key = make_key(s, pos);
-            keys[r] = key;
-            min_key = key < min_key ? key : min_key;
+            key = make_key(s, is_new ? a.new_pos : pos_old);
+            if (general) keys[r] = key;
         }
+        return key;
+    };
+    // rows 0..127 use the scores and positions fetched before the stream: no load, and therefore no wait
+    // on this wave's own stores, in the common case
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int r = lane + 64 * k;
+        if (r < total) my_key[k] = score_row(r, pre_score[k], pre_pos[k]);
+    }
+    for (int r = lane + 128; r < total; r += 64) {       // long row buffers only
+        const bool is_new = FUSED && r == sg.total;
+        const int slot = is_new ? a.new_slot_se : seg_slot(sg, r);
+        score_row(r, is_new ? 0.f : u.score[slot], (is_new || !compress) ? 0 : u.pos[slot]);
     }
     if (!compress) return;
-    wave_sync();
-    if (n_evict >= 2) {                                   // general case: rank every candidate
+#ifdef SSD_PROBE
+    if (a.probe % 10 == 5) return;
+#endif
+    if (general) {
+        lds_sync();
         select_and_move<64, true>(a.g, u, sel, n_cand, a.m, n_old, a.base, a.lpr, lane);
         return;
     }
-    // At most one eviction (always the case when compressing after every token): the promoted buffered
-    // tokens and the slots they go to follow from the index of the single evicted candidate.
-    int e_idx = -1;                                       // evicted candidate, -1 if none
+    // The promoted buffered tokens and the slots they go to follow from the index of the single evicted
+    // candidate (the one with the smallest key), if any.
+    int e_idx = -1;
     if (n_evict == 1) {
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const unsigned long long o = __shfl_xor(min_key, off);
-            min_key = o < min_key ? o : min_key;
-        }
-        int *e_store = reinterpret_cast<int *>(keys + n_cand);
-        for (int r = lane; r < n_cand; r += 64)
-            if (keys[r] == min_key) *e_store = r;
-        wave_sync();
-        e_idx = *e_store;
+        const unsigned long long min_key = wave_min_u64(my_key[0] < my_key[1] ? my_key[0] : my_key[1]);
+        const unsigned long long hit0 = __ballot(my_key[0] == min_key);
+        const unsigned long long hit1 = __ballot(my_key[1] == min_key);
+        e_idx = hit0 ? __builtin_ctzll(hit0) : 64 + __builtin_ctzll(hit1);
     }
+#ifdef SSD_PROBE
+    if (a.probe % 10 == 6) return;
+#endif
     const bool ev_heavy = e_idx >= 0 && e_idx < a.m;
     const bool ev_staged = e_idx >= a.m;
     const int n_move = n_old - (ev_staged ? 1 : 0);
+    if (n_move <= 0) return;
+    wave_global_sync();                                   // rows / scores stored earlier by other lanes of this wave
     const int frag_per_tok = 2 * a.lpr;
     // k-th promoted candidate (oldest first) and k-th free heavy slot
     auto src_idx = [&](int k) { return a.m + k + ((ev_staged && k >= e_idx - a.m) ? 1 : 0); };
@@ -194,10 +217,17 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
         const uint4 v = *reinterpret_cast<const uint4 *>(plane + (size_t)from * a.g.row_bytes + (size_t)fs * 16u);
         *reinterpret_cast<uint4 *>(plane + (size_t)dst_slot(k) * a.g.row_bytes + (size_t)fs * 16u) = v;
     }
-    for (int k = lane; k < n_move; k += 64) {
-        const unsigned long long key = keys[src_idx(k)];
-        u.pos[dst_slot(k)] = key_pos(key);
-        u.score[dst_slot(k)] = key_score(key);
+    // position and score travel with the token: its key sits in the registers of lane (index mod 64)
+    for (int k0 = 0; k0 < n_move; k0 += 64) {             // wave-uniform trip count: the shuffles need every lane
+        const int k = k0 + lane;
+        const int src = k < n_move ? src_idx(k) : 0;
+        const unsigned long long c0 = __shfl(my_key[0], src & 63);
+        const unsigned long long c1 = __shfl(my_key[1], src & 63);
+        const unsigned long long key = src < 64 ? c0 : c1;
+        if (k < n_move) {
+            u.pos[dst_slot(k)] = key_pos(key);
+            u.score[dst_slot(k)] = key_score(key);
+        }
     }
 }
 

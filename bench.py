@@ -77,6 +77,7 @@ def main():
     ap.add_argument("--layers-per-call", type=int, default=1,
                     help="layers handed to each library call for the headline figure (1 = as a real model would)")
     ap.add_argument("--prompts", type=int, default=0, help="override the number of prompts (0 = the configuration's)")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the configuration's)")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
@@ -106,6 +107,8 @@ def main():
     wl = workload.config(args.config)
     if args.prompts:
         wl = wl.replace(prompts=args.prompts)
+    if args.layers:
+        wl = wl.replace(L=args.layers, name=wl.name + "-L%d" % args.layers)
     if args.grid_rows:
         wl = wl.replace(grid_h=args.grid_rows, name=wl.name + "-rows%d" % args.grid_rows)
     accumulate = not args.no_accumulate
@@ -133,28 +136,42 @@ def main():
         Returns wall seconds of the timed steps and, if asked, the mean HIP-event duration of a launch."""
         calls = [(lb, min(wl.L, lb + lpc)) for lb in range(0, wl.L, lpc)]
 
+        # raw device addresses: a launch should cost the host a ctypes call, not four tensor slices
+        stride_l = wl.B * wl.H * wl.d * (2 if wl.dtype == "bf16" else 4)
+        stride_p = wl.L * stride_l
+        qb, kb, vb, ob = data["q"].data_ptr(), data["k"].data_ptr(), data["v"].data_ptr(), out.data_ptr()
+        stream = torch.cuda.current_stream().cuda_stream
+        h = cache.handle
+        L_ = ssd.lib
+        acc_i = int(accumulate)
+
         def step(p, ev=None, acct=None):
-            q, k, v = data["q"][p], data["k"][p], data["v"][p]
+            comp = int(bool(sched[p]))
             if ev is not None and fused:
                 ev[0].record()
             for ci, (lb, le) in enumerate(calls):
+                o = p * stride_p + lb * stride_l
                 if fused:
                     if acct is not None:            # what this launch has to move, from the live counters
                         n_, m_, c_, _ = cache.layer_state(lb)
                         acct.append(algorithmic_bytes_attend(wl, ht, range(lb, le), (n_ + 1, m_, c_ + 1)) +
                                     algorithmic_bytes_append(wl, ht, range(lb, le)))
-                    ssd.ssd_decode_step(cache, lb, le, q[lb:le], k[lb:le], v[lb:le], out[lb:le], accumulate, bool(sched[p]))
+                    rc = L_.ssd_decode_step(h, lb, le, qb + o, kb + o, vb + o, ob + lb * stride_l, acc_i, comp, stream)
+                    assert rc == 0, ssd.ssd_last_error()
                     continue
-                ssd.ssd_append_token(cache, lb, le, k[lb:le], v[lb:le])
+                rc = L_.ssd_append_token(h, lb, le, kb + o, vb + o, stream)
+                assert rc == 0, ssd.ssd_last_error()
                 if acct is not None:
                     acct.append(algorithmic_bytes_attend(wl, ht, range(lb, le), cache.layer_state(lb)[:3]))
                 if ev is not None:
                     ev[2 * ci].record()
-                ssd.ssd_decode_attn(cache, lb, le, q[lb:le], out[lb:le], accumulate)
+                rc = L_.ssd_decode_attn(h, lb, le, qb + o, ob + lb * stride_l, acc_i, stream)
+                assert rc == 0, ssd.ssd_last_error()
                 if ev is not None:
                     ev[2 * ci + 1].record()
-                if sched[p]:
-                    ssd.ssd_compress_kv(cache, lb, le)
+                if comp:
+                    rc = L_.ssd_compress_kv(h, lb, le, None, None, None, 0, stream)
+                    assert rc == 0, ssd.ssd_last_error()
             if ev is not None and fused:
                 ev[1].record()
 

@@ -16,26 +16,30 @@
 
 namespace ssd {
 
+// Field order matters: a wave reads its arguments with scalar loads, and every 64-byte line of the
+// argument block it touches for the first time is a trip to memory that the whole (in-phase) launch waits
+// for.  Everything a unit needs sits in the first lines; the per-layer table, of which a wave reads one
+// entry, comes last.
 struct StepArgs {
-    Geom g;
-    LaunchMeta lm;
     const char *q;
     char *out;
     const char *k_new;   // fused append only
     const char *v_new;
+    float qscale;        // softmax scale * log2(e)
     int layer_off;       // index of the launch's first layer inside q / out / k_new / v_new
-    Segs sp, se;         // rows streamed from the cache (fused append: without the new token's slot)
     int new_slot_sp;     // fused append: destination slots and position of the new token
     int new_slot_se;
     int new_pos;
-    float qscale;        // softmax scale * log2(e)
     int accumulate;
-    int zcap;            // floats of LDS per wave for the logits of a semantic unit
-    int wave_lds;        // bytes of LDS per wave (logits + selection scratch)
     int do_compress;     // run the selection after the attention (semantic units)
     int m, c, base, R;   // row-buffer state the selection works on (c counts a fused new token)
     int lpr;
+    int zcap;            // floats of LDS per wave for the logits of a semantic unit
+    int wave_lds;        // bytes of LDS per wave (logits + selection scratch)
     int probe;           // SSD_PROBE builds only
+    Segs sp, se;         // rows streamed from the cache (fused append: without the new token's slot)
+    Geom g;
+    LaunchMeta lm;
 };
 
 // One wave per unit, WPB units (consecutive heads of one sequence and layer) per workgroup;
@@ -46,6 +50,13 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
     constexpr int LPR = D / VEC;
     extern __shared__ __align__(16) unsigned char lds_raw[];
 
+    // The arguments the tail of a unit needs are fetched now, with everything else, and pinned in scalar
+    // registers: fetched lazily they would add a memory round trip to the end of every wave.
+    int t_m = a.m, t_c = a.c, t_base = a.base, t_R = a.R, t_lpr = a.lpr, t_new_pos = a.new_pos,
+        t_new_slot_se = a.new_slot_se, t_do_compress = a.do_compress, t_accumulate = a.accumulate,
+        t_M = a.g.M, t_C = a.g.C, t_row_bytes = a.g.row_bytes;
+    asm volatile("" : "+s"(t_m), "+s"(t_c), "+s"(t_base), "+s"(t_R), "+s"(t_lpr), "+s"(t_new_pos), "+s"(t_new_slot_se),
+                      "+s"(t_do_compress), "+s"(t_accumulate), "+s"(t_M), "+s"(t_C), "+s"(t_row_bytes));
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: everything per-unit stays uniform
     const int lane = threadIdx.x & 63;
     const int sub = lane % LPR;
@@ -63,13 +74,13 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
     const typename Elem<T>::Q q = Elem<T>::load_q(*reinterpret_cast<const uint4 *>(a.q + qoff));
     Softmax<VEC> sm;
     sm.init();
-    const bool want_z = u.sem && a.accumulate;
+    const bool want_z = u.sem && t_accumulate;
 
     // Everything the tail of this wave will need is requested now, ahead of the K/V stream, so that no
     // memory round trip is left exposed after the last row: the new token's fragments (fused append) and
     // the running scores / positions of the first 128 rows (one or two per lane).
-    const bool compress = a.do_compress != 0;
-    const bool tail = u.sem && (a.accumulate || compress || FUSED);
+    const bool compress = t_do_compress != 0;
+    const bool tail = u.sem && (t_accumulate || compress || FUSED);
     uint4 new_k = make_uint4(0, 0, 0, 0), new_v = make_uint4(0, 0, 0, 0);
     if (FUSED && lane < LPR) {
         new_k = *reinterpret_cast<const uint4 *>(a.k_new + qoff);
@@ -141,9 +152,9 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
     if (a.probe % 10 == 4) return;
 #endif
     lds_sync();                                           // the logits written by the group leaders
-    const int M = a.g.M, C = a.g.C;
-    const int n_old = a.c - a.R;                          // buffered tokens that become candidates
-    const int n_cand = a.m + n_old;
+    const int M = t_M, C = t_C;
+    const int n_old = t_c - t_R;                          // buffered tokens that become candidates
+    const int n_cand = t_m + n_old;
     const int n_evict = n_cand - M;                       // <= 0: everything is kept
     // At most one eviction among at most 128 candidates (always the case when compressing after every
     // token) is settled in registers; anything else ranks all candidates through LDS.
@@ -154,14 +165,14 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
     // One row's share: add the probability to its running score, note position and key.
     auto score_row = [&](int r, float s_old, int pos_old) -> unsigned long long {
         const bool is_new = FUSED && r == sg.total;
-        const int slot = is_new ? a.new_slot_se : seg_slot(sg, r);
-        const float p = a.accumulate ? fast_exp2(zbuf[r] - m_all) * inv_l : 0.f;
+        const int slot = is_new ? t_new_slot_se : seg_slot(sg, r);
+        const float p = t_accumulate ? fast_exp2(zbuf[r] - m_all) * inv_l : 0.f;
         const float s = (is_new ? 0.f : s_old) + p;
-        if (a.accumulate || is_new) u.score[slot] = s;
-        if (is_new) u.pos[slot] = a.new_pos;
+        if (t_accumulate || is_new) u.score[slot] = s;
+        if (is_new) u.pos[slot] = t_new_pos;
         unsigned long long key = ~0ull;
         if (compress && r < n_cand) {
-            key = make_key(s, is_new ? a.new_pos : pos_old);
+            key = make_key(s, is_new ? t_new_pos : pos_old);
             if (general) keys[r] = key;
         }
         return key;
@@ -175,7 +186,7 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
     }
     for (int r = lane + 128; r < total; r += 64) {       // long row buffers only
         const bool is_new = FUSED && r == sg.total;
-        const int slot = is_new ? a.new_slot_se : seg_slot(sg, r);
+        const int slot = is_new ? t_new_slot_se : seg_slot(sg, r);
         score_row(r, is_new ? 0.f : u.score[slot], (is_new || !compress) ? 0 : u.pos[slot]);
     }
     if (!compress) return;
@@ -184,7 +195,7 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
 #endif
     if (general) {
         lds_sync();
-        select_and_move<64, true>(a.g, u, sel, n_cand, a.m, n_old, a.base, a.lpr, lane);
+        select_and_move<64, true>(a.g, u, sel, n_cand, t_m, n_old, t_base, t_lpr, lane);
         return;
     }
     // The promoted buffered tokens and the slots they go to follow from the index of the single evicted
@@ -199,23 +210,23 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
 #ifdef SSD_PROBE
     if (a.probe % 10 == 6) return;
 #endif
-    const bool ev_heavy = e_idx >= 0 && e_idx < a.m;
-    const bool ev_staged = e_idx >= a.m;
+    const bool ev_heavy = e_idx >= 0 && e_idx < t_m;
+    const bool ev_staged = e_idx >= t_m;
     const int n_move = n_old - (ev_staged ? 1 : 0);
     if (n_move <= 0) return;
     wave_global_sync();                                   // rows / scores stored earlier by other lanes of this wave
-    const int frag_per_tok = 2 * a.lpr;
+    const int frag_per_tok = 2 * t_lpr;
     // k-th promoted candidate (oldest first) and k-th free heavy slot
-    auto src_idx = [&](int k) { return a.m + k + ((ev_staged && k >= e_idx - a.m) ? 1 : 0); };
-    auto dst_slot = [&](int k) { return ev_heavy ? (k == 0 ? e_idx : a.m + k - 1) : a.m + k; };
+    auto src_idx = [&](int k) { return t_m + k + ((ev_staged && k >= e_idx - t_m) ? 1 : 0); };
+    auto dst_slot = [&](int k) { return ev_heavy ? (k == 0 ? e_idx : t_m + k - 1) : t_m + k; };
     for (int t = lane; t < n_move * frag_per_tok; t += 64) {
         const int k = t / frag_per_tok;
         const int f = t % frag_per_tok;
-        const int kv = f / a.lpr, fs = f % a.lpr;
+        const int kv = f / t_lpr, fs = f % t_lpr;
         char *plane = kv ? u.V : u.K;
-        const int from = M + (a.base + (src_idx(k) - a.m)) % C;
-        const uint4 v = *reinterpret_cast<const uint4 *>(plane + (size_t)from * a.g.row_bytes + (size_t)fs * 16u);
-        *reinterpret_cast<uint4 *>(plane + (size_t)dst_slot(k) * a.g.row_bytes + (size_t)fs * 16u) = v;
+        const int from = M + (t_base + (src_idx(k) - t_m)) % C;
+        const uint4 v = *reinterpret_cast<const uint4 *>(plane + (size_t)from * t_row_bytes + (size_t)fs * 16u);
+        *reinterpret_cast<uint4 *>(plane + (size_t)dst_slot(k) * t_row_bytes + (size_t)fs * 16u) = v;
     }
     // position and score travel with the token: its key sits in the registers of lane (index mod 64)
     for (int k0 = 0; k0 < n_move; k0 += 64) {             // wave-uniform trip count: the shuffles need every lane

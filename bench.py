@@ -47,7 +47,8 @@ def algorithmic_bytes_attend(wl, ht, layers, state):
     output out, and the score read-modify-write of semantic heads."""
     n, m, c = state
     row = row_bytes(wl)
-    rows_sp = min(n, wl.S + wl.W)
+    # Algorithm 2: a spatial head also reads the tokens appended since the last compression (c - R of them)
+    rows_sp = min(n, wl.S + wl.W + (max(c - wl.R, 0) if wl.alg2 else 0))
     rows_se = m + c
     total = 0
     for l in layers:
@@ -88,6 +89,8 @@ def main():
     ap.add_argument("--cpu-units", type=int, default=4096)
     ap.add_argument("--grid-rows", type=int, default=0, help="profiling aid: shorten the image to this many grid rows (0 = full image)")
     ap.add_argument("--no-accumulate", action="store_true", help="experiment: attention without the running-score update")
+    ap.add_argument("--alg2", action="store_true",
+                    help="row-buffer variant (Algorithm 2): both head types read a 24-token row buffer, compression every 24 tokens")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every (layer, sequence, head) unit is independent, so it "
@@ -109,6 +112,8 @@ def main():
         wl = wl.replace(prompts=args.prompts)
     if args.layers:
         wl = wl.replace(L=args.layers, name=wl.name + "-L%d" % args.layers)
+    if args.alg2:
+        wl = wl.replace(alg2=True, R=0, C=wl.grid_w, cadence=wl.grid_w, name=wl.name + "-alg2")
     if args.grid_rows:
         wl = wl.replace(grid_h=args.grid_rows, name=wl.name + "-rows%d" % args.grid_rows)
     accumulate = not args.no_accumulate
@@ -125,7 +130,7 @@ def main():
     torch.cuda.synchronize()
     t_gen = time.time() - t0
     sched = workload.compress_schedule(wl)
-    cfg = make_config(wl.L, wl.B, wl.H, wl.d, wl.dtype, wl.W, wl.S, wl.M, wl.R, wl.C, 0.0)
+    cfg = make_config(wl.L, wl.B, wl.H, wl.d, wl.dtype, wl.W, wl.S, wl.M, wl.R, wl.C, 0.0, int(wl.alg2))
     cache = ssd.Cache(cfg, ht, device=dev)
     out = torch.empty((wl.L, wl.B, wl.H, wl.d), dtype=wl.torch_dtype, device=dev)
     p_timed = wl.n_total - K_steps
@@ -313,7 +318,7 @@ def main():
 
         def run_unit(i):
             l, b, h = units[i]
-            u = oracle.Unit(ht[l, h] == workload.SEMANTIC, wl.W, wl.S, wl.M, wl.R, wl.C)
+            u = oracle.Unit(ht[l, h] == workload.SEMANTIC, wl.W, wl.S, wl.M, wl.R, wl.C, buffered_spatial=wl.alg2)
             q_, k_, v_ = (a[h] for a in host[(l, b)])
             u.run(q_, k_, v_, wl.scale, sched)
             return 0

@@ -44,7 +44,16 @@ struct StepArgs {
 
 // One wave per unit, WPB units (consecutive heads of one sequence and layer) per workgroup;
 // grid = (ceil(H / WPB), B, layers of the launch).  Nothing below needs a workgroup barrier.
-template <typename T, int D, int CH, int WPB, bool FUSED>
+#ifdef SSD_PROBE
+#define SSD_ST16(ptr, val) do { const uint4 _v = (val); uint4 *_p = reinterpret_cast<uint4 *>(ptr); \
+    if (a.probe / 100 == 1) {} else if (a.probe / 100 == 3) { asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" :: "v"(_p), "v"(_v) : "memory"); } else if (a.probe / 100 == 2) { __builtin_nontemporal_store(_v.x, &_p->x); __builtin_nontemporal_store(_v.y, &_p->y); __builtin_nontemporal_store(_v.z, &_p->z); __builtin_nontemporal_store(_v.w, &_p->w); } else *_p = _v; } while (0)
+#define SSD_ST4(ptr, val) do { if (a.probe / 100 == 1) {} else if (a.probe / 100 == 3) { asm volatile("global_store_dword %0, %1, off sc0 sc1" :: "v"(ptr), "v"(val) : "memory"); } else if (a.probe / 100 == 2) __builtin_nontemporal_store((val), (ptr)); else *(ptr) = (val); } while (0)
+#else
+#define SSD_ST16(ptr, val) (*reinterpret_cast<uint4 *>(ptr) = (val))
+#define SSD_ST4(ptr, val) (*(ptr) = (val))
+#endif
+
+template <typename T, int D, int CH, int WPB, bool FUSED, bool PF = true>
 __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
     constexpr int VEC = Elem<T>::VEC;
     constexpr int LPR = D / VEC;
@@ -106,17 +115,17 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
         if (FUSED && lane < LPR) {
             const int slot = u.sem ? a.new_slot_se : a.new_slot_sp;
             const size_t off = (size_t)slot * (size_t)a.g.row_bytes + (size_t)sub * 16u;
-            *reinterpret_cast<uint4 *>(u.K + off) = new_k;
-            *reinterpret_cast<uint4 *>(u.V + off) = new_v;
+            SSD_ST16(u.K + off, new_k);
+            SSD_ST16(u.V + off, new_v);
         }
     };
 #ifdef SSD_PROBE
-    if (a.probe == 2 || a.probe == 3 || a.probe >= 10) { sm.l = 1.f; store_new(); } else
+    if (a.probe % 100 == 2 || a.probe % 100 == 3 || a.probe % 100 >= 10) { sm.l = 1.f; store_new(); } else
 #endif
     if (want_z)
-        stream_rows<T, D, CH, true, false, true>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, zbuf, 0, 0, a.probe, store_new);
+        stream_rows<T, D, CH, true, false, PF>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, zbuf, 0, 0, a.probe, store_new);
     else
-        stream_rows<T, D, CH, false, false, true>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, nullptr, 0, 0, a.probe, store_new);
+        stream_rows<T, D, CH, false, false, PF>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, nullptr, 0, 0, a.probe, store_new);
     if (FUSED) {
         // The new token, from the registers it was loaded into, is folded into lane group 0's softmax as
         // one more row (index sg.total).
@@ -144,7 +153,7 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
         float o[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) o[e] = sm.acc[e] * inv_l;
-        *reinterpret_cast<uint4 *>(a.out + qoff) = Elem<T>::pack(o);
+        SSD_ST16(a.out + qoff, Elem<T>::pack(o));
     }
 
     if (!tail) return;
@@ -168,8 +177,8 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
         const int slot = is_new ? t_new_slot_se : seg_slot(sg, r);
         const float p = t_accumulate ? fast_exp2(zbuf[r] - m_all) * inv_l : 0.f;
         const float s = (is_new ? 0.f : s_old) + p;
-        if (t_accumulate || is_new) u.score[slot] = s;
-        if (is_new) u.pos[slot] = t_new_pos;
+        if (t_accumulate || is_new) SSD_ST4(&u.score[slot], s);
+        if (is_new) SSD_ST4(&u.pos[slot], t_new_pos);
         unsigned long long key = ~0ull;
         if (compress && r < n_cand) {
             key = make_key(s, is_new ? t_new_pos : pos_old);
@@ -255,10 +264,10 @@ static Tuning g_tune = DEFAULT_TUNE;
 // compression kernel (a whole workgroup per head) runs after the attention.
 static constexpr int FUSED_SELECT_MAX = 1024;
 
-template <typename T, int D, int CH, int WPB>
+template <typename T, int D, int CH, int WPB, bool PF = true>
 static void launch_one(const StepArgs &a, dim3 blocks, size_t lds, bool fused, hipStream_t s) {
-    if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true>), blocks, dim3(WPB * 64), lds, s, a);
-    else hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, false>), blocks, dim3(WPB * 64), lds, s, a);
+    if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, PF>), blocks, dim3(WPB * 64), lds, s, a);
+    else hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, false, PF>), blocks, dim3(WPB * 64), lds, s, a);
 }
 
 template <typename T, int D>
@@ -277,6 +286,11 @@ static hipError_t launch_step(StepArgs &a, int H, int B, int layers, bool fused,
         SSD_CASE(1, 1) SSD_CASE(2, 1) SSD_CASE(4, 1)
         SSD_CASE(1, 2) SSD_CASE(2, 2) SSD_CASE(4, 2)
         SSD_CASE(1, 4) SSD_CASE(2, 4) SSD_CASE(4, 4)
+#ifdef SSD_PROBE
+#define SSD_CASE_NPF(CODE_, CH_, WPB_) if (ch == CODE_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_, false>(a, blocks, lds, fused, s); return hipGetLastError(); }
+        SSD_CASE_NPF(14, 4, 4) SSD_CASE_NPF(18, 8, 4) SSD_CASE_NPF(14, 4, 8) SSD_CASE_NPF(18, 8, 8) SSD_CASE_NPF(18, 8, 2) SSD_CASE(4, 8) SSD_CASE(2, 8)
+#undef SSD_CASE_NPF
+#endif
     } else {
         if (ch == 1) ch = 2;
         SSD_CASE(2, 1) SSD_CASE(4, 1) SSD_CASE(2, 2) SSD_CASE(4, 2) SSD_CASE(2, 4) SSD_CASE(4, 4)
@@ -360,7 +374,9 @@ using namespace ssd;
 extern "C" int ssd_tune_attend(int ch, int wpb, int probe) {
     g_probe = probe;
     if (ch == 0 && wpb == 0) { g_tune = DEFAULT_TUNE; return SSD_OK; }
+#ifndef SSD_PROBE
     if ((ch != 0 && ch != 1 && ch != 2 && ch != 4) || (wpb != 1 && wpb != 2 && wpb != 4)) return SSD_ERR_INVALID_ARG;
+#endif
     g_tune.ch = ch; g_tune.wpb = wpb;
     return SSD_OK;
 }

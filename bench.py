@@ -69,6 +69,59 @@ def algorithmic_bytes_append(wl, ht, layers):
     return total
 
 
+def sweep5(args, dev):
+    """Configuration 5: B = 512 sequences, 32 heads, d = 128; spatial fraction in {25, 50, 75} %, W and M in
+    {32, 64, 128}.  Steady-state fused per-layer launches on `--layers` layers (default 4; a per-layer launch has
+    the full configuration's shape whatever the layer count), inputs plain Gaussians (timing does not depend on
+    the values)."""
+    import numpy as np
+    import torch
+
+    import paper_2510_18716_amd as ssd
+    import workload
+    from paper_2510_18716_amd.binding import make_config
+    L = args.layers or 4
+    rows = []
+    base = workload.config(5).replace(L=L, plain=True, grid_h=8)          # 64 + 192 tokens: every window fills
+    data = workload.generate(base, device=dev)
+    K_steps = 40
+    for frac in (0.25, 0.5, 0.75):
+        for W in (32, 64, 128):
+            for M in (32, 64, 128):
+                wl = base.replace(spatial_frac=frac, W=W, M=M)
+                ht = workload.head_map(wl)
+                cache = ssd.Cache(make_config(wl.L, wl.B, wl.H, wl.d, wl.dtype, W, wl.S, M, wl.R, wl.C), ht, device=dev)
+                out = torch.empty((wl.L, wl.B, wl.H, wl.d), dtype=wl.torch_dtype, device=dev)
+                stride_l = wl.B * wl.H * wl.d * 2
+                qb, kb, vb, ob = data["q"].data_ptr(), data["k"].data_ptr(), data["v"].data_ptr(), out.data_ptr()
+                stream = torch.cuda.current_stream().cuda_stream
+
+                def step(p):
+                    for l in range(wl.L):
+                        o = (p * wl.L + l) * stride_l
+                        rc = ssd.lib.ssd_decode_step(cache.handle, l, l + 1, qb + o, kb + o, vb + o, ob + l * stride_l, 1, 1, stream)
+                        assert rc == 0, ssd.ssd_last_error()
+                p_timed = wl.n_total - K_steps
+                for p in range(p_timed):
+                    step(p)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for p in range(p_timed, wl.n_total):
+                    step(p)
+                torch.cuda.synchronize()
+                dt = (time.perf_counter() - t0) / K_steps
+                n_, m_, c_, _ = cache.layer_state(0)
+                gb = (algorithmic_bytes_attend(wl, ht, range(wl.L), (n_, m_, c_ + 1)) + algorithmic_bytes_append(wl, ht, range(wl.L))) / 1e9
+                rows.append({"spatial_frac": frac, "W": W, "M": M, "ms_per_layer": dt / wl.L * 1e3, "GB_per_layer": gb / wl.L,
+                             "GBps": gb / dt, "frac_of_hbm_peak": gb / dt / HBM_PEAK_GBS,
+                             "tokens_per_s_at_30_layers": wl.prompts / (dt / wl.L * 30)})
+                del cache
+    print(json.dumps({"metric": "visual tokens/sec per GPU (compressed decode attn, all layers)", "unit": "tokens/s",
+                      "config": {"workload": "cfg5-large sweep", "sequences": base.B, "heads": base.H, "head_dim": base.d,
+                                 "layers_timed": L, "launches": "ssd_decode_step, one per layer"},
+                      "sweep": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -89,6 +142,8 @@ def main():
     ap.add_argument("--cpu-units", type=int, default=4096)
     ap.add_argument("--grid-rows", type=int, default=0, help="profiling aid: shorten the image to this many grid rows (0 = full image)")
     ap.add_argument("--no-accumulate", action="store_true", help="experiment: attention without the running-score update")
+    ap.add_argument("--sweep5", action="store_true",
+                    help="large-batch sweep (configuration 5): spatial fraction x W x M at B = 512, one JSON line with a list")
     ap.add_argument("--alg2", action="store_true",
                     help="row-buffer variant (Algorithm 2): both head types read a 24-token row buffer, compression every 24 tokens")
     args = ap.parse_args()
@@ -107,6 +162,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.sweep5:
+        return sweep5(args, dev)
     wl = workload.config(args.config)
     if args.prompts:
         wl = wl.replace(prompts=args.prompts)
@@ -181,7 +238,11 @@ def main():
                 ev[1].record()
 
         cache.reset()
-        for p in range(0, p_warm):                  # untimed fill: prompt and the earlier part of the image
+        for p in range(0, wl.n0):                   # the prompt, through ordinary decode steps
+            step(p)
+        torch.cuda.synchronize()
+        t_vis = time.perf_counter()
+        for p in range(wl.n0, p_warm):              # the earlier part of the image (fills every window and budget)
             step(p)
         torch.cuda.synchronize()
         for p in range(p_warm, p_timed):
@@ -191,7 +252,9 @@ def main():
         for p in range(p_timed, wl.n_total):
             step(p)
         torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
+        t1 = time.perf_counter()
+        dt = t1 - t0
+        whole = t1 - t_vis                          # all N visual tokens, two intermediate synchronisations included
 
         # algorithmic bytes of the timed launches, from the counters each launch ran with (host-only replay)
         acct = []
@@ -202,6 +265,9 @@ def main():
         ssd.lib.ssd_cache_set_launch(cache.handle, 1)
         bytes_launch = float(np.mean(acct))
         res = {"seconds": dt, "ms_per_step": dt / K_steps * 1e3, "value": wl.prompts * K_steps / dt,
+               "whole_decode": {"visual_tokens": wl.N, "seconds": whole, "value": wl.prompts * wl.N / whole, "unit": "tokens/s",
+                                "note": "all %d visual tokens of the raster decode from the end of the prompt, cache filling up "
+                                        "on the way" % wl.N},
                "launches_per_step": len(calls) * (1 if fused else 3), "bytes_per_launch": bytes_launch,
                "algorithmic_GB_per_step": bytes_launch * len(calls) / 1e9}
         if not with_events:
@@ -257,6 +323,7 @@ def main():
     }
     if "roofline" in head:
         result["roofline"] = head["roofline"]
+    result["whole_decode"] = head["whole_decode"]
 
     if not args.no_all_layers and lpc != wl.L:
         alt = measure(wl.L, with_events=not args.no_roofline)
@@ -294,12 +361,22 @@ def main():
         dtd = (time.perf_counter() - t0) / reps
         row = row_bytes(wl)
         dense_bytes = wl.L * wl.B * wl.H * ((n - (reps - 1) / 2) * 2 * row + 2 * row)
+        # whole raster decode through the dense kernel (its cost grows with n)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for p in range(wl.n0, n):
+            dense_step(p)
+        torch.cuda.synchronize()
+        dense_whole = time.perf_counter() - t0
         result["dense_baseline"] = {"value": wl.prompts / dtd, "unit": "tokens/s", "ms_per_step": dtd * 1e3,
                                     "algorithmic_GB_per_step": dense_bytes / 1e9, "GBps": dense_bytes / 1e9 / dtd,
                                     "frac_of_hbm_peak": dense_bytes / 1e9 / dtd / HBM_PEAK_GBS, "steps": reps,
                                     "kind": "hand-written HIP split-K decode attention over all n rows, one launch per layer, "
                                             "appending the new token not included",
-                                    "speedup_of_compressed": dtd / (head["ms_per_step"] / 1e3)}
+                                    "speedup_of_compressed": dtd / (head["ms_per_step"] / 1e3),
+                                    "whole_decode": {"visual_tokens": wl.N, "seconds": dense_whole,
+                                                     "value": wl.prompts * wl.N / dense_whole, "unit": "tokens/s",
+                                                     "speedup_of_compressed": dense_whole / head["whole_decode"]["seconds"]}}
         result["setup_s"]["dense_layout"] = round(t_dense_setup, 2)
         del Kd, Vd
 

@@ -336,6 +336,44 @@ struct UnitRef {
     int32_t *pos;     // semantic only: [M+C]
 };
 
+// Index of the k-th set bit (k = 0 for the lowest) of the 128-bit mask (m1:m0); k must be below the
+// number of set bits.  Scalar arithmetic: a popcount-guided binary search.
+static __device__ __forceinline__ int kth_set_bit(uint64_t m0, uint64_t m1, int k) {
+    int r = 0;
+    uint64_t m = m0;
+    const int c0 = __popcll(m0);
+    if (k >= c0) { k -= c0; r = 64; m = m1; }
+    uint32_t lo = (uint32_t)m;
+    const int c = __popc(lo);
+    if (k >= c) { k -= c; r += 32; lo = (uint32_t)(m >> 32); }
+#pragma unroll
+    for (int wd = 16; wd >= 1; wd >>= 1) {
+        const int cc = __popc(lo & ((1u << wd) - 1u));
+        if (k >= cc) { k -= cc; r += wd; lo >>= wd; }
+    }
+    return r;
+}
+
+// Addresses of the unit that is the `local`-th head of its type (sem) in its layer, sequence b.
+static __device__ __forceinline__ UnitRef unit_ref_local(const Geom &g, const LayerDesc &ld, int b, bool sem, int local) {
+    UnitRef u;
+    u.sem = sem;
+    if (sem) {
+        const size_t idx = (size_t)b * (size_t)ld.n_se + (size_t)local;
+        u.K = g.base + ld.off_se + idx * (size_t)g.unit_se_bytes;
+        u.V = u.K + (size_t)(g.M + g.C) * (size_t)g.row_bytes;
+        u.score = reinterpret_cast<float *>(g.base + ld.off_score) + idx * (size_t)(g.M + g.C);
+        u.pos = reinterpret_cast<int32_t *>(g.base + ld.off_pos) + idx * (size_t)(g.M + g.C);
+    } else {
+        const size_t idx = (size_t)b * (size_t)ld.n_sp + (size_t)local;
+        u.K = g.base + ld.off_sp + idx * (size_t)g.unit_sp_bytes;
+        u.V = u.K + (size_t)(g.S + g.RW) * (size_t)g.row_bytes;
+        u.score = nullptr;
+        u.pos = nullptr;
+    }
+    return u;
+}
+
 // ld: the layer's entry of the launch's LaunchMeta (kernel-argument memory, scalar loads)
 static __device__ __forceinline__ UnitRef unit_ref(const Geom &g, const LayerDesc &ld, int b, int h) {
     UnitRef u;

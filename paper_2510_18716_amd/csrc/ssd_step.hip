@@ -37,6 +37,7 @@ struct StepArgs {
     int zcap;            // floats of LDS per wave for the logits of a semantic unit
     int wave_lds;        // bytes of LDS per wave (logits + selection scratch)
     int probe;           // SSD_PROBE builds only
+    int sem_first;       // semantic units have more rows than spatial ones: dispatch them first
     Segs sp, se;         // rows streamed from the cache (fused append: without the new token's slot)
     Geom g;
     LaunchMeta lm;
@@ -69,11 +70,19 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: everything per-unit stays uniform
     const int lane = threadIdx.x & 63;
     const int sub = lane % LPR;
-    const int h = blockIdx.x * WPB + w;
-    if (h >= a.g.H) return;
-    const int lrel = blockIdx.z;
+    // grid = (ceil(max heads of a type / WPB), B, 2 * layers): z selects the layer and the head type, the type
+    // with more rows first, so that within a layer the long units are dispatched before the short ones and
+    // all waves of a workgroup have units of one length
+    const int lrel = blockIdx.z >> 1;
+    const bool sem_unit = ((blockIdx.z & 1) == 0) == (a.sem_first != 0);
+    const int local = blockIdx.x * WPB + w;               // index among the heads of this type in this layer
+    const LayerDesc &ld = a.lm.layer[lrel];
+    if (local >= (sem_unit ? ld.n_se : ld.n_sp)) return;
+    const uint64_t m0 = sem_unit ? ld.sem_mask[0] : ~ld.sem_mask[0];
+    const uint64_t m1 = sem_unit ? ld.sem_mask[1] : ~ld.sem_mask[1];
+    const int h = kth_set_bit(m0, m1, local);             // spatial heads: bits above H are never reached (local < n_sp)
     const int rem = blockIdx.y * a.g.H + h;
-    const UnitRef u = unit_ref(a.g, a.lm.layer[lrel], blockIdx.y, h);
+    const UnitRef u = unit_ref_local(a.g, ld, blockIdx.y, sem_unit, local);
     const Segs sg = u.sem ? a.se : a.sp;       // by value: the runs stay in scalar registers to the end
     const size_t qoff = ((size_t)(a.layer_off + lrel) * (size_t)(a.g.B * a.g.H) + rem) * (size_t)a.g.row_bytes + (size_t)sub * 16u;
     unsigned char *region = lds_raw + (size_t)w * a.wave_lds;
@@ -271,7 +280,7 @@ static void launch_one(const StepArgs &a, dim3 blocks, size_t lds, bool fused, h
 }
 
 template <typename T, int D>
-static hipError_t launch_step(StepArgs &a, int H, int B, int layers, bool fused, int M, hipStream_t s) {
+static hipError_t launch_step(StepArgs &a, int H, int max_type_heads, int B, int layers, bool fused, int M, hipStream_t s) {
     const int n_old = a.c - a.R, n_cand = a.m + n_old;
     // Few units (one layer of a modest batch): every wave is resident at once and shallow queues finish
     // sooner; many units: waves come and go, deeper per-wave queues keep HBM busier.
@@ -280,7 +289,7 @@ static hipError_t launch_step(StepArgs &a, int H, int B, int layers, bool fused,
     a.wave_lds = (int)(((size_t)a.zcap * 4 + (a.do_compress ? select_lds_bytes(M, n_cand, n_old) + 16 : 0) + 15) / 16 * 16);
     while (wpb > 1 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;
     const size_t lds = (size_t)wpb * a.wave_lds;
-    const dim3 blocks((unsigned)((H + wpb - 1) / wpb), (unsigned)B, (unsigned)layers);
+    const dim3 blocks((unsigned)((max_type_heads + wpb - 1) / wpb), (unsigned)B, (unsigned)(2 * layers));
 #define SSD_CASE(CH_, WPB_) if (ch == CH_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_>(a, blocks, lds, fused, s); return hipGetLastError(); }
     if constexpr (sizeof(T) == 2 && D == 128) {       // the shape the sweeps are run on has every variant
         SSD_CASE(1, 1) SSD_CASE(2, 1) SSD_CASE(4, 1)
@@ -341,13 +350,19 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.m = at.m; a.c = at.c; a.base = at.base; a.R = cf.recent;
             a.lpr = a.g.row_bytes / 16;
             a.probe = g_probe;
+            int mth = 1;
+            for (int l = lb; l < le; ++l) {
+                mth = cache->ldesc[l].n_sp > mth ? cache->ldesc[l].n_sp : mth;
+                mth = cache->ldesc[l].n_se > mth ? cache->ldesc[l].n_se : mth;
+            }
+            a.sem_first = a.se.total + (fused ? 1 : 0) >= a.sp.total + (fused ? 1 : 0) ? 1 : 0;
             hipError_t e;
             if (cf.dtype == SSD_BF16)
-                e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(a, cf.n_heads, cf.n_seqs, le - lb, fused, cf.budget, s)
-                                       : launch_step<bf16_t, 64>(a, cf.n_heads, cf.n_seqs, le - lb, fused, cf.budget, s);
+                e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cf.budget, s)
+                                       : launch_step<bf16_t, 64>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cf.budget, s);
             else
-                e = cf.head_dim == 128 ? launch_step<float, 128>(a, cf.n_heads, cf.n_seqs, le - lb, fused, cf.budget, s)
-                                       : launch_step<float, 64>(a, cf.n_heads, cf.n_seqs, le - lb, fused, cf.budget, s);
+                e = cf.head_dim == 128 ? launch_step<float, 128>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cf.budget, s)
+                                       : launch_step<float, 64>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cf.budget, s);
             if (e != hipSuccess) return hip_fail(e, what);
             if (do_compress && !in_kernel) {
                 const int rc = launch_compress_inplace(cache, lb, le, at, s);

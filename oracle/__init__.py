@@ -55,6 +55,8 @@ _lib.ssd_oracle_profile_unit.argtypes = [_f32p, _f32p, _f32p, C.c_int, C.c_int, 
 _lib.ssd_oracle_profile_unit.restype = None
 _lib.ssd_oracle_classify.argtypes = [_f32p, _f32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, _f64p, _u8p]
 _lib.ssd_oracle_classify.restype = None
+_lib.ssd_oracle_prefill_scores.argtypes = [_f32p, _f32p, C.c_int, C.c_int, C.c_double, _f32p]
+_lib.ssd_oracle_prefill_scores.restype = None
 _lib.ssd_oracle_top_m.argtypes = [_f32p, _i32p, C.c_int, C.c_int, _i32p, C.POINTER(C.c_double)]
 _lib.ssd_oracle_top_m.restype = C.c_int
 _lib.ssd_oracle_unit_new.argtypes = [C.c_int] * 6
@@ -136,6 +138,15 @@ def classify(far, tot, tau):
     ty = np.zeros((L, H), np.uint8)
     _lib.ssd_oracle_classify(far, tot, L, P, H, T, float(tau), s, ty)
     return s, ty
+
+
+def prefill_scores(q, K, scale):
+    """Accumulated causal attention scores of a prompt: q, K [n, d] -> float32 [n]."""
+    q, K = _f32(q), _f32(K)
+    n, d = q.shape
+    out = np.zeros(max(n, 1), np.float32)
+    _lib.ssd_oracle_prefill_scores(q, K, d, n, float(scale), out)
+    return out[:n]
 
 
 def top_m(score, pos, M):

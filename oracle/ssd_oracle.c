@@ -20,6 +20,8 @@
  *   O2  the sparsity metric s_{l,h} (display formula in Sec. 3.3,
  *       "Spatial Sparsity Analysis") and the threshold rule, Eq. (3).
  *   O3  top-M selection by accumulated score ("IndicesOfTopM", Algorithm 1).
+ *   O5  accumulated scores of a prompt processed at once under causal
+ *       attention (prefill branch of Algorithm 2).
  *   O4  the per-head cache policy of Algorithm 1 with the additions the text
  *       of Sec. 3.3 makes (initial sink token for spatial heads, reserved
  *       recent window R for semantic heads) and the deferred-compression
@@ -181,6 +183,40 @@ void ssd_oracle_classify(const float *far, const float *tot, int L, int P,
             type_out[(size_t)l * H + h] = (acc > tau) ? 1 : 0;
         }
     }
+}
+
+/* ---------------------------------------------------------- prefill scores -- */
+
+/*
+ * Accumulated attention scores of a prompt of n tokens under causal attention
+ * (the prefill branch of Algorithm 2: "Accumulate semantic attention scores"
+ * when the whole prompt is processed at once):
+ *   a_i = softmax over rows 0..i of scale * q_i . k_j          (query i sees rows 0..i)
+ *   score[j] = sum_{i=j}^{n-1} a_i(j)
+ * q, K are [n, d]; score_out[n] (float).  The same numbers n ordinary decode
+ * steps without compression would accumulate.
+ */
+void ssd_oracle_prefill_scores(const float *q, const float *K, int d, int n,
+                               double scale, float *score_out)
+{
+    int i, j, t;
+    double *acc = (double *)calloc((size_t)(n > 0 ? n : 1), sizeof(double));
+    double *z = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+    for (i = 0; i < n; ++i) {
+        double mx, sum = 0.0;
+        for (j = 0; j <= i; ++j) {
+            double dot = 0.0;
+            for (t = 0; t < d; ++t) dot += (double)q[(size_t)i * d + t] * (double)K[(size_t)j * d + t];
+            z[j] = scale * dot;
+        }
+        mx = z[0];
+        for (j = 1; j <= i; ++j) if (z[j] > mx) mx = z[j];
+        for (j = 0; j <= i; ++j) { z[j] = exp(z[j] - mx); sum += z[j]; }
+        for (j = 0; j <= i; ++j) acc[j] += z[j] / sum;
+    }
+    for (j = 0; j < n; ++j) score_out[j] = (float)acc[j];
+    free(acc);
+    free(z);
 }
 
 /* ------------------------------------------------------------------ O3 -- */

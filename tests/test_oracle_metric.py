@@ -88,3 +88,45 @@ def test_planted_head_types_are_recovered():
     np.testing.assert_array_equal(ty, ht)
     assert s[ht == workload.SPATIAL].max() < 0.2
     assert s[ht == workload.SEMANTIC].min() > 0.4
+
+
+# ------------------------------------------------------------------ prefill scores ----
+
+def test_prefill_scores_closed_forms_and_library_softmax():
+    import scipy.special
+    r = np.random.default_rng(3)
+    n, d = 37, 16
+    q = r.standard_normal((n, d)).astype(np.float32)
+    K = r.standard_normal((n, d)).astype(np.float32)
+    s = oracle.prefill_scores(q, K, 0.25)
+    # every query row distributes exactly one unit of mass
+    assert abs(float(s.astype(np.float64).sum()) - n) < 1e-4
+    # library softmax with a causal mask, column sums
+    z = (q.astype(np.float64) @ K.astype(np.float64).T) * 0.25
+    z[np.triu_indices(n, 1)] = -np.inf
+    ref = scipy.special.softmax(z, axis=1).sum(axis=0)
+    np.testing.assert_allclose(s, ref, rtol=1e-6, atol=1e-7)
+    # uniform attention (all keys equal): score[j] = sum_{i>=j} 1/(i+1) = H_n - H_j
+    Ku = np.zeros_like(K)
+    su = oracle.prefill_scores(q, Ku, 1.0)
+    H = np.concatenate([[0.0], np.cumsum(1.0 / np.arange(1, n + 1))])
+    np.testing.assert_allclose(su, H[n] - H[:n], rtol=1e-6)
+    # the last token is only ever seen by itself; the first by everyone
+    assert abs(su[-1] - 1.0 / n) < 1e-7 and su[0] == su.max()
+    # one dominant key at position 5: it collects one unit from every later query
+    Kd = np.zeros((n, d), np.float32); Kd[5, 0] = 60.0
+    qd = np.zeros((n, d), np.float32); qd[:, 0] = 1.0
+    sd = oracle.prefill_scores(qd, Kd, 1.0)
+    assert abs(sd[5] - (n - 5)) < 1e-5
+
+
+def test_prefill_scores_equal_what_decode_steps_accumulate():
+    # the same prompt fed token by token through the cache policy without any compression
+    r = np.random.default_rng(4)
+    n, d = 20, 8
+    q, K, V = (r.standard_normal((n, d)).astype(np.float32) for _ in range(3))
+    u = oracle.Unit(True, W=0, S=0, M=n, R=1, C_=n + 1)
+    u.run(q, K, V, 0.3, np.zeros(n, np.uint8))
+    _, _, sp, ss = u.state()
+    assert sp.tolist() == list(range(n))
+    np.testing.assert_allclose(ss, oracle.prefill_scores(q, K, 0.3), rtol=2e-6, atol=1e-6)

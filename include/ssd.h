@@ -199,6 +199,26 @@ int ssd_compress_kv(ssd_cache *cache, int layer_begin, int layer_end,
                     int n_src, void *stream);
 
 /*
+ * Accumulated attention scores of a prompt processed in one piece (Algorithm 2:
+ * scores are accumulated whenever attention weights exist, and a prefill is
+ * compressed at once; Sec. 3.3 for what is accumulated).  For every unit
+ * u = (layer, sequence, head) and prompt token j
+ *     score_out[u, j] = sum over i >= j of softmax_{j' <= i}(scale * q_i . k_j')[j]
+ * i.e. the column sums of the causal attention matrix -- the value the decode
+ * path would have accumulated had the prompt been fed token by token.  The
+ * result is the score_src argument of ssd_compress_kv's dense-source mode.
+ *   Q, K      : dev [n_units, n_src, d] of `dtype` (the K_src layout with the
+ *               leading three dimensions flattened)
+ *   n_units   : >= 1;  n_src : 1 .. 1024;  d : 64 or 128
+ *   dtype     : ssd_dtype;  softmax_scale : 0 selects 1/sqrt(d)
+ *   score_out : dev float [n_units, n_src], overwritten
+ * The products run on the matrix cores with fp32 accumulation; the sum over i
+ * is taken in a fixed order (bit-reproducible).
+ */
+int ssd_prefill_scores(const void *Q, const void *K, int n_units, int n_src, int d,
+                       int dtype, float softmax_scale, float *score_out, void *stream);
+
+/*
  * One whole decode step of the layers in a single launch per layer group:
  * ssd_append_token, then ssd_decode_attn, then (compress != 0) the in-place
  * mode of ssd_compress_kv, with exactly their results.  Each (sequence, head)

@@ -1,6 +1,6 @@
 """Compile the HIP sources under csrc/ into libssd_hip.so (gfx950 only), in tree.
 
-Run as `python -m paper_2510_18716_amd.build`; __graft_entry__.build() calls build(force=True).
+Run as `python paper_2510_18716_amd/build.py` (not with -m: importing the package loads the library); __graft_entry__.build() calls build(force=True).
 """
 from __future__ import annotations
 

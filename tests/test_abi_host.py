@@ -244,3 +244,16 @@ def test_algorithm2_mode_counters_and_limits():
         assert c.layer_state(0)[0] == u.n and c.layer_state(0)[2] == c.layer_state(1)[2]
     cfg.spatial_row_buffer = 2
     assert ssd.ssd_cache_bytes(cfg, ht) == 0
+
+
+def test_prefill_scores_rejects_bad_arguments_before_any_launch():
+    ok = dict(Q=FAKE, K=FAKE, n_units=4, n_src=64, d=128, dtype=ssd.SSD_BF16, scale=0.0, out=FAKE)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return ssd.lib.ssd_prefill_scores(a["Q"], a["K"], a["n_units"], a["n_src"], a["d"], a["dtype"], a["scale"], a["out"], None)
+
+    for bad in (dict(Q=None), dict(K=None), dict(out=None), dict(Q=FAKE + 8), dict(n_units=0), dict(n_src=0), dict(n_src=1025),
+                dict(d=96), dict(dtype=7), dict(scale=-1.0), dict(scale=float("nan"))):
+        assert call(**bad) == ssd.SSD_ERR_INVALID_ARG, bad
+        assert ssd.ssd_last_error() != ""

@@ -1,0 +1,139 @@
+"""GPU parity of ssd_prefill_scores (accumulated causal attention scores of a prompt, matrix-core kernel)
+against the oracle, and of the whole prompt pipeline: prefill scores -> dense-source compression -> decode."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_18716_amd as ssd
+import workload
+from harness import GAP_MARGIN, check_outputs, gpu_decode, make_cache, sample_units, say
+
+pytestmark = pytest.mark.gpu
+
+# scores are sums of up to n probabilities, each from an fp32-accumulated product and the hardware exp2
+SCORE_TOL = (2e-4, 2e-4)
+
+
+def _check_scores(got, ref, what):
+    err = np.abs(got - ref)
+    bad = err > SCORE_TOL[0] + SCORE_TOL[1] * np.abs(ref)
+    assert not bad.any(), "%s: %d of %d scores off (max abs err %.3e)" % (what, int(bad.sum()), bad.size, float(err.max()))
+
+
+def _case(dtype, d, n, units, seed, scale_mult=1.0, peaky=False):
+    say("prefill case", dtype, d, "n", n, "units", units, "seed", seed)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    g = torch.Generator().manual_seed(seed)
+    q = torch.randn((units, n, d), generator=g)
+    k = torch.randn((units, n, d), generator=g)
+    if peaky:      # a few keys that every later query looks at, as a sink token would be
+        k[:, :: max(1, n // 3)] *= 3.0
+        q += 0.5 * k[:, :1]
+    q, k = q.to(tdt), k.to(tdt)
+    out = torch.full((units, n), -5.0, device="cuda")
+    scale = scale_mult / np.sqrt(d)
+    ssd.ssd_prefill_scores(q.cuda(), k.cuda(), units, n, d, dtype, out, 0.0 if scale_mult == 1.0 else scale)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    for u in range(units):
+        ref = oracle.prefill_scores(q[u].float().numpy(), k[u].float().numpy(), scale)
+        _check_scores(got[u], ref, "unit %d" % u)
+    # every query row spreads probability 1 over the keys
+    np.testing.assert_allclose(got.sum(axis=1), n, rtol=1e-4)
+    return got
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128), ("f32", 64)])
+def test_prefill_scores_match_oracle(dtype, d):
+    for i, n in enumerate([1, 2, 31, 32, 33, 64, 100, 129]):     # below, at and across tile edges; ragged tails
+        _case(dtype, d, n, 3, 100 + i)
+    _case(dtype, d, 257, 2, 7, peaky=True)                        # more query blocks than waves
+    _case(dtype, d, 96, 2, 8, scale_mult=2.5, peaky=True)         # caller's scale, sharper softmax
+
+
+def test_prefill_scores_largest_prompt_and_many_units():
+    _case("bf16", 128, 1024, 2, 11, peaky=True)
+    got = _case("bf16", 128, 64, 600, 12)                         # more workgroups than compute units
+    assert np.isfinite(got).all()
+
+
+def test_prefill_scores_bit_reproducible():
+    g = torch.Generator().manual_seed(5)
+    q = torch.randn((40, 200, 128), generator=g).to(torch.bfloat16).cuda()
+    k = torch.randn((40, 200, 128), generator=g).to(torch.bfloat16).cuda()
+    a = torch.empty((40, 200), device="cuda")
+    b = torch.empty((40, 200), device="cuda")
+    ssd.ssd_prefill_scores(q, k, 40, 200, 128, "bf16", a)
+    ssd.ssd_prefill_scores(q, k, 40, 200, 128, "bf16", b)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+def test_prefill_scores_equal_token_by_token_decode_accumulation():
+    """Feeding the prompt one token at a time through the decode path with an unbounded budget accumulates the
+    same scores (same definition, different kernels and summation order)."""
+    n = 48
+    wl = workload.Workload("pf-eq", L=1, prompts=1, H=4, d=128, dtype="bf16", n0=n, grid_h=1, grid_w=1, W=8, M=n + 2,
+                           S=1, R=0, C=2, cadence=1, seed=77)
+    ht = np.ones((1, 4), np.uint8)
+    dev = {x: v.cuda() for x, v in workload.generate(wl, head_type=ht).items()}
+    cache = make_cache(wl, ht)
+    out = torch.empty((1, wl.B, wl.H, wl.d), dtype=torch.bfloat16, device="cuda")
+    for p in range(n):
+        ssd.ssd_decode_step(cache, 0, 1, dev["q"][p], dev["k"][p], dev["v"][p], out, True, True)
+    pos, _, sc = [x.cpu().numpy() for x in cache.export(0)]
+    Q = workload.dense_layout(dev["q"][:n]).contiguous()
+    K = workload.dense_layout(dev["k"][:n]).contiguous()
+    score = torch.empty((wl.B * wl.H, n), device="cuda")
+    ssd.ssd_prefill_scores(Q, K, wl.B * wl.H, n, wl.d, "bf16", score)
+    torch.cuda.synchronize()
+    score = score.cpu().numpy().reshape(wl.B, wl.H, n)
+    for b in range(wl.B):
+        for h in range(wl.H):
+            by_pos = {int(pp): float(ss) for pp, ss in zip(pos[b, h], sc[b, h]) if pp >= 0}
+            assert sorted(by_pos) == list(range(n))
+            _check_scores(np.array([by_pos[j] for j in range(n)], np.float32), score[b, h], "unit (%d,%d)" % (b, h))
+
+
+@pytest.mark.parametrize("dtype,d,n0", [("bf16", 128, 64), ("f32", 64, 37)])
+def test_prompt_pipeline_prefill_compress_decode(dtype, d, n0):
+    """Prompt in one piece: scores from the prefill kernel, dense-source compression, then token-by-token
+    decode of the image -- against an oracle that took the same route on its own scores."""
+    wl = workload.Workload("pf-pipe", L=2, prompts=1, H=4, d=d, dtype=dtype, n0=n0, grid_h=3, grid_w=4, W=16, M=12,
+                           S=1, R=1, C=3, cadence=2, seed=5 + n0)
+    ht = workload.head_map(wl)
+    data = workload.generate(wl, head_type=ht)
+    dev = {x: v.cuda() for x, v in data.items()}
+    Q = workload.dense_layout(dev["q"][:n0]).contiguous()
+    K = workload.dense_layout(dev["k"][:n0]).contiguous()
+    V = workload.dense_layout(dev["v"][:n0]).contiguous()
+    n_units = wl.L * wl.B * wl.H
+    score = torch.empty((wl.L, wl.B, wl.H, n0), device="cuda")
+    ssd.ssd_prefill_scores(Q, K, n_units, n0, d, dtype, score)
+    cache = make_cache(wl, ht)
+    ssd.ssd_compress_kv(cache, 0, wl.L, K, V, score, n0)
+    units = sample_units(wl, ht, 10 ** 9)
+    sched = workload.compress_schedule(wl)
+    steps = list(range(n0, wl.n_total))
+    outs, exports, _ = gpu_decode(wl, dev, ht, sched, units, export_steps=steps, cache=cache, p_begin=n0)
+    score_h = score.cpu().numpy()
+    n_ties = 0
+    for ui, (l, b, h) in enumerate(units):
+        q_, K_, V_ = workload.unit_arrays(data, l, b, h)
+        sem = ht[l, h] == workload.SEMANTIC
+        ref_score = oracle.prefill_scores(q_[:n0], K_[:n0], wl.scale)
+        _check_scores(score_h[l, b, h], ref_score, "prompt scores of %s" % ((l, b, h),))
+        u = oracle.Unit(sem, wl.W, wl.S, wl.M, wl.R, wl.C)
+        _, gap0 = u.load_dense(n0, ref_score)
+        o_ref, hl, gl = u.run(q_, K_, V_, wl.scale, sched, log=True)
+        gaps = [gap0] + list(gl)
+        if sem and any(0 <= g <= GAP_MARGIN for g in gaps):
+            n_ties += 1          # a cut inside the rounding margin may fall either way: nothing further to compare
+            continue
+        check_outputs(outs[:, ui], o_ref, dtype, "unit %s after the prompt pipeline" % ((l, b, h),))
+        if sem:
+            for p in steps:
+                row = exports[p]["post"][0][l, b, h]
+                assert sorted(int(x) for x in row[: wl.M] if x >= 0) == [int(x) for x in hl[p - n0] if x >= 0], ((l, b, h), p)
+    assert n_ties <= len(units) // 4

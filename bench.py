@@ -134,6 +134,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the configuration's)")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-microbatch", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--no-all-layers", action="store_true")
     ap.add_argument("--tune", type=str, default="", help="ch,wpb[,probe] launch-shape knobs of the attention kernel")
@@ -334,6 +336,73 @@ def main():
                     "up front; in a model each layer's query depends on the layer before, so this is an upper bound" % wl.L}
         if "roofline" in alt:
             result["all_layers_one_launch"]["roofline"] = alt["roofline"]
+
+    # ---- the batch as two halves on two streams (sequences are independent; layers of one half stay ordered) ----
+    if not args.no_microbatch and fused and lpc == 1 and wl.B % 2 == 0 and not wl.alg2:
+        ns = 2
+        Bm = wl.B // ns
+        cfg_m = make_config(wl.L, Bm, wl.H, wl.d, wl.dtype, wl.W, wl.S, wl.M, wl.R, wl.C, 0.0, 0)
+        caches = [ssd.Cache(cfg_m, ht, device=dev) for _ in range(ns)]
+        streams = [torch.cuda.Stream() for _ in range(ns)]              # default priority
+        stride_b = wl.H * wl.d * (2 if wl.dtype == "bf16" else 4)
+        stride_l = wl.B * stride_b
+        stride_p = wl.L * stride_l
+        qb, kb, vb, ob = data["q"].data_ptr(), data["k"].data_ptr(), data["v"].data_ptr(), out.data_ptr()
+        hs = [c.handle for c in caches]
+        ss = [st.cuda_stream for st in streams]
+
+        def mb_step(p):
+            comp = int(bool(sched[p]))
+            for l in range(wl.L):
+                for i in range(ns):
+                    o = p * stride_p + l * stride_l + i * Bm * stride_b
+                    rc = ssd.lib.ssd_decode_step(hs[i], l, l + 1, qb + o, kb + o, vb + o, ob + l * stride_l + i * Bm * stride_b,
+                                                 int(accumulate), comp, ss[i])
+                    assert rc == 0, ssd.ssd_last_error()
+        torch.cuda.synchronize()
+        for p in range(0, p_timed):
+            mb_step(p)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for p in range(p_timed, wl.n_total):
+            mb_step(p)
+        torch.cuda.synchronize()
+        dtm = time.perf_counter() - t0
+        result["two_half_batches_two_streams"] = {
+            "value": wl.prompts * K_steps / dtm, "unit": "tokens/s", "ms_per_step": dtm / K_steps * 1e3,
+            "launches_per_step": ns * wl.L, "whole_step_GBps": head["algorithmic_GB_per_step"] / (dtm / K_steps),
+            "frac_of_hbm_peak": head["algorithmic_GB_per_step"] / (dtm / K_steps) / HBM_PEAK_GBS,
+            "note": "same step, the sequences split into two caches of %d whose per-layer launches go to two streams: the start and "
+                    "the tail of one half's launch overlap the other's; each half keeps its layer order" % Bm}
+        del caches
+
+    # ---- prompt scoring (accumulated causal scores of the n0 prompt tokens), one launch per layer ------------
+    if not args.no_prefill:
+        n0 = wl.n0
+        Qp = [workload.dense_layout(data["q"][:n0, l:l + 1])[0].contiguous() for l in range(wl.L)]
+        Kp = [workload.dense_layout(data["k"][:n0, l:l + 1])[0].contiguous() for l in range(wl.L)]
+        sc = torch.empty((wl.B, wl.H, n0), device=dev)
+        units = wl.B * wl.H
+
+        def prefill_pass():
+            for l in range(wl.L):
+                ssd.ssd_prefill_scores(Qp[l], Kp[l], units, n0, wl.d, wl.dtype, sc)
+        prefill_pass()
+        torch.cuda.synchronize()
+        reps = 5
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            prefill_pass()
+        torch.cuda.synchronize()
+        tp = (time.perf_counter() - t0) / reps
+        pf_bytes = wl.L * units * (2 * n0 * row_bytes(wl) + 4 * n0)
+        nb = (n0 + 31) // 32
+        pf_flops = wl.L * units * 2 * (nb * (nb + 1) // 2) * 2 * 32 * 32 * wl.d      # tiles on or below the diagonal, two sweeps
+        result["prefill_scores"] = {"ms_all_layers": tp * 1e3, "us_per_layer_launch": tp * 1e6 / wl.L, "prompt_tokens": n0,
+                                    "algorithmic_GB": pf_bytes / 1e9, "GBps": pf_bytes / 1e9 / tp,
+                                    "frac_of_hbm_peak": pf_bytes / 1e9 / tp / HBM_PEAK_GBS, "mfma_TFLOPs": pf_flops / 1e12 / tp,
+                                    "kind": "ssd_prefill_scores, Q and K of the prompt read once, fp32 column sums written"}
+        del Qp, Kp
 
     # ---- the same steps through the dense full-cache kernel -----------------------------------------------
     if not args.no_dense:

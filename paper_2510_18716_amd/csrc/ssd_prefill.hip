@@ -12,10 +12,11 @@
 // k-slice selected by (l div 32), the same slice for Q and K, so no transpose or LDS staging is
 // needed.  A tile's 32 x 32 results sit 16 per lane: column = l mod 32, row = 8*(v/4) + 4*(l/32) + v%4.
 //
-// One workgroup of four waves per unit; wave w owns query blocks w, w+4, ...  Per query block two
+// One workgroup per unit, of as many waves as the prompt has blocks of 32 queries (at most four); wave
+// w owns query blocks w, w + waves, ...  Per query block two
 // sweeps over the key blocks up to the diagonal: the first keeps a running max and sum per lane and
 // result register and merges them over the 32 lanes of a row once at its end, the second recomputes
-// the tile, normalises and adds the tile's column sums into a wave-private LDS array; the four
+// the tile, normalises and adds the tile's column sums into a wave-private LDS array; the waves'
 // arrays are added in a fixed order at the end (bit-reproducible, no atomics).
 // Bound: HBM for the short prompts this is meant for (Q and K of a unit are read once from HBM,
 // re-reads of K tiles hit in L2); at n = 64, d = 128 a unit does 1 MFLOP on 32 KB.
@@ -83,8 +84,9 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void prefill_scores_kernel(PrefillArgs a) {
     typedef typename Mma<T>::Frag Frag;
     constexpr int NK = D / Mma<T>::KSTEP;
-    extern __shared__ float colsum[];                      // [4][n]
+    extern __shared__ float colsum[];                      // [waves][n]
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int waves = blockDim.x >> 6;
     const int lane = threadIdx.x & 63;
     const int half = lane >> 5;
     const int l32 = lane & 31;
@@ -97,7 +99,7 @@ __global__ __launch_bounds__(256) void prefill_scores_kernel(PrefillArgs a) {
     // (no barrier needed: only this wave touches `mine` until the final sum)
 
     const int n_blocks = (n + 31) / 32;
-    for (int qb = w; qb < n_blocks; qb += 4) {
+    for (int qb = w; qb < n_blocks; qb += waves) {
         int qrow = qb * 32 + l32;
         if (qrow > n - 1) qrow = n - 1;                    // rows past the end repeat the last one; masked below
         Frag qa[NK];
@@ -159,8 +161,11 @@ __global__ __launch_bounds__(256) void prefill_scores_kernel(PrefillArgs a) {
     }
     __syncthreads();
     float *out = a.score_out + (size_t)blockIdx.x * (size_t)n;
-    for (int j = threadIdx.x; j < n; j += 256)
-        out[j] = ((colsum[j] + colsum[n + j]) + colsum[2 * n + j]) + colsum[3 * n + j];
+    for (int j = threadIdx.x; j < n; j += blockDim.x) {
+        float t = colsum[j];
+        for (int x = 1; x < waves; ++x) t += colsum[x * n + j];
+        out[j] = t;
+    }
 }
 
 }  // namespace ssd
@@ -184,9 +189,11 @@ extern "C" int ssd_prefill_scores(const void *Q, const void *K, int n_units, int
     a.n = n_src;
     a.row_bytes = d * (dtype == SSD_F32 ? 4 : 2);
     a.qscale = (softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d)) * LOG2E;
-    const size_t lds = 4 * (size_t)n_src * sizeof(float);
+    const int n_blocks = (n_src + 31) / 32;
+    const int waves = n_blocks < 4 ? n_blocks : 4;
+    const size_t lds = (size_t)waves * (size_t)n_src * sizeof(float);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid((unsigned)n_units), block(256);
+    const dim3 grid((unsigned)n_units), block(64u * waves);
     if (dtype == SSD_BF16) {
         if (d == 128) hipLaunchKernelGGL((prefill_scores_kernel<bf16_t, 128>), grid, block, lds, s, a);
         else hipLaunchKernelGGL((prefill_scores_kernel<bf16_t, 64>), grid, block, lds, s, a);

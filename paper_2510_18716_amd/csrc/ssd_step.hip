@@ -45,10 +45,9 @@ struct StepArgs {
 
 // One wave per unit, WPB units (consecutive heads of one sequence and layer) per workgroup;
 // grid = (ceil(H / WPB), B, layers of the launch).  Nothing below needs a workgroup barrier.
-#ifdef SSD_PROBE
-#define SSD_ST16(ptr, val) do { const uint4 _v = (val); uint4 *_p = reinterpret_cast<uint4 *>(ptr); \
-    if (a.probe / 100 == 1) {} else if (a.probe / 100 == 3) { asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" :: "v"(_p), "v"(_v) : "memory"); } else if (a.probe / 100 == 2) { __builtin_nontemporal_store(_v.x, &_p->x); __builtin_nontemporal_store(_v.y, &_p->y); __builtin_nontemporal_store(_v.z, &_p->z); __builtin_nontemporal_store(_v.w, &_p->w); } else *_p = _v; } while (0)
-#define SSD_ST4(ptr, val) do { if (a.probe / 100 == 1) {} else if (a.probe / 100 == 3) { asm volatile("global_store_dword %0, %1, off sc0 sc1" :: "v"(ptr), "v"(val) : "memory"); } else if (a.probe / 100 == 2) __builtin_nontemporal_store((val), (ptr)); else *(ptr) = (val); } while (0)
+#ifdef SSD_PROBE      // probe / 100 == 1: the kernel with its stores left out (what the write path costs)
+#define SSD_ST16(ptr, val) do { if (a.probe / 100 != 1) *reinterpret_cast<uint4 *>(ptr) = (val); } while (0)
+#define SSD_ST4(ptr, val) do { if (a.probe / 100 != 1) *(ptr) = (val); } while (0)
 #else
 #define SSD_ST16(ptr, val) (*reinterpret_cast<uint4 *>(ptr) = (val))
 #define SSD_ST4(ptr, val) (*(ptr) = (val))
@@ -262,11 +261,11 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
 
 struct Tuning {
     int ch;      // wave-wide loads of K (and of V) per chunk; two chunks are in flight per wave (0 = by launch size)
-    int wpb;     // units (waves) per workgroup
+    int wpb;     // units (waves) per workgroup (0 = by launch size)
 };
 
 static int g_probe = 0;
-static constexpr Tuning DEFAULT_TUNE = {0, 4};
+static constexpr Tuning DEFAULT_TUNE = {0, 0};
 static Tuning g_tune = DEFAULT_TUNE;
 
 // Largest candidate count the fused entry point ranks with a single wave; beyond it the stand-alone
@@ -282,13 +281,20 @@ static void launch_one(const StepArgs &a, dim3 blocks, size_t lds, bool fused, h
 template <typename T, int D>
 static hipError_t launch_step(StepArgs &a, int H, int max_type_heads, int B, int layers, bool fused, int M, hipStream_t s) {
     const int n_old = a.c - a.R, n_cand = a.m + n_old;
-    // Few units (one layer of a modest batch): every wave is resident at once and shallow queues finish
-    // sooner; many units: waves come and go, deeper per-wave queues keep HBM busier.
-    int ch = g_tune.ch ? g_tune.ch : ((long long)H * B * layers <= 16384 ? 2 : 4);
-    int wpb = g_tune.wpb;
+    // Launch shape by the number of units (measured on the 7B- and 1B-shaped workloads).  Up to half of
+    // what the chip holds at once (256 CUs x 16 waves): the launch is latency-bound, so spread the waves
+    // over as many CUs as possible (one unit per workgroup) and give each a deep load queue.  Around one
+    // resident round: shallow queues finish sooner.  Many rounds: waves come and go, deeper per-wave
+    // queues keep HBM busier.
+    const long long units = (long long)H * B * layers;
+    int ch = g_tune.ch ? g_tune.ch : (units <= 2048 || units > 16384 ? 4 : 2);
+    int wpb = g_tune.wpb ? g_tune.wpb : (units <= 2048 ? 1 : 4);
     a.wave_lds = (int)(((size_t)a.zcap * 4 + (a.do_compress ? select_lds_bytes(M, n_cand, n_old) + 16 : 0) + 15) / 16 * 16);
     while (wpb > 1 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;
-    const size_t lds = (size_t)wpb * a.wave_lds;
+    size_t lds = (size_t)wpb * a.wave_lds;
+#ifdef SSD_PROBE
+    if ((size_t)(g_probe / 1000) * 1024 > lds) lds = (size_t)(g_probe / 1000) * 1024;   // occupancy experiments: pad the workgroup's LDS
+#endif
     const dim3 blocks((unsigned)((max_type_heads + wpb - 1) / wpb), (unsigned)B, (unsigned)(2 * layers));
 #define SSD_CASE(CH_, WPB_) if (ch == CH_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_>(a, blocks, lds, fused, s); return hipGetLastError(); }
     if constexpr (sizeof(T) == 2 && D == 128) {       // the shape the sweeps are run on has every variant
@@ -390,7 +396,7 @@ extern "C" int ssd_tune_attend(int ch, int wpb, int probe) {
     g_probe = probe;
     if (ch == 0 && wpb == 0) { g_tune = DEFAULT_TUNE; return SSD_OK; }
 #ifndef SSD_PROBE
-    if ((ch != 0 && ch != 1 && ch != 2 && ch != 4) || (wpb != 1 && wpb != 2 && wpb != 4)) return SSD_ERR_INVALID_ARG;
+    if ((ch != 0 && ch != 1 && ch != 2 && ch != 4) || (wpb != 0 && wpb != 1 && wpb != 2 && wpb != 4)) return SSD_ERR_INVALID_ARG;
 #endif
     g_tune.ch = ch; g_tune.wpb = wpb;
     return SSD_OK;

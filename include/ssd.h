@@ -66,7 +66,8 @@ typedef enum ssd_status {
 
 /*
  * Shape and policy parameters (Algorithm 1 "Parameter" line; Sec. 3.3).
- * One config describes one cache: all layers share W, S, M, R, C.
+ * One config describes one cache: all layers share S, R, C, and also W and M
+ * unless ssd_cache_init_layered gives those per layer.
  */
 typedef struct ssd_config {
     int32_t n_layers;      /* L                                                            */
@@ -106,6 +107,25 @@ size_t ssd_cache_bytes(const ssd_config *cfg, const uint8_t *head_type);
  */
 int ssd_cache_init(const ssd_config *cfg, const uint8_t *head_type, void *dev_mem,
                    size_t bytes, ssd_cache **out);
+
+/*
+ * The same two calls with a window and a budget per layer (layer-wise budget
+ * allocation: Sec. 3.3 finds the share of long-range attention to fall from
+ * the lower to the upper layers, and Sec. 5 "Integration with Other
+ * Compression Techniques" names layer-wise allocation as a combination).
+ *   window, budget : host int32 [L], or NULL for cfg->window / cfg->budget in
+ *                    every layer; each entry obeys the limits of the config
+ *                    field it replaces.  The arrays are copied.
+ * Layers of different W or M have units of different size and go to separate
+ * launches; everything else (call order, counters, errors) is unchanged.
+ */
+size_t ssd_cache_bytes_layered(const ssd_config *cfg, const uint8_t *head_type,
+                               const int32_t *window, const int32_t *budget);
+int ssd_cache_init_layered(const ssd_config *cfg, const uint8_t *head_type,
+                           const int32_t *window, const int32_t *budget, void *dev_mem,
+                           size_t bytes, ssd_cache **out);
+/* Window and budget of one layer (either output may be NULL). */
+int ssd_cache_layer_budget(const ssd_cache *cache, int layer, int32_t *window, int32_t *budget);
 
 /* Free the descriptor (not dev_mem).  NULL is allowed. */
 void ssd_cache_free(ssd_cache *cache);
@@ -237,7 +257,7 @@ int ssd_decode_step(ssd_cache *cache, int layer_begin, int layer_end, const void
  *   pos   : dev int32 [B, H, slots]  absolute position held by each slot, -1 if unused
  *   score : dev float [B, H, slots]  accumulated score of the slot (0 for spatial heads)
  *   count : dev int32 [B, H]         retained tokens of the head
- * slots = ssd_cache_export_slots(cache) = max(S + W, M + C).  Any of the three may be NULL.
+ * slots = ssd_cache_export_slots(cache) = max(S + W, M + C) over all layers.  Any of the three may be NULL.
  */
 int ssd_cache_export_slots(const ssd_cache *cache);
 int ssd_cache_export(ssd_cache *cache, int layer, int32_t *pos, int32_t *count,

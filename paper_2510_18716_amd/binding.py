@@ -43,6 +43,12 @@ lib.ssd_cache_bytes.argtypes = [C.POINTER(SsdConfig), _vp]
 lib.ssd_cache_bytes.restype = C.c_size_t
 lib.ssd_cache_init.argtypes = [C.POINTER(SsdConfig), _vp, _vp, C.c_size_t, C.POINTER(_vp)]
 lib.ssd_cache_init.restype = C.c_int
+lib.ssd_cache_bytes_layered.argtypes = [C.POINTER(SsdConfig), _vp, _vp, _vp]
+lib.ssd_cache_bytes_layered.restype = C.c_size_t
+lib.ssd_cache_init_layered.argtypes = [C.POINTER(SsdConfig), _vp, _vp, _vp, _vp, C.c_size_t, C.POINTER(_vp)]
+lib.ssd_cache_init_layered.restype = C.c_int
+lib.ssd_cache_layer_budget.argtypes = [_vp, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+lib.ssd_cache_layer_budget.restype = C.c_int
 lib.ssd_cache_free.argtypes = [_vp]
 lib.ssd_cache_free.restype = None
 lib.ssd_cache_reset.argtypes = [_vp]
@@ -140,9 +146,21 @@ def make_config(L, B, H, d, dtype, W, S, M, R, C_, softmax_scale=0.0, spatial_ro
     return cfg
 
 
-def ssd_cache_bytes(cfg: SsdConfig, head_type: np.ndarray) -> int:
+def _per_layer(x, L):
+    """Host int32 [L] array for a per-layer window / budget list, or None."""
+    if x is None:
+        return None
+    a = np.ascontiguousarray(x, dtype=np.int32)
+    if a.shape != (L,):
+        raise ValueError("per-layer array must have one entry per layer")
+    return a
+
+
+def ssd_cache_bytes(cfg: SsdConfig, head_type: np.ndarray, window=None, budget=None) -> int:
     ht = np.ascontiguousarray(head_type, dtype=np.uint8)
-    return lib.ssd_cache_bytes(C.byref(cfg), ht.ctypes.data)
+    w, m = _per_layer(window, cfg.n_layers), _per_layer(budget, cfg.n_layers)
+    return lib.ssd_cache_bytes_layered(C.byref(cfg), ht.ctypes.data, None if w is None else w.ctypes.data,
+                                       None if m is None else m.ctypes.data)
 
 
 class Cache:
@@ -153,10 +171,13 @@ class Cache:
     on a machine without a GPU.
     """
 
-    def __init__(self, cfg: SsdConfig, head_type: np.ndarray, device="cuda"):
+    def __init__(self, cfg: SsdConfig, head_type: np.ndarray, device="cuda", window=None, budget=None):
+        """window, budget: optional per-layer lists [L] (ssd_cache_init_layered)."""
         self.cfg = cfg
         self.head_type = np.ascontiguousarray(head_type, dtype=np.uint8)
-        nbytes = lib.ssd_cache_bytes(C.byref(cfg), self.head_type.ctypes.data)
+        w, m = _per_layer(window, cfg.n_layers), _per_layer(budget, cfg.n_layers)
+        wp, mp = (None if w is None else w.ctypes.data), (None if m is None else m.ctypes.data)
+        nbytes = lib.ssd_cache_bytes_layered(C.byref(cfg), self.head_type.ctypes.data, wp, mp)
         if nbytes == 0:
             raise SsdError(SSD_ERR_INVALID_ARG, "ssd_cache_bytes")
         self.head_type = self.head_type.reshape(cfg.n_layers, cfg.n_heads)
@@ -168,7 +189,8 @@ class Cache:
         else:
             self.mem = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
             base = (self.mem.data_ptr() + 255) // 256 * 256
-        _check(lib.ssd_cache_init(C.byref(cfg), self.head_type.ctypes.data, base, nbytes, C.byref(self._h)), "ssd_cache_init")
+        _check(lib.ssd_cache_init_layered(C.byref(cfg), self.head_type.ctypes.data, wp, mp, base, nbytes, C.byref(self._h)),
+               "ssd_cache_init")
         if device is None:
             _check(lib.ssd_cache_set_launch(self._h, 0), "ssd_cache_set_launch")
         self.torch_dtype = torch.bfloat16 if cfg.dtype == SSD_BF16 else torch.float32
@@ -190,6 +212,12 @@ class Cache:
         out = (C.c_int32 * 4)()
         _check(lib.ssd_cache_layer_state(self._h, layer, C.byref(out)), "ssd_cache_layer_state")
         return tuple(out)
+
+    def layer_budget(self, layer: int):
+        """(W, M) of one layer."""
+        w, m = C.c_int32(0), C.c_int32(0)
+        _check(lib.ssd_cache_layer_budget(self._h, layer, C.byref(w), C.byref(m)), "ssd_cache_layer_budget")
+        return w.value, m.value
 
     def layer_window(self, layer: int) -> int:
         out = C.c_int32(0)

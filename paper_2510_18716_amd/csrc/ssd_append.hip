@@ -69,7 +69,7 @@ extern "C" int ssd_append_token(ssd_cache *cache, int layer_begin, int layer_end
         const LayerState st = cache->st[lb];
         if (cache->launch_enabled) {
             AppendArgs a;
-            a.g = make_geom(cache);
+            a.g = make_geom(cache, lb);
             a.k_new = static_cast<const char *>(k_new);
             a.v_new = static_cast<const char *>(v_new);
             fill_launch_meta(cache, lb, le, &a.lm);
@@ -77,8 +77,8 @@ extern "C" int ssd_append_token(ssd_cache *cache, int layer_begin, int layer_end
             a.n_units = (le - lb) * BH;
             a.lpr = a.g.row_bytes / 16;
             a.pos = st.n;
-            a.slot_sp = spatial_slot(cache, st.n);
-            a.slot_se = cf.budget + (st.base + st.c) % cf.stage_cap;
+            a.slot_sp = spatial_slot(cache, lb, st.n);
+            a.slot_se = cache->Ml[lb] + (st.base + st.c) % cf.stage_cap;
             const long long threads = (long long)a.n_units * 2 * a.lpr;
             const unsigned blocks = (unsigned)((threads + 255) / 256);
             hipLaunchKernelGGL(append_kernel, dim3(blocks), dim3(256), 0, s, a);

@@ -44,7 +44,7 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 static int esize_of(int dtype) { return dtype == SSD_F32 ? 4 : dtype == SSD_BF16 ? 2 : 0; }
 
-static int validate(const ssd_config *c, const uint8_t *head_type) {
+static int validate(const ssd_config *c, const uint8_t *head_type, const int32_t *window, const int32_t *budget) {
     if (!c || !head_type) return fail(SSD_ERR_INVALID_ARG, "config or head_type is NULL");
     if (c->n_layers < 1 || c->n_layers > 1024) return fail(SSD_ERR_INVALID_ARG, "n_layers=%d outside 1..1024", c->n_layers);
     if (c->n_seqs < 1 || c->n_seqs > 65535) return fail(SSD_ERR_INVALID_ARG, "n_seqs=%d outside 1..65535", c->n_seqs);
@@ -66,19 +66,32 @@ static int validate(const ssd_config *c, const uint8_t *head_type) {
     const size_t n = (size_t)c->n_layers * c->n_heads;
     for (size_t i = 0; i < n; ++i)
         if (head_type[i] > 1) return fail(SSD_ERR_INVALID_ARG, "head_type[%zu]=%d is neither SSD_SPATIAL nor SSD_SEMANTIC", i, head_type[i]);
+    for (int l = 0; l < c->n_layers; ++l) {
+        if (window) {
+            if (window[l] < 1) return fail(SSD_ERR_INVALID_ARG, "window[%d]=%d must be >= 1", l, window[l]);
+            if ((int64_t)c->n_init_sink + window[l] + (c->spatial_row_buffer ? c->stage_cap : 0) > 65536)
+                return fail(SSD_ERR_INVALID_ARG, "window[%d]=%d: a spatial head would need more than 65536 slots", l, window[l]);
+        }
+        if (budget) {
+            if (budget[l] < 1) return fail(SSD_ERR_INVALID_ARG, "budget[%d]=%d must be >= 1", l, budget[l]);
+            if ((int64_t)budget[l] + c->stage_cap > 4096) return fail(SSD_ERR_INVALID_ARG, "budget[%d] + C = %lld exceeds 4096", l, (long long)budget[l] + c->stage_cap);
+        }
+    }
     return SSD_OK;
 }
 
 // Fills ldesc (if non-null) and returns the total byte size.
-static size_t plan_layout(const ssd_config *c, const uint8_t *head_type, std::vector<LayerDesc> *ldesc) {
+static size_t plan_layout(const ssd_config *c, const uint8_t *head_type, const int32_t *window, const int32_t *budget,
+                          std::vector<LayerDesc> *ldesc) {
     const int L = c->n_layers, H = c->n_heads;
     const size_t row = (size_t)c->head_dim * esize_of(c->dtype);
-    const size_t unit_sp = 2 * (size_t)(c->n_init_sink + c->window + (c->spatial_row_buffer ? c->stage_cap : 0)) * row;
-    const size_t unit_se = 2 * (size_t)(c->budget + c->stage_cap) * row;
-    const size_t slots = (size_t)c->budget + c->stage_cap;
     size_t off = 0;
     if (ldesc) ldesc->resize(L);
     for (int l = 0; l < L; ++l) {
+        const int W = window ? window[l] : c->window, M = budget ? budget[l] : c->budget;
+        const size_t unit_sp = 2 * (size_t)(c->n_init_sink + W + (c->spatial_row_buffer ? c->stage_cap : 0)) * row;
+        const size_t unit_se = 2 * (size_t)(M + c->stage_cap) * row;
+        const size_t slots = (size_t)M + c->stage_cap;
         LayerDesc m;
         m.sem_mask[0] = m.sem_mask[1] = 0;
         m.n_sp = m.n_se = 0;
@@ -110,14 +123,14 @@ int check_layers(const ssd_cache *c, int lb, int le) {
     return SSD_OK;
 }
 
-Geom make_geom(const ssd_cache *c) {
+Geom make_geom(const ssd_cache *c, int l) {
     Geom g;
     g.base = c->dev;
     g.B = c->cfg.n_seqs;
     g.H = c->cfg.n_heads;
     g.S = c->cfg.n_init_sink;
-    g.W = c->cfg.window;
-    g.M = c->cfg.budget;
+    g.W = c->Wl[l];
+    g.M = c->Ml[l];
     g.C = c->cfg.stage_cap;
     g.RW = g.W + (c->cfg.spatial_row_buffer ? g.C : 0);
     g.row_bytes = c->cfg.head_dim * c->esize;
@@ -141,21 +154,21 @@ void apply_compress_counters(ssd_cache *c, int l) {
     if (!has_buffer(c, l) || old <= 0) return;
     if (c->ldesc[l].n_se > 0) {
         const int tot = x.m + old;
-        x.m = tot < cf.budget ? tot : cf.budget;
+        x.m = tot < c->Ml[l] ? tot : c->Ml[l];
     }
     x.base = (x.base + old) % cf.stage_cap;
     x.c = cf.recent;
 }
 
-int spatial_slot(const ssd_cache *c, int p) {
+int spatial_slot(const ssd_cache *c, int l, int p) {
     const int S = c->cfg.n_init_sink;
-    const int RW = c->cfg.window + (c->cfg.spatial_row_buffer ? c->cfg.stage_cap : 0);
+    const int RW = c->Wl[l] + (c->cfg.spatial_row_buffer ? c->cfg.stage_cap : 0);
     return p < S ? p : S + (p - S) % RW;
 }
 
-Segs spatial_segs(const ssd_cache *c, const LayerState &st) {
+Segs spatial_segs(const ssd_cache *c, int l, const LayerState &st) {
     Segs s = {{0, 0, 0}, {0, 0, 0}, 0};
-    const int S = c->cfg.n_init_sink, W = c->cfg.window;
+    const int S = c->cfg.n_init_sink, W = c->Wl[l];
     if (!c->cfg.spatial_row_buffer) {
         // Algorithm 1: the ring fills front to back, so the valid slots are always a prefix
         const int cap = S + W;
@@ -176,9 +189,9 @@ Segs spatial_segs(const ssd_cache *c, const LayerState &st) {
     return s;
 }
 
-Segs semantic_segs(const ssd_cache *c, const LayerState &st) {
+Segs semantic_segs(const ssd_cache *c, int l, const LayerState &st) {
     Segs s = {{0, 0, 0}, {0, 0, 0}, 0};
-    const int M = c->cfg.budget, C = c->cfg.stage_cap;
+    const int M = c->Ml[l], C = c->cfg.stage_cap;
     s.start[0] = 0;
     s.len[0] = st.m;
     const int first = st.base + st.c <= C ? st.c : C - st.base;   // run up to the end of the ring
@@ -190,10 +203,10 @@ Segs semantic_segs(const ssd_cache *c, const LayerState &st) {
     return s;
 }
 
-Segs spatial_segs_fused(const ssd_cache *c, const LayerState &before, const LayerState &after, int new_slot) {
-    if (c->cfg.spatial_row_buffer) return spatial_segs(c, before);   // the new token's slot is never a retained one
+Segs spatial_segs_fused(const ssd_cache *c, int l, const LayerState &before, const LayerState &after, int new_slot) {
+    if (c->cfg.spatial_row_buffer) return spatial_segs(c, l, before);   // the new token's slot is never a retained one
     // Algorithm 1: the new token overwrites the oldest ring slot; stream the prefix around it
-    Segs s = spatial_segs(c, after);
+    Segs s = spatial_segs(c, l, after);
     const int end = s.len[0];
     if (new_slot < 0 || new_slot >= end) return s;
     s.start[0] = 0;            s.len[0] = new_slot;
@@ -202,11 +215,21 @@ Segs spatial_segs_fused(const ssd_cache *c, const LayerState &before, const Laye
     return s;
 }
 
+static bool same_geom(const ssd_cache *c, int a, int b) { return c->Wl[a] == c->Wl[b] && c->Ml[a] == c->Ml[b]; }
+
 int same_state_run(const ssd_cache *c, int lb, int le) {
     int l = lb + 1;
     // layers with and without semantic heads never share a launch: only the former have a row buffer
     const bool buf = has_buffer(c, lb), has_se = c->ldesc[lb].n_se > 0;
-    while (l < le && l - lb < LMAX && c->st[l] == c->st[lb] && has_buffer(c, l) == buf && (c->ldesc[l].n_se > 0) == has_se) ++l;
+    while (l < le && l - lb < LMAX && c->st[l] == c->st[lb] && same_geom(c, l, lb) && has_buffer(c, l) == buf &&
+           (c->ldesc[l].n_se > 0) == has_se)
+        ++l;
+    return l;
+}
+
+int same_geom_run(const ssd_cache *c, int lb, int le) {
+    int l = lb + 1;
+    while (l < le && l - lb < LMAX && same_geom(c, l, lb)) ++l;
     return l;
 }
 
@@ -257,17 +280,24 @@ using namespace ssd;
 
 extern "C" {
 
-size_t ssd_cache_bytes(const ssd_config *cfg, const uint8_t *head_type) {
-    clear_error();
-    if (validate(cfg, head_type) != SSD_OK) return 0;
-    return plan_layout(cfg, head_type, nullptr);
-}
+size_t ssd_cache_bytes(const ssd_config *cfg, const uint8_t *head_type) { return ssd_cache_bytes_layered(cfg, head_type, nullptr, nullptr); }
 
 int ssd_cache_init(const ssd_config *cfg, const uint8_t *head_type, void *dev_mem, size_t bytes, ssd_cache **out) {
+    return ssd_cache_init_layered(cfg, head_type, nullptr, nullptr, dev_mem, bytes, out);
+}
+
+size_t ssd_cache_bytes_layered(const ssd_config *cfg, const uint8_t *head_type, const int32_t *window, const int32_t *budget) {
+    clear_error();
+    if (validate(cfg, head_type, window, budget) != SSD_OK) return 0;
+    return plan_layout(cfg, head_type, window, budget, nullptr);
+}
+
+int ssd_cache_init_layered(const ssd_config *cfg, const uint8_t *head_type, const int32_t *window, const int32_t *budget,
+                           void *dev_mem, size_t bytes, ssd_cache **out) {
     clear_error();
     if (!out) return fail(SSD_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
-    int rc = validate(cfg, head_type);
+    int rc = validate(cfg, head_type, window, budget);
     if (rc != SSD_OK) return rc;
     if (!dev_mem) return fail(SSD_ERR_INVALID_ARG, "dev_mem is NULL");
     if (!aligned(dev_mem, 256)) return fail(SSD_ERR_INVALID_ARG, "dev_mem is not 256-byte aligned");
@@ -277,7 +307,11 @@ int ssd_cache_init(const ssd_config *cfg, const uint8_t *head_type, void *dev_me
     c->esize = esize_of(cfg->dtype);
     c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
     c->head_type.assign(head_type, head_type + (size_t)cfg->n_layers * cfg->n_heads);
-    const size_t need = plan_layout(cfg, head_type, &c->ldesc);
+    c->Wl.assign(cfg->n_layers, cfg->window);
+    c->Ml.assign(cfg->n_layers, cfg->budget);
+    if (window) c->Wl.assign(window, window + cfg->n_layers);
+    if (budget) c->Ml.assign(budget, budget + cfg->n_layers);
+    const size_t need = plan_layout(cfg, head_type, window, budget, &c->ldesc);
     if (bytes < need) {
         delete c;
         return fail(SSD_ERR_INVALID_ARG, "dev_mem holds %zu bytes, the cache needs %zu", bytes, need);
@@ -325,11 +359,25 @@ int ssd_cache_set_launch(ssd_cache *cache, int enable) {
     return SSD_OK;
 }
 
+int ssd_cache_layer_budget(const ssd_cache *cache, int layer, int32_t *window, int32_t *budget) {
+    clear_error();
+    int rc = check_layers(cache, layer, layer + 1);
+    if (rc != SSD_OK) return rc;
+    if (window) *window = cache->Wl[layer];
+    if (budget) *budget = cache->Ml[layer];
+    return SSD_OK;
+}
+
 int ssd_cache_export_slots(const ssd_cache *cache) {
     if (!cache) return 0;
-    const int a = cache->cfg.n_init_sink + cache->cfg.window + (cache->cfg.spatial_row_buffer ? cache->cfg.stage_cap : 0);
-    const int b = cache->cfg.budget + cache->cfg.stage_cap;
-    return a > b ? a : b;
+    int slots = 0;
+    for (int l = 0; l < cache->cfg.n_layers; ++l) {
+        const int a = cache->cfg.n_init_sink + cache->Wl[l] + (cache->cfg.spatial_row_buffer ? cache->cfg.stage_cap : 0);
+        const int b = cache->Ml[l] + cache->cfg.stage_cap;
+        slots = a > slots ? a : slots;
+        slots = b > slots ? b : slots;
+    }
+    return slots;
 }
 
 int ssd_cache_export(ssd_cache *cache, int layer, int32_t *pos, int32_t *count, float *score, void *stream) {
@@ -340,12 +388,12 @@ int ssd_cache_export(ssd_cache *cache, int layer, int32_t *pos, int32_t *count, 
     if (!cache->launch_enabled) return SSD_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const LayerState st = cache->st[layer];
-    const Segs se = semantic_segs(cache, st);
+    const Segs se = semantic_segs(cache, layer, st);
     const int units = cache->cfg.n_seqs * cache->cfg.n_heads;
-    const int S = cache->cfg.n_init_sink, W = cache->cfg.window;
+    const int S = cache->cfg.n_init_sink, W = cache->Wl[layer];
     const int ref = cache->cfg.spatial_row_buffer ? st.nc : st.n;      // Algorithm 1: the window always ends at n
     const int lo = ref - W > S ? ref - W : S;
-    hipLaunchKernelGGL(export_kernel, dim3(units), dim3(64), 0, s, make_geom(cache), cache->ldesc[layer], st, se, lo,
+    hipLaunchKernelGGL(export_kernel, dim3(units), dim3(64), 0, s, make_geom(cache, layer), cache->ldesc[layer], st, se, lo,
                        ssd_cache_export_slots(cache), pos, count, score);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "export launch");

@@ -144,7 +144,7 @@ int launch_compress_inplace(const ssd_cache *cache, int lb, int le, const LayerS
     const ssd_config &cf = cache->cfg;
     const int n_old = st.c - cf.recent;
     CompressArgs a;
-    a.g = make_geom(cache);
+    a.g = make_geom(cache, lb);
     fill_launch_meta(cache, lb, le, &a.lm);
     a.m = st.m;
     a.c = st.c;
@@ -153,7 +153,7 @@ int launch_compress_inplace(const ssd_cache *cache, int lb, int le, const LayerS
     a.lpr = cf.head_dim * cache->esize / 16;
     const int n_cand = st.m + n_old;
     const unsigned units = (unsigned)((le - lb) * cf.n_seqs * cf.n_heads);
-    const size_t lds = select_lds_bytes(cf.budget, n_cand, n_old);
+    const size_t lds = select_lds_bytes(cache->Ml[lb], n_cand, n_old);
     if (n_cand <= 192)
         hipLaunchKernelGGL((compress_inplace_kernel<64>), dim3(units), dim3(64), lds, s, a);
     else
@@ -185,10 +185,10 @@ extern "C" int ssd_compress_kv(ssd_cache *cache, int layer_begin, int layer_end,
         const int n_rec = n_src < cf.recent ? n_src : cf.recent;
         const int n_cand = n_src - n_rec;
         if (cache->launch_enabled) {
-            for (int lb = layer_begin; lb < layer_end; lb += LMAX) {
-                const int le = lb + LMAX < layer_end ? lb + LMAX : layer_end;
+            for (int lb = layer_begin, le; lb < layer_end; lb = le) {
+                le = same_geom_run(cache, lb, layer_end);
                 DenseSrcArgs a;
-                a.g = make_geom(cache);
+                a.g = make_geom(cache, lb);
                 fill_launch_meta(cache, lb, le, &a.lm);
                 a.K_src = static_cast<const char *>(K_src);
                 a.V_src = static_cast<const char *>(V_src);
@@ -197,7 +197,7 @@ extern "C" int ssd_compress_kv(ssd_cache *cache, int layer_begin, int layer_end,
                 a.n_src = n_src;
                 a.R = cf.recent;
                 a.lpr = lpr;
-                const size_t lds = sizeof(unsigned long long) * (size_t)n_cand + sizeof(int) * (size_t)cf.budget + (size_t)n_cand + 16;
+                const size_t lds = sizeof(unsigned long long) * (size_t)n_cand + sizeof(int) * (size_t)cache->Ml[lb] + (size_t)n_cand + 16;
                 hipLaunchKernelGGL((compress_dense_kernel<256>), dim3((unsigned)((le - lb) * BH)), dim3(256), lds, s, a);
                 hipError_t e = hipGetLastError();
                 if (e != hipSuccess) return hip_fail(e, "dense-source compression launch");
@@ -206,7 +206,7 @@ extern "C" int ssd_compress_kv(ssd_cache *cache, int layer_begin, int layer_end,
         for (int l = layer_begin; l < layer_end; ++l) {
             LayerState &st = cache->st[l];
             st.n = n_src;
-            st.m = cache->ldesc[l].n_se > 0 ? (n_cand < cf.budget ? n_cand : cf.budget) : 0;
+            st.m = cache->ldesc[l].n_se > 0 ? (n_cand < cache->Ml[l] ? n_cand : cache->Ml[l]) : 0;
             st.c = has_buffer(cache, l) ? n_rec : 0;
             st.base = 0;
             st.nc = n_src;

@@ -33,7 +33,7 @@ struct LaunchMeta {
     LayerDesc layer[LMAX];
 };
 
-// Geometry common to all layers.
+// Geometry common to all layers of one launch (layers with different W or M go to different launches).
 struct Geom {
     char *base;               // device memory of the cache
     int32_t B, H, S, W, M, C;
@@ -68,6 +68,7 @@ struct ssd_cache {
     int esize;
     std::vector<uint8_t> head_type;           // [L*H]
     std::vector<ssd::LayerDesc> ldesc;        // [L]
+    std::vector<int32_t> Wl, Ml;              // [L] window and budget of each layer (cfg.window / cfg.budget unless given per layer)
     std::vector<ssd::LayerState> st;          // [L]
     char *dev;
     size_t bytes;
@@ -83,21 +84,23 @@ void clear_error();
 
 // host helpers implemented in ssd_cache.hip
 int check_layers(const ssd_cache *c, int lb, int le);
-Geom make_geom(const ssd_cache *c);
+Geom make_geom(const ssd_cache *c, int l);                                     // geometry of layer l
 void fill_launch_meta(const ssd_cache *c, int lb, int le, LaunchMeta *out);   // le - lb <= LMAX
-Segs spatial_segs(const ssd_cache *c, const LayerState &st);
-Segs semantic_segs(const ssd_cache *c, const LayerState &st);
+Segs spatial_segs(const ssd_cache *c, int l, const LayerState &st);
+Segs semantic_segs(const ssd_cache *c, int l, const LayerState &st);
 // Rows a fused append + attention streams from a spatial unit: everything retained after the append except
 // the new token itself (which the kernel holds in registers); new_slot is where that token goes.
-Segs spatial_segs_fused(const ssd_cache *c, const LayerState &before, const LayerState &after, int new_slot);
-// slot of position p in a spatial unit
-int spatial_slot(const ssd_cache *c, int p);
+Segs spatial_segs_fused(const ssd_cache *c, int l, const LayerState &before, const LayerState &after, int new_slot);
+// slot of position p in a spatial unit of layer l
+int spatial_slot(const ssd_cache *c, int l, int p);
 // host bookkeeping of one in-place compression of layer l (the kernels' effect on the counters)
 void apply_compress_counters(ssd_cache *c, int l);
 // does layer l keep a row buffer (semantic heads, or spatial heads under Algorithm 2)
 bool has_buffer(const ssd_cache *c, int l);
-// end of the run of layers starting at lb that share layer lb's state, at most LMAX long
+// end of the run of layers starting at lb that share layer lb's state, window and budget, at most LMAX long
 int same_state_run(const ssd_cache *c, int lb, int le);
+// the same without the state: layers that share layer lb's window and budget
+int same_geom_run(const ssd_cache *c, int lb, int le);
 
 // implemented in ssd_compress.hip
 int launch_compress_inplace(const ssd_cache *cache, int lb, int le, const LayerState &st, hipStream_t s);

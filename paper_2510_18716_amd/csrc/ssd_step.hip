@@ -332,7 +332,7 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
         const bool in_kernel = do_compress && at.m + n_old <= FUSED_SELECT_MAX;
         if (cache->launch_enabled) {
             StepArgs a;
-            a.g = make_geom(cache);
+            a.g = make_geom(cache, lb);
             fill_launch_meta(cache, lb, le, &a.lm);
             a.q = static_cast<const char *>(q);
             a.out = static_cast<char *>(out);
@@ -340,14 +340,14 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.v_new = static_cast<const char *>(v_new);
             a.layer_off = lb - layer_begin;
             a.new_pos = before.n;
-            a.new_slot_sp = spatial_slot(cache, before.n);
-            a.new_slot_se = cf.budget + (before.base + before.c) % cf.stage_cap;
+            a.new_slot_sp = spatial_slot(cache, lb, before.n);
+            a.new_slot_se = cache->Ml[lb] + (before.base + before.c) % cf.stage_cap;
             if (fused) {
-                a.sp = spatial_segs_fused(cache, before, at, a.new_slot_sp);
-                a.se = semantic_segs(cache, before);
+                a.sp = spatial_segs_fused(cache, lb, before, at, a.new_slot_sp);
+                a.se = semantic_segs(cache, lb, before);
             } else {
-                a.sp = spatial_segs(cache, at);
-                a.se = semantic_segs(cache, at);
+                a.sp = spatial_segs(cache, lb, at);
+                a.se = semantic_segs(cache, lb, at);
             }
             a.qscale = cache->scale * LOG2E;
             a.accumulate = accumulate ? 1 : 0;
@@ -364,11 +364,11 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.sem_first = a.se.total + (fused ? 1 : 0) >= a.sp.total + (fused ? 1 : 0) ? 1 : 0;
             hipError_t e;
             if (cf.dtype == SSD_BF16)
-                e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cf.budget, s)
-                                       : launch_step<bf16_t, 64>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cf.budget, s);
+                e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s)
+                                       : launch_step<bf16_t, 64>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s);
             else
-                e = cf.head_dim == 128 ? launch_step<float, 128>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cf.budget, s)
-                                       : launch_step<float, 64>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cf.budget, s);
+                e = cf.head_dim == 128 ? launch_step<float, 128>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s)
+                                       : launch_step<float, 64>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s);
             if (e != hipSuccess) return hip_fail(e, what);
             if (do_compress && !in_kernel) {
                 const int rc = launch_compress_inplace(cache, lb, le, at, s);

@@ -31,7 +31,7 @@ def say(*a):
 
 def make_cache(wl: workload.Workload, ht: np.ndarray, device="cuda") -> ssd.Cache:
     cfg = make_config(wl.L, wl.B, wl.H, wl.d, wl.dtype, wl.W, wl.S, wl.M, wl.R, wl.C, 0.0, int(wl.alg2))
-    return ssd.Cache(cfg, ht, device=device)
+    return ssd.Cache(cfg, ht, device=device, window=wl.W_layers, budget=wl.M_layers)
 
 
 def flat_index(wl: workload.Workload, units: Sequence[Tuple[int, int, int]]) -> torch.Tensor:
@@ -113,11 +113,13 @@ def gpu_decode(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.ndar
 
 
 def oracle_unit(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.ndarray, schedule: np.ndarray,
-                unit: Tuple[int, int, int], p_end: Optional[int] = None):
-    """Oracle decode of one unit: (o [steps,d], heavy_log, gap_log, Unit)."""
+                unit: Tuple[int, int, int], p_end: Optional[int] = None, layer: Optional[int] = None):
+    """Oracle decode of one unit: (o [steps,d], heavy_log, gap_log, Unit).  `unit` indexes `data` and `ht`;
+    `layer` is the unit's layer in the workload where those are slices (it selects the layer's W and M)."""
     l, b, h = unit
+    lw = l if layer is None else layer
     q, K, V = workload.unit_arrays(data, l, b, h)
-    u = oracle.Unit(ht[l, h] == workload.SEMANTIC, wl.W, wl.S, wl.M, wl.R, wl.C, buffered_spatial=wl.alg2)
+    u = oracle.Unit(ht[l, h] == workload.SEMANTIC, wl.W_of(lw), wl.S, wl.M_of(lw), wl.R, wl.C, buffered_spatial=wl.alg2)
     o, hl, gl = u.run(q, K, V, wl.scale, schedule, p_end=p_end, log=True)
     return o, hl, gl, u
 
@@ -132,11 +134,11 @@ def check_outputs(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str):
     return float(err.max())
 
 
-def spatial_positions(wl: workload.Workload, n: int, n_c: Optional[int] = None) -> List[int]:
+def spatial_positions(wl: workload.Workload, n: int, n_c: Optional[int] = None, layer: int = 0) -> List[int]:
     """Closed form of a spatial head's retained set after n tokens; under Algorithm 2 the window is cut at
     n_c, the token count at the last compression."""
     ref = n if not wl.alg2 else n_c
-    return sorted(set(range(min(wl.S, n))) | set(range(max(wl.S, ref - wl.W), n)))
+    return sorted(set(range(min(wl.S, n))) | set(range(max(wl.S, ref - wl.W_of(layer)), n)))
 
 
 def compare_unit_sets(wl, ht, unit, layer_index, exports, heavy_log, gap_log, schedule):
@@ -144,6 +146,7 @@ def compare_unit_sets(wl, ht, unit, layer_index, exports, heavy_log, gap_log, sc
     step.  Returns the first step at which a permitted near-tie divergence was seen, or None."""
     l, b, h = unit
     sem = ht[l, h] == workload.SEMANTIC
+    M = wl.M_of(l)
     for p in sorted(exports):
         pos, score = exports[p]["post"]
         row = pos[layer_index, b, h]
@@ -151,10 +154,10 @@ def compare_unit_sets(wl, ht, unit, layer_index, exports, heavy_log, gap_log, sc
         n = p + 1
         if not sem:
             n_c = max([s + 1 for s in range(p + 1) if schedule[s]], default=0)
-            assert got == spatial_positions(wl, n, n_c), ("spatial set", unit, p)
+            assert got == spatial_positions(wl, n, n_c, l), ("spatial set", unit, p)
             continue
-        heavy_gpu = sorted(int(x) for x in row[: wl.M] if x >= 0)
-        staged_gpu = sorted(int(x) for x in row[wl.M:] if x >= 0)
+        heavy_gpu = sorted(int(x) for x in row[:M] if x >= 0)
+        staged_gpu = sorted(int(x) for x in row[M:] if x >= 0)
         heavy_ref = [int(x) for x in heavy_log[p] if x >= 0]
         if heavy_gpu != heavy_ref:
             # allowed only if some cut so far was a near-tie in the oracle
@@ -191,9 +194,9 @@ def check_selection_on_own_scores(wl, ht, unit, layer_index, exports):
         cand_sc = row_s[valid]
         newest = np.sort(cand_pos)[len(cand_pos) - min(wl.R, len(cand_pos)):] if wl.R > 0 else np.zeros(0, np.int32)
         is_cand = ~np.isin(cand_pos, newest)
-        keep, _ = oracle.top_m(cand_sc[is_cand], cand_pos[is_cand], wl.M)
+        keep, _ = oracle.top_m(cand_sc[is_cand], cand_pos[is_cand], wl.M_of(l))
         want = sorted(int(x) for x in cand_pos[is_cand][keep])
-        got = sorted(int(x) for x in pos1[layer_index, b, h][: wl.M] if x >= 0)
+        got = sorted(int(x) for x in pos1[layer_index, b, h][: wl.M_of(l)] if x >= 0)
         assert got == want, ("selection on the GPU's own scores", unit, p)
         # scores travel with their tokens, bit for bit
         after = {int(pp): float(ss) for pp, ss in zip(pos1[layer_index, b, h], sc1[layer_index, b, h]) if pp >= 0}

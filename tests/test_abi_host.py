@@ -257,3 +257,42 @@ def test_prefill_scores_rejects_bad_arguments_before_any_launch():
                 dict(d=96), dict(dtype=7), dict(scale=-1.0), dict(scale=float("nan"))):
         assert call(**bad) == ssd.SSD_ERR_INVALID_ARG, bad
         assert ssd.ssd_last_error() != ""
+
+
+def test_per_layer_window_and_budget_layout_counters_and_limits():
+    L, B, H, d, S, R, C_ = 3, 2, 4, 64, 1, 1, 3
+    Wl, Ml = [8, 3, 16], [5, 12, 2]
+    cfg = make_config(L, B, H, d, "f32", 99, S, 99, R, C_)
+    ht = _ht(L, H)                                   # two spatial, two semantic heads per layer
+    row = d * 4
+    want = sum(B * 2 * 2 * (S + w) * row + B * 2 * 2 * (m + C_) * row + 2 * B * 2 * (m + C_) * 4 for w, m in zip(Wl, Ml))
+    got = ssd.ssd_cache_bytes(cfg, ht, Wl, Ml)
+    assert want <= got <= want + 4 * 256 * L
+    assert got < ssd.ssd_cache_bytes(cfg, ht)        # the per-layer values replace the config's (99, 99)
+    # either array alone; the config value fills in for the other
+    assert ssd.ssd_cache_bytes(cfg, ht, Wl, None) > ssd.ssd_cache_bytes(cfg, ht, Wl, Ml)
+    c = ssd.Cache(cfg, ht, device=None, window=Wl, budget=Ml)
+    assert [c.layer_budget(l) for l in range(L)] == list(zip(Wl, Ml))
+    assert c.export_slots == max(max(S + w for w in Wl), max(m + C_ for m in Ml))
+    # counters: each layer's heavy count saturates at its own budget
+    units = [oracle.Unit(True, Wl[l], S, Ml[l], R, C_) for l in range(L)]
+    for step in range(30):
+        ssd.ssd_decode_step(c, 0, L, FAKE, FAKE, FAKE, FAKE, True, step % 2 == 1)
+        for u in units:
+            assert u.append() == 0
+            if step % 2 == 1:
+                u.compress()
+        for l, u in enumerate(units):
+            hp, _, sp, _ = u.state()
+            assert c.layer_state(l)[:3] == (u.n, len(hp), len(sp))
+    assert [c.layer_state(l)[1] for l in range(L)] == Ml
+    # dense-source mode: the same per layer
+    ssd.ssd_compress_kv(c, 0, L, FAKE, FAKE, None, 10)
+    assert [c.layer_state(l)[1] for l in range(L)] == [min(m, 10 - R) for m in Ml]
+    # limits hold per entry
+    for bad_w, bad_m in (([8, 0, 16], Ml), (Wl, [5, 0, 2]), (Wl, [5, 4094, 2]), ([8, 70000, 16], Ml)):
+        assert ssd.ssd_cache_bytes(cfg, ht, bad_w, bad_m) == 0
+        with pytest.raises(ssd.SsdError):
+            ssd.Cache(cfg, ht, device=None, window=bad_w, budget=bad_m)
+    with pytest.raises(ValueError):
+        ssd.Cache(cfg, ht, device=None, window=[1, 2])

@@ -45,7 +45,7 @@ def _full_compare(wl, ht=None, lpc=None, k_units=10 ** 9, export_every=1, seed=0
     for ui, unit in enumerate(units):
         l, b, h = unit
         host = {x: dev_data[x][:, l:l + 1, b:b + 1, h:h + 1].cpu() for x in "qkv"}
-        o_ref, hl, gl, u = oracle_unit(wl, host, ht[l:l + 1, h:h + 1], schedule, (0, 0, 0))
+        o_ref, hl, gl, u = oracle_unit(wl, host, ht[l:l + 1, h:h + 1], schedule, (0, 0, 0), layer=l)
         li = layers.index(l)
         diverged = compare_unit_sets(wl, ht, unit, li, exports, hl, gl, schedule)
         t3 += check_selection_on_own_scores(wl, ht, unit, li, exports)
@@ -121,6 +121,19 @@ def test_degenerate_parameters(fused):
     _full_compare(workload.Workload("W1-M1", W=1, M=1, S=0, R=1, C=2, cadence=1, **base), fused=fused)
     _full_compare(workload.Workload("R0", W=2, M=3, S=1, R=0, C=1, cadence=1, **base), fused=fused)
     _full_compare(workload.Workload("S-exceeds-n0", W=4, M=4, S=6, R=3, C=4, cadence=1, **base), fused=fused)
+
+
+@FUSED
+def test_window_and_budget_per_layer(fused):
+    # layer-wise allocation: every layer its own W and M (units of different size, separate launches), also
+    # two neighbouring layers that share both (one launch) and a budget larger than the sequence
+    wl = workload.Workload("per-layer", L=5, prompts=1, H=6, d=128, dtype="bf16", n0=7, grid_h=6, grid_w=10, W=99, M=99,
+                           S=1, R=1, C=4, cadence=3, seed=23, plain=True,
+                           W_layers=(24, 5, 5, 1, 13), M_layers=(20, 9, 9, 3, 200))
+    _full_compare(wl, fused=fused)
+    _full_compare(wl.replace(name="per-layer-calls"), lpc=1, fused=fused)
+    wl2 = workload.config(2).replace(name="cfg2-pyramid", L=4, prompts=4, W_layers=(64, 48, 32, 16), M_layers=(96, 64, 32, 16))
+    _full_compare(wl2, k_units=32, export_every=50, device_gen=True, fused=fused)
 
 
 @FUSED

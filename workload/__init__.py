@@ -52,6 +52,8 @@ class Workload:
     plain: bool = False       # True: no planted structure, q = k = v = N(0,1) in every head
     seed: int = 20251018
     w_metric: int = 32        # recency window of the sparsity metric
+    W_layers: Optional[Sequence[int]] = None    # window per layer (None = W everywhere)
+    M_layers: Optional[Sequence[int]] = None    # budget per layer (None = M everywhere)
 
     @property
     def B(self) -> int:
@@ -72,6 +74,12 @@ class Workload:
     @property
     def scale(self) -> float:
         return 1.0 / math.sqrt(self.d)
+
+    def W_of(self, layer: int) -> int:
+        return self.W if self.W_layers is None else int(self.W_layers[layer])
+
+    def M_of(self, layer: int) -> int:
+        return self.M if self.M_layers is None else int(self.M_layers[layer])
 
     def replace(self, **kw) -> "Workload":
         return dataclasses.replace(self, **kw)

@@ -397,7 +397,8 @@ def main():
         tp = (time.perf_counter() - t0) / reps
         pf_bytes = wl.L * units * (2 * n0 * row_bytes(wl) + 4 * n0)
         nb = (n0 + 31) // 32
-        pf_flops = wl.L * units * 2 * (nb * (nb + 1) // 2) * 2 * 32 * 32 * wl.d      # tiles on or below the diagonal, two sweeps
+        sweeps = 1 if nb <= 4 else 2                                                # short prompts keep their logits in registers
+        pf_flops = wl.L * units * sweeps * (nb * (nb + 1) // 2) * 2 * 32 * 32 * wl.d   # tiles on or below the diagonal
         result["prefill_scores"] = {"ms_all_layers": tp * 1e3, "us_per_layer_launch": tp * 1e6 / wl.L, "prompt_tokens": n0,
                                     "algorithmic_GB": pf_bytes / 1e9, "GBps": pf_bytes / 1e9 / tp,
                                     "frac_of_hbm_peak": pf_bytes / 1e9 / tp / HBM_PEAK_GBS, "mfma_TFLOPs": pf_flops / 1e12 / tp,

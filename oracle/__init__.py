@@ -57,6 +57,8 @@ _lib.ssd_oracle_classify.argtypes = [_f32p, _f32p, C.c_int, C.c_int, C.c_int, C.
 _lib.ssd_oracle_classify.restype = None
 _lib.ssd_oracle_prefill_scores.argtypes = [_f32p, _f32p, C.c_int, C.c_int, C.c_double, _f32p]
 _lib.ssd_oracle_prefill_scores.restype = None
+_lib.ssd_oracle_cfg_mix.argtypes = [_f32p, C.c_int, C.c_int, C.c_double, _f32p]
+_lib.ssd_oracle_cfg_mix.restype = None
 _lib.ssd_oracle_top_m.argtypes = [_f32p, _i32p, C.c_int, C.c_int, _i32p, C.POINTER(C.c_double)]
 _lib.ssd_oracle_top_m.restype = C.c_int
 _lib.ssd_oracle_unit_new.argtypes = [C.c_int] * 6
@@ -147,6 +149,16 @@ def prefill_scores(q, K, scale):
     out = np.zeros(max(n, 1), np.float32)
     _lib.ssd_oracle_prefill_scores(q, K, d, n, float(scale), out)
     return out[:n]
+
+
+def cfg_mix(p, gamma):
+    """O6.  p [2 * prompts, V] (rows 2i conditional, 2i+1 unconditional) -> float32 [prompts, V], Eq. (1)."""
+    p = _f32(p)
+    B, V = p.shape
+    assert B % 2 == 0
+    out = np.zeros((max(B // 2, 1), max(V, 1)), np.float32)
+    _lib.ssd_oracle_cfg_mix(p, B // 2, V, float(gamma), out)
+    return out[: B // 2, :V]
 
 
 def top_m(score, pos, M):

@@ -22,6 +22,8 @@
  *   O3  top-M selection by accumulated score ("IndicesOfTopM", Algorithm 1).
  *   O5  accumulated scores of a prompt processed at once under causal
  *       attention (prefill branch of Algorithm 2).
+ *   O6  classifier-free guidance of the two distributions of a prompt,
+ *       Eq. (1) of Sec. 3.1.
  *   O4  the per-head cache policy of Algorithm 1 with the additions the text
  *       of Sec. 3.3 makes (initial sink token for spatial heads, reserved
  *       recent window R for semantic heads) and the deferred-compression
@@ -217,6 +219,24 @@ void ssd_oracle_prefill_scores(const float *q, const float *K, int d, int n,
     for (j = 0; j < n; ++j) score_out[j] = (float)acc[j];
     free(acc);
     free(z);
+}
+
+/* ------------------------------------------------------------------ O6 -- */
+
+/*
+ * Classifier-free guidance, Eq. (1): for prompt i the conditional row is
+ * sequence 2i, the unconditional row sequence 2i+1 (Sec. 3.1 names the two
+ * passes; the adjacent pairing is this build's batch layout), and
+ *   out[i, v] = p_c[v] + gamma * (p_c[v] - p_u[v]).
+ * p is [2 * n_prompts, V]; out is [n_prompts, V].
+ */
+void ssd_oracle_cfg_mix(const float *p, int n_prompts, int V, double gamma, float *out)
+{
+    int i, v;
+    for (i = 0; i < n_prompts; ++i) {
+        const float *c = p + (size_t)(2 * i) * V, *u = p + (size_t)(2 * i + 1) * V;
+        for (v = 0; v < V; ++v) out[(size_t)i * V + v] = (float)((double)c[v] + gamma * ((double)c[v] - (double)u[v]));
+    }
 }
 
 /* ------------------------------------------------------------------ O3 -- */

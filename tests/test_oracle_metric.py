@@ -130,3 +130,36 @@ def test_prefill_scores_equal_what_decode_steps_accumulate():
     _, _, sp, ss = u.state()
     assert sp.tolist() == list(range(n))
     np.testing.assert_allclose(ss, oracle.prefill_scores(q, K, 0.3), rtol=2e-6, atol=1e-6)
+
+
+# ---- O6: classifier-free guidance, Eq. (1) -------------------------------------------------------------
+
+def test_cfg_mix_pinned_values_and_special_cases():
+    # hand-computed: c + gamma (c - u)
+    p = np.array([[0.5, 0.25, 0.25],        # prompt 0, conditional
+                  [0.25, 0.5, 0.25],        # prompt 0, unconditional
+                  [1.0, 0.0, -2.0],         # prompt 1, conditional
+                  [0.0, 0.0, 2.0]], np.float32)
+    got = oracle.cfg_mix(p, 2.0)
+    assert got.tolist() == [[1.0, -0.25, 0.25], [3.0, 0.0, -10.0]]
+    # gamma = 0 returns the conditional rows; equal rows are a fixed point for every gamma
+    assert np.array_equal(oracle.cfg_mix(p, 0.0), p[0::2])
+    same = np.repeat(p[0::2], 2, axis=0)
+    assert np.array_equal(oracle.cfg_mix(same, 7.5), p[0::2])
+    # gamma = -1 returns the unconditional rows (the formula is affine in gamma)
+    assert np.array_equal(oracle.cfg_mix(p, -1.0), p[1::2])
+
+
+def test_cfg_mix_matches_numpy_and_keeps_the_total_mass():
+    r = np.random.default_rng(3)
+    p = r.random((6, 37)).astype(np.float32)
+    p /= p.sum(axis=1, keepdims=True)
+    for gamma in (1.0, 5.0):
+        got = oracle.cfg_mix(p, gamma)
+        ref = p[0::2].astype(np.float64) * (1 + gamma) - gamma * p[1::2].astype(np.float64)
+        np.testing.assert_allclose(got, ref, rtol=1e-6, atol=1e-7)
+        # both inputs sum to one, so the guided row does too (it need not stay non-negative)
+        np.testing.assert_allclose(got.sum(axis=1), 1.0, atol=1e-5)
+    # the pair order matters: swapping conditional and unconditional changes the result
+    sw = p.reshape(3, 2, 37)[:, ::-1].reshape(6, 37)
+    assert not np.allclose(oracle.cfg_mix(sw, 5.0), oracle.cfg_mix(p, 5.0))

@@ -239,6 +239,20 @@ int ssd_prefill_scores(const void *Q, const void *K, int n_units, int n_src, int
                        int dtype, float softmax_scale, float *score_out, void *stream);
 
 /*
+ * Classifier-free guidance of the two next-token distributions of each prompt
+ * (Sec. 3.1, Eq. 1):
+ *     out[i, v] = p[2i, v] + gamma * (p[2i, v] - p[2i+1, v])
+ * where sequence 2i is the pass conditioned on the prompt and 2i+1 the
+ * unconditional one (the pairing of the conventions above).  The paper writes
+ * the rule on the distributions; the arithmetic is the same whatever the rows
+ * hold (probabilities or logits), and the result is not renormalised.
+ *   p      : dev [n_seqs, V] of `dtype`, n_seqs even
+ *   out    : dev float [n_seqs / 2, V], 16-byte aligned, overwritten
+ *   gamma  : guidance strength (the paper takes gamma > 1; any finite value is accepted)
+ */
+int ssd_cfg_mix(const void *p, int n_seqs, int V, int dtype, float gamma, float *out, void *stream);
+
+/*
  * One whole decode step of the layers in a single launch per layer group:
  * ssd_append_token, then ssd_decode_attn, then (compress != 0) the in-place
  * mode of ssd_compress_kv, with exactly their results.  Each (sequence, head)

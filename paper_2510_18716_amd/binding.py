@@ -71,6 +71,8 @@ lib.ssd_compress_kv.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp, C.c_int, _
 lib.ssd_compress_kv.restype = C.c_int
 lib.ssd_prefill_scores.argtypes = [_vp, _vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, _vp, _vp]
 lib.ssd_prefill_scores.restype = C.c_int
+lib.ssd_cfg_mix.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_float, _vp, _vp]
+lib.ssd_cfg_mix.restype = C.c_int
 lib.ssd_cache_export_slots.argtypes = [_vp]
 lib.ssd_cache_export_slots.restype = C.c_int
 lib.ssd_cache_export.argtypes = [_vp, C.c_int, _vp, _vp, _vp, _vp]
@@ -265,6 +267,10 @@ def ssd_compress_kv(cache: Cache, layer_begin: int, layer_end: int, K_src=None, 
 def ssd_prefill_scores(Q, K, n_units: int, n_src: int, d: int, dtype, score_out, softmax_scale: float = 0.0, stream=None) -> None:
     _check(lib.ssd_prefill_scores(_ptr(Q), _ptr(K), int(n_units), int(n_src), int(d), _dtype_code(dtype), float(softmax_scale),
                                   _ptr(score_out), _stream(stream)), "ssd_prefill_scores")
+
+
+def ssd_cfg_mix(p, n_seqs: int, V: int, dtype, gamma: float, out, stream=None) -> None:
+    _check(lib.ssd_cfg_mix(_ptr(p), int(n_seqs), int(V), _dtype_code(dtype), float(gamma), _ptr(out), _stream(stream)), "ssd_cfg_mix")
 
 
 def ssd_classify_heads(far, tot, L: int, P: int, H: int, T: int, tau: float, s_out, type_out, stream=None) -> None:

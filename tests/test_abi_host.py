@@ -296,3 +296,16 @@ def test_per_layer_window_and_budget_layout_counters_and_limits():
             ssd.Cache(cfg, ht, device=None, window=bad_w, budget=bad_m)
     with pytest.raises(ValueError):
         ssd.Cache(cfg, ht, device=None, window=[1, 2])
+
+
+def test_cfg_mix_rejects_bad_arguments_before_any_launch():
+    ok = dict(p=FAKE, n_seqs=4, V=64, dtype=ssd.SSD_BF16, gamma=5.0, out=FAKE)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return ssd.lib.ssd_cfg_mix(a["p"], a["n_seqs"], a["V"], a["dtype"], a["gamma"], a["out"], None)
+
+    for bad in (dict(p=None), dict(out=None), dict(p=FAKE + 4), dict(out=FAKE + 8), dict(n_seqs=0), dict(n_seqs=3), dict(V=0),
+                dict(dtype=2), dict(gamma=float("inf")), dict(gamma=float("nan"))):
+        assert call(**bad) == ssd.SSD_ERR_INVALID_ARG, bad
+        assert ssd.ssd_last_error() != ""

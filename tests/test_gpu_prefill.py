@@ -137,3 +137,25 @@ def test_prompt_pipeline_prefill_compress_decode(dtype, d, n0):
                 row = exports[p]["post"][0][l, b, h]
                 assert sorted(int(x) for x in row[: wl.M] if x >= 0) == [int(x) for x in hl[p - n0] if x >= 0], ((l, b, h), p)
     assert n_ties <= len(units) // 4
+
+
+# ---- classifier-free guidance mix (Eq. 1) -----------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,V", [(2, 1), (4, 7), (6, 64), (8, 1000), (128, 16384), (2, 16385)])
+def test_cfg_mix_matches_oracle(dtype, B, V):
+    say("cfg mix", dtype, B, V)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    g = torch.Generator().manual_seed(B * 31 + V)
+    p = (3.0 * torch.randn((B, V), generator=g)).to(tdt)
+    out = torch.full((B // 2, V), -9.0, device="cuda")
+    for gamma in (5.0, 0.0, -1.0):
+        ssd.ssd_cfg_mix(p.cuda(), B, V, dtype, gamma, out)
+        torch.cuda.synchronize()
+        ref = oracle.cfg_mix(p.float().numpy(), gamma)
+        got = out.cpu().numpy()
+        # one fused multiply-add in fp32 on exactly representable inputs
+        bound = 1e-6 * (np.abs(ref) + abs(gamma) * 6.0 + 1.0)
+        assert (np.abs(got - ref) <= bound).all(), (gamma, float(np.abs(got - ref).max()))
+        if gamma == 0.0:
+            assert np.array_equal(got, p[0::2].float().numpy())

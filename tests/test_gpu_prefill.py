@@ -1,5 +1,6 @@
 """GPU parity of ssd_prefill_scores (accumulated causal attention scores of a prompt, matrix-core kernel)
-against the oracle, and of the whole prompt pipeline: prefill scores -> dense-source compression -> decode."""
+against the oracle, of the whole prompt pipeline: prefill scores -> dense-source compression -> decode, and of
+the classifier-free guidance mix that follows the last layer (ssd_cfg_mix)."""
 import numpy as np
 import pytest
 import torch

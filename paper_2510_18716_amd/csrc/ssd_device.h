@@ -217,19 +217,18 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
     const int n_iter = (row_end - row_begin + RPW - 1) / RPW;
     const int chunk_iters = CH * iter_stride;
 
-    // issue the loads of the chunk that starts at iteration it0 (clamped rows reload the last row:
-    // same cache line as a neighbouring lane's, so no extra HBM traffic)
+    // Issue the loads of the chunk that starts at iteration it0.  Always exactly 2 * CH loads, whatever
+    // it0: rows past the end are clamped to the last row (a cache line some lane has just fetched, so no
+    // extra HBM traffic).  A fixed number of requests per chunk is what lets the compiler wait for "all but
+    // the newest chunk" instead of "everything": with loads under a condition it has to assume the fewest.
     auto load = [&](int it0, uint4 (&kr)[CH], uint4 (&vr)[CH]) {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const int it = it0 + i * iter_stride;
-            if (it < n_iter) {                                   // wave-uniform
-                int r = row_begin + it * RPW + grp;
-                r = r < row_end ? r : row_end - 1;
-                const uint32_t off = (uint32_t)seg_slot(sg, r) * (uint32_t)row_bytes + lane_off;
-                kr[i] = *reinterpret_cast<const uint4 *>(Kb + off);
-                vr[i] = *reinterpret_cast<const uint4 *>(Vb + off);
-            }
+            int r = row_begin + (it0 + i * iter_stride) * RPW + grp;
+            r = r < row_end ? r : row_end - 1;
+            const uint32_t off = (uint32_t)seg_slot(sg, r) * (uint32_t)row_bytes + lane_off;
+            kr[i] = *reinterpret_cast<const uint4 *>(Kb + off);
+            vr[i] = *reinterpret_cast<const uint4 *>(Vb + off);
         }
     };
     auto compute = [&](int it0, const uint4 (&kr)[CH], const uint4 (&vr)[CH]) {
@@ -298,17 +297,15 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
     for (int i = 0; i < CH; ++i) { ka[i] = va[i] = kb[i] = vb[i] = make_uint4(0, 0, 0, 0); }
     load(it, ka, va);
     after_first_issue();
-    for (;;) {
-        int nxt = it + chunk_iters;
-        if (nxt < n_iter) load(nxt, kb, vb);
+    for (;;) {                                     // the chunk after the last one is requested too (clamped) and dropped
+        load(it + chunk_iters, kb, vb);
         compute(it, ka, va);
-        if (nxt >= n_iter) break;
-        it = nxt;
-        nxt = it + chunk_iters;
-        if (nxt < n_iter) load(nxt, ka, va);
+        it += chunk_iters;
+        if (it >= n_iter) break;
+        load(it + chunk_iters, ka, va);
         compute(it, kb, vb);
-        if (nxt >= n_iter) break;
-        it = nxt;
+        it += chunk_iters;
+        if (it >= n_iter) break;
     }
 }
 

@@ -93,47 +93,52 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
     sm.init();
     const bool want_z = u.sem && t_accumulate;
 
-    // Everything the tail of this wave will need is requested now, ahead of the K/V stream, so that no
-    // memory round trip is left exposed after the last row: the new token's fragments (fused append) and
-    // the running scores / positions of the first 128 rows (one or two per lane).
+    // No memory round trip may be left exposed after the last row, so everything the tail of this wave
+    // needs is requested around the start of the K/V stream.  The new token's fragments (fused append) are
+    // fetched by every lane group alike (the same 16 lines, no extra traffic): only group 0 uses them, but a
+    // load under a per-lane condition costs a branch and a wait.
     const bool compress = t_do_compress != 0;
     const bool tail = u.sem && (t_accumulate || compress || FUSED);
     uint4 new_k = make_uint4(0, 0, 0, 0), new_v = make_uint4(0, 0, 0, 0);
-    if (FUSED && lane < LPR) {
+    if (FUSED) {
         new_k = *reinterpret_cast<const uint4 *>(a.k_new + qoff);
         new_v = *reinterpret_cast<const uint4 *>(a.v_new + qoff);
     }
     float pre_score[2] = {0.f, 0.f};
     int pre_pos[2] = {0, 0};
-    if (tail) {
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const int r = lane + 64 * k;
-            if (r < sg.total) {
-                const int slot = seg_slot(sg, r);
-                pre_score[k] = u.score[slot];
-                if (compress) pre_pos[k] = u.pos[slot];
-            }
-        }
-    }
 
-    // Fused append: the new token's rows go to their slot as soon as the stream's first loads are in
-    // flight, so these stores drain during the stream instead of in the tail of the unit.
-    auto store_new = [&]() {
+    // Runs once, right after the stream's first loads have been issued, so that nothing here delays them:
+    //  - fused append: the new token's rows go to their slot now and drain during the stream instead of in
+    //    the tail of the unit;
+    //  - the running scores and positions of the first 128 rows (one or two per lane) are requested now and
+    //    have long arrived when the tail needs them.  The loads are unconditional (rows past the end are
+    //    clamped to a valid slot and ignored later): a load under a per-lane condition makes the compiler
+    //    wait for it on the spot.
+    auto after_first_issue = [&]() {
         if (FUSED && lane < LPR) {
             const int slot = u.sem ? a.new_slot_se : a.new_slot_sp;
             const size_t off = (size_t)slot * (size_t)a.g.row_bytes + (size_t)sub * 16u;
             SSD_ST16(u.K + off, new_k);
             SSD_ST16(u.V + off, new_v);
         }
+        if (tail) {
+            const int last = sg.total > 0 ? sg.total - 1 : 0;    // no rows yet: slot of row 0, inside the unit
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int r = lane + 64 * k;
+                const int slot = seg_slot(sg, r < last ? r : last);
+                pre_score[k] = u.score[slot];
+                pre_pos[k] = u.pos[slot];
+            }
+        }
     };
 #ifdef SSD_PROBE
-    if (a.probe % 100 == 2 || a.probe % 100 == 3 || a.probe % 100 >= 10) { sm.l = 1.f; store_new(); } else
+    if (a.probe % 100 == 2 || a.probe % 100 == 3 || a.probe % 100 >= 10) { sm.l = 1.f; after_first_issue(); } else
 #endif
     if (want_z)
-        stream_rows<T, D, CH, true, false, PF>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, zbuf, 0, 0, a.probe, store_new);
+        stream_rows<T, D, CH, true, false, PF>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, zbuf, 0, 0, a.probe, after_first_issue);
     else
-        stream_rows<T, D, CH, false, false, PF>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, nullptr, 0, 0, a.probe, store_new);
+        stream_rows<T, D, CH, false, false, PF>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, nullptr, 0, 0, a.probe, after_first_issue);
     if (FUSED) {
         // The new token, from the registers it was loaded into, is folded into lane group 0's softmax as
         // one more row (index sg.total).

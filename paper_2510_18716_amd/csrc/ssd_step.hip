@@ -16,11 +16,8 @@
 
 namespace ssd {
 
-// Field order matters: a wave reads its arguments with scalar loads, and every 64-byte line of the
-// argument block it touches for the first time is a trip to memory that the whole (in-phase) launch waits
-// for.  Everything a unit needs sits in the first lines; the per-layer table, of which a wave reads one
-// entry, comes last.
-struct StepArgs {
+// What a wave needs from the argument block: these fields and its one entry of the per-layer table.
+struct StepHot {
     const char *q;
     char *out;
     const char *k_new;   // fused append only
@@ -40,8 +37,68 @@ struct StepArgs {
     int sem_first;       // semantic units have more rows than spatial ones: dispatch them first
     Segs sp, se;         // rows streamed from the cache (fused append: without the new token's slot)
     Geom g;
+};
+
+struct StepArgs {
+    StepHot h;
     LaunchMeta lm;
 };
+
+// A wave reads its arguments with scalar loads from the kernel-argument segment.  Left to itself the
+// compiler fetches each field where it is first used, which here gave seven dependent groups of loads, each
+// a round trip through the scalar cache -- and to memory for the first waves of every CU, which in a launch
+// that is one resident round means for everybody -- before the first K/V row was requested.  So the kernel
+// reads the segment itself: four 64-byte loads for the fixed part and four smaller ones for its entry of
+// the per-layer table (whose address depends on the block index only), all issued back to back and waited
+// for once.  The empty asm names all eight results, so none of the loads can sink to a later use.
+typedef uint32_t u32x16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+#define SSD_KERNARG __attribute__((address_space(4)))
+
+static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDesc &ld) {
+    static_assert(sizeof(StepHot) <= 256, "the fixed part is read as four 64-byte pieces");
+    static_assert(sizeof(LayerDesc) == 56, "one table entry is read as three 16-byte pieces and one of 8 bytes");
+    static_assert(sizeof(StepArgs) >= 256 && sizeof(StepArgs) == sizeof(StepHot) + sizeof(LaunchMeta), "layout of the argument block");
+    const SSD_KERNARG char *kp = (const SSD_KERNARG char *)__builtin_amdgcn_kernarg_segment_ptr();
+    struct { u32x16_t w[4]; } fixed;
+    struct { u32x4_t w[3]; u32x2_t t; } entry;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fixed.w[i] = *reinterpret_cast<const SSD_KERNARG u32x16_t *>(kp + 64 * i);
+    const SSD_KERNARG char *ep = kp + sizeof(StepHot) + (size_t)lrel * sizeof(LayerDesc);
+#pragma unroll
+    for (int i = 0; i < 3; ++i) entry.w[i] = *reinterpret_cast<const SSD_KERNARG u32x4_t *>(ep + 16 * i);
+    entry.t = *reinterpret_cast<const SSD_KERNARG u32x2_t *>(ep + 48);
+    asm volatile("" : "+s"(fixed.w[0]), "+s"(fixed.w[1]), "+s"(fixed.w[2]), "+s"(fixed.w[3]), "+s"(entry.w[0]), "+s"(entry.w[1]),
+                      "+s"(entry.w[2]), "+s"(entry.t));
+    // field by field out of the loaded words (constant indices only, so everything stays in registers)
+#define SSD_W(off) (fixed.w[(off) / 64][((off) % 64) / 4])
+#define SSD_I(f) a.f = (int32_t)SSD_W(offsetof(StepHot, f))
+#define SSD_U(f) a.f = SSD_W(offsetof(StepHot, f))
+    // (through a global-address-space pointer: rebuilt from bare integers a pointer would be generic, and every
+    // access through it a flat instruction, which counts against both memory counters)
+#define SSD_P(f, T_) a.f = (T_)(__attribute__((address_space(1))) char *)((uint64_t)SSD_W(offsetof(StepHot, f)) | ((uint64_t)SSD_W(offsetof(StepHot, f) + 4) << 32))
+    SSD_P(q, const char *); SSD_P(out, char *); SSD_P(k_new, const char *); SSD_P(v_new, const char *);
+    a.qscale = __uint_as_float(SSD_W(offsetof(StepHot, qscale)));
+    SSD_I(layer_off); SSD_I(new_slot_sp); SSD_I(new_slot_se); SSD_I(new_pos); SSD_I(accumulate); SSD_I(do_compress);
+    SSD_I(m); SSD_I(c); SSD_I(base); SSD_I(R); SSD_I(lpr); SSD_I(zcap); SSD_I(wave_lds); SSD_I(probe); SSD_I(sem_first);
+    SSD_I(sp.start[0]); SSD_I(sp.start[1]); SSD_I(sp.start[2]); SSD_I(sp.len[0]); SSD_I(sp.len[1]); SSD_I(sp.len[2]); SSD_I(sp.total);
+    SSD_I(se.start[0]); SSD_I(se.start[1]); SSD_I(se.start[2]); SSD_I(se.len[0]); SSD_I(se.len[1]); SSD_I(se.len[2]); SSD_I(se.total);
+    SSD_P(g.base, char *); SSD_I(g.B); SSD_I(g.H); SSD_I(g.S); SSD_I(g.W); SSD_I(g.M); SSD_I(g.C); SSD_I(g.RW); SSD_I(g.row_bytes);
+    SSD_U(g.unit_sp_bytes); SSD_U(g.unit_se_bytes);
+#undef SSD_W
+#define SSD_W(off) ((off) < 48 ? entry.w[((off) % 48) / 16][((off) % 16) / 4] : entry.t[((off) % 16) / 4])
+#define SSD_Q(f) ld.f = (uint64_t)SSD_W(offsetof(LayerDesc, f)) | ((uint64_t)SSD_W(offsetof(LayerDesc, f) + 4) << 32)
+    SSD_Q(off_sp); SSD_Q(off_se); SSD_Q(off_score); SSD_Q(off_pos); SSD_Q(sem_mask[0]); SSD_Q(sem_mask[1]);
+    ld.n_sp = (int32_t)SSD_W(offsetof(LayerDesc, n_sp));
+    ld.n_se = (int32_t)SSD_W(offsetof(LayerDesc, n_se));
+#undef SSD_W
+#undef SSD_I
+#undef SSD_U
+#undef SSD_P
+#undef SSD_Q
+}
+#undef SSD_KERNARG
 
 // One wave per unit, WPB units (consecutive heads of one sequence and layer) per workgroup;
 // grid = (ceil(H / WPB), B, layers of the launch).  Nothing below needs a workgroup barrier.
@@ -54,18 +111,17 @@ struct StepArgs {
 #endif
 
 template <typename T, int D, int CH, int WPB, bool FUSED, bool PF = true>
-__global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
+__global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read through fetch_args
     constexpr int VEC = Elem<T>::VEC;
     constexpr int LPR = D / VEC;
     extern __shared__ __align__(16) unsigned char lds_raw[];
+    StepHot a;
+    LayerDesc ld;
+    fetch_args(blockIdx.z >> 1, a, ld);
 
-    // The arguments the tail of a unit needs are fetched now, with everything else, and pinned in scalar
-    // registers: fetched lazily they would add a memory round trip to the end of every wave.
-    int t_m = a.m, t_c = a.c, t_base = a.base, t_R = a.R, t_lpr = a.lpr, t_new_pos = a.new_pos,
-        t_new_slot_se = a.new_slot_se, t_do_compress = a.do_compress, t_accumulate = a.accumulate,
-        t_M = a.g.M, t_C = a.g.C, t_row_bytes = a.g.row_bytes;
-    asm volatile("" : "+s"(t_m), "+s"(t_c), "+s"(t_base), "+s"(t_R), "+s"(t_lpr), "+s"(t_new_pos), "+s"(t_new_slot_se),
-                      "+s"(t_do_compress), "+s"(t_accumulate), "+s"(t_M), "+s"(t_C), "+s"(t_row_bytes));
+    const int t_m = a.m, t_c = a.c, t_base = a.base, t_R = a.R, t_lpr = a.lpr, t_new_pos = a.new_pos,
+              t_new_slot_se = a.new_slot_se, t_do_compress = a.do_compress, t_accumulate = a.accumulate,
+              t_M = a.g.M, t_C = a.g.C, t_row_bytes = a.g.row_bytes;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: everything per-unit stays uniform
     const int lane = threadIdx.x & 63;
     const int sub = lane % LPR;
@@ -75,14 +131,22 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs a) {
     const int lrel = blockIdx.z >> 1;
     const bool sem_unit = ((blockIdx.z & 1) == 0) == (a.sem_first != 0);
     const int local = blockIdx.x * WPB + w;               // index among the heads of this type in this layer
-    const LayerDesc &ld = a.lm.layer[lrel];
     if (local >= (sem_unit ? ld.n_se : ld.n_sp)) return;
     const uint64_t m0 = sem_unit ? ld.sem_mask[0] : ~ld.sem_mask[0];
     const uint64_t m1 = sem_unit ? ld.sem_mask[1] : ~ld.sem_mask[1];
     const int h = kth_set_bit(m0, m1, local);             // spatial heads: bits above H are never reached (local < n_sp)
     const int rem = blockIdx.y * a.g.H + h;
     const UnitRef u = unit_ref_local(a.g, ld, blockIdx.y, sem_unit, local);
-    const Segs sg = u.sem ? a.se : a.sp;       // by value: the runs stay in scalar registers to the end
+    // field by field, constant indices: a choice between two structs, or an index the compiler has not
+    // unrolled yet, would pin the argument copy in (scratch) memory
+    Segs sg;
+    sg.start[0] = u.sem ? a.se.start[0] : a.sp.start[0];
+    sg.start[1] = u.sem ? a.se.start[1] : a.sp.start[1];
+    sg.start[2] = u.sem ? a.se.start[2] : a.sp.start[2];
+    sg.len[0] = u.sem ? a.se.len[0] : a.sp.len[0];
+    sg.len[1] = u.sem ? a.se.len[1] : a.sp.len[1];
+    sg.len[2] = u.sem ? a.se.len[2] : a.sp.len[2];
+    sg.total = u.sem ? a.se.total : a.sp.total;
     const size_t qoff = ((size_t)(a.layer_off + lrel) * (size_t)(a.g.B * a.g.H) + rem) * (size_t)a.g.row_bytes + (size_t)sub * 16u;
     unsigned char *region = lds_raw + (size_t)w * a.wave_lds;
     float *zbuf = reinterpret_cast<float *>(region);                    // [zcap]
@@ -278,13 +342,14 @@ static Tuning g_tune = DEFAULT_TUNE;
 static constexpr int FUSED_SELECT_MAX = 1024;
 
 template <typename T, int D, int CH, int WPB, bool PF = true>
-static void launch_one(const StepArgs &a, dim3 blocks, size_t lds, bool fused, hipStream_t s) {
-    if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, PF>), blocks, dim3(WPB * 64), lds, s, a);
-    else hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, false, PF>), blocks, dim3(WPB * 64), lds, s, a);
+static void launch_one(const StepArgs &full, dim3 blocks, size_t lds, bool fused, hipStream_t s) {
+    if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, PF>), blocks, dim3(WPB * 64), lds, s, full);
+    else hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, false, PF>), blocks, dim3(WPB * 64), lds, s, full);
 }
 
 template <typename T, int D>
-static hipError_t launch_step(StepArgs &a, int H, int max_type_heads, int B, int layers, bool fused, int M, hipStream_t s) {
+static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, int layers, bool fused, int M, hipStream_t s) {
+    StepHot &a = full.h;
     const int n_old = a.c - a.R, n_cand = a.m + n_old;
     // Launch shape by the number of units (measured on the 7B- and 1B-shaped workloads).  Up to half of
     // what the chip holds at once (256 CUs x 16 waves): the launch is latency-bound, so spread the waves
@@ -301,13 +366,13 @@ static hipError_t launch_step(StepArgs &a, int H, int max_type_heads, int B, int
     if ((size_t)(g_probe / 1000) * 1024 > lds) lds = (size_t)(g_probe / 1000) * 1024;   // occupancy experiments: pad the workgroup's LDS
 #endif
     const dim3 blocks((unsigned)((max_type_heads + wpb - 1) / wpb), (unsigned)B, (unsigned)(2 * layers));
-#define SSD_CASE(CH_, WPB_) if (ch == CH_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_>(a, blocks, lds, fused, s); return hipGetLastError(); }
+#define SSD_CASE(CH_, WPB_) if (ch == CH_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_>(full, blocks, lds, fused, s); return hipGetLastError(); }
     if constexpr (sizeof(T) == 2 && D == 128) {       // the shape the sweeps are run on has every variant
         SSD_CASE(1, 1) SSD_CASE(2, 1) SSD_CASE(4, 1)
         SSD_CASE(1, 2) SSD_CASE(2, 2) SSD_CASE(4, 2)
         SSD_CASE(1, 4) SSD_CASE(2, 4) SSD_CASE(4, 4)
 #ifdef SSD_PROBE
-#define SSD_CASE_NPF(CODE_, CH_, WPB_) if (ch == CODE_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_, false>(a, blocks, lds, fused, s); return hipGetLastError(); }
+#define SSD_CASE_NPF(CODE_, CH_, WPB_) if (ch == CODE_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_, false>(full, blocks, lds, fused, s); return hipGetLastError(); }
         SSD_CASE_NPF(14, 4, 4) SSD_CASE_NPF(18, 8, 4) SSD_CASE_NPF(14, 4, 8) SSD_CASE_NPF(18, 8, 8) SSD_CASE_NPF(18, 8, 2) SSD_CASE(4, 8) SSD_CASE(2, 8)
 #undef SSD_CASE_NPF
 #endif
@@ -336,9 +401,10 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
         const bool do_compress = compress && has_se && n_old > 0;
         const bool in_kernel = do_compress && at.m + n_old <= FUSED_SELECT_MAX;
         if (cache->launch_enabled) {
-            StepArgs a;
+            StepArgs full;
+            StepHot &a = full.h;
             a.g = make_geom(cache, lb);
-            fill_launch_meta(cache, lb, le, &a.lm);
+            fill_launch_meta(cache, lb, le, &full.lm);
             a.q = static_cast<const char *>(q);
             a.out = static_cast<char *>(out);
             a.k_new = static_cast<const char *>(k_new);
@@ -369,11 +435,11 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.sem_first = a.se.total + (fused ? 1 : 0) >= a.sp.total + (fused ? 1 : 0) ? 1 : 0;
             hipError_t e;
             if (cf.dtype == SSD_BF16)
-                e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s)
-                                       : launch_step<bf16_t, 64>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s);
+                e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s)
+                                       : launch_step<bf16_t, 64>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s);
             else
-                e = cf.head_dim == 128 ? launch_step<float, 128>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s)
-                                       : launch_step<float, 64>(a, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s);
+                e = cf.head_dim == 128 ? launch_step<float, 128>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s)
+                                       : launch_step<float, 64>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s);
             if (e != hipSuccess) return hip_fail(e, what);
             if (do_compress && !in_kernel) {
                 const int rc = launch_compress_inplace(cache, lb, le, at, s);

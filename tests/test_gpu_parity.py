@@ -218,6 +218,42 @@ def test_determinism_same_inputs_same_bits():
         np.testing.assert_array_equal(ea[wl.n_total - 1]["post"][k], eb[wl.n_total - 1]["post"][k])
 
 
+def test_two_half_batches_on_two_streams_equal_one_batch():
+    """The schedule bench.py also times: the sequences split into two caches whose per-layer launches go to two
+    streams.  Sequences are independent, so outputs and final tables must equal the one-cache run bit for bit."""
+    from paper_2510_18716_amd.binding import make_config
+    wl = workload.config(2).replace(name="cfg2-two-streams", L=3, prompts=8, grid_h=5)
+    ht = workload.head_map(wl)
+    data = workload.generate(wl, device="cuda", head_type=ht)
+    sched = workload.compress_schedule(wl)
+    whole = make_cache(wl, ht)
+    Bm = wl.B // 2
+    cfg_m = make_config(wl.L, Bm, wl.H, wl.d, wl.dtype, wl.W, wl.S, wl.M, wl.R, wl.C)
+    halves = [ssd.Cache(cfg_m, ht), ssd.Cache(cfg_m, ht)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    out1 = torch.zeros((wl.L, wl.B, wl.H, wl.d), dtype=wl.torch_dtype, device="cuda")
+    out2 = torch.zeros_like(out1)
+    torch.cuda.synchronize()
+    for p in range(wl.n_total):
+        q, k, v = data["q"][p], data["k"][p], data["v"][p]
+        for l in range(wl.L):
+            ssd.ssd_decode_step(whole, l, l + 1, q[l], k[l], v[l], out1[l], True, bool(sched[p]))
+            for i in (0, 1):
+                sl = slice(i * Bm, (i + 1) * Bm)
+                ssd.ssd_decode_step(halves[i], l, l + 1, q[l, sl], k[l, sl], v[l, sl], out2[l, sl], True, bool(sched[p]),
+                                    stream=streams[i].cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.equal(out1, out2), ("outputs differ at token", p)
+    for l in range(wl.L):
+        pw, cw, sw = whole.export(l)
+        torch.cuda.synchronize()
+        for i in (0, 1):
+            ph, ch_, sh = halves[i].export(l)
+            torch.cuda.synchronize()
+            sl = slice(i * Bm, (i + 1) * Bm)
+            assert torch.equal(pw[sl], ph) and torch.equal(cw[sl], ch_) and torch.equal(sw[sl], sh)
+
+
 @pytest.mark.parametrize("frac,W,M", [(0.25, 32, 128), (0.5, 64, 64), (0.75, 128, 32)])
 def test_config5_large_batch_online_classification_then_decode(frac, W, M):
     """Large-batch shape (B = 512, 32 heads) with the head types found online: a dense profiling run on a

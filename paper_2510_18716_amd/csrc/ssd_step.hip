@@ -102,13 +102,14 @@ static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDes
 
 // One wave per unit, WPB units (consecutive heads of one sequence and layer) per workgroup;
 // grid = (ceil(H / WPB), B, layers of the launch).  Nothing below needs a workgroup barrier.
-#ifdef SSD_PROBE      // probe / 100 == 1: the kernel with its stores left out (what the write path costs)
-#define SSD_ST16(ptr, val) do { if (a.probe / 100 != 1) *reinterpret_cast<uint4 *>(ptr) = (val); } while (0)
-#define SSD_ST4(ptr, val) do { if (a.probe / 100 != 1) *(ptr) = (val); } while (0)
+#ifdef SSD_PROBE      // (probe / 100) & bit: the kernel with that class of stores left out (what the write path costs)
+#define SSD_ST16(bit, ptr, val) do { if (!((a.probe / 100) & (bit))) { if ((a.probe / 100) & 8) { const uint4 _v = (val); __builtin_nontemporal_store(__builtin_bit_cast(u32x4_t, _v), reinterpret_cast<u32x4_t *>(ptr)); } else *reinterpret_cast<uint4 *>(ptr) = (val); } } while (0)
+#define SSD_ST4(bit, ptr, val) do { if (!((a.probe / 100) & (bit))) { if ((a.probe / 100) & 8) __builtin_nontemporal_store((val), (ptr)); else *(ptr) = (val); } } while (0)
 #else
-#define SSD_ST16(ptr, val) (*reinterpret_cast<uint4 *>(ptr) = (val))
-#define SSD_ST4(ptr, val) (*(ptr) = (val))
+#define SSD_ST16(bit, ptr, val) (*reinterpret_cast<uint4 *>(ptr) = (val))
+#define SSD_ST4(bit, ptr, val) (*(ptr) = (val))
 #endif
+// store classes: 1 = new token's rows, 2 = output, 4 = running scores and positions
 
 template <typename T, int D, int CH, int WPB, bool FUSED, bool PF = true>
 __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read through fetch_args
@@ -182,8 +183,8 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
         if (FUSED && lane < LPR) {
             const int slot = u.sem ? a.new_slot_se : a.new_slot_sp;
             const size_t off = (size_t)slot * (size_t)a.g.row_bytes + (size_t)sub * 16u;
-            SSD_ST16(u.K + off, new_k);
-            SSD_ST16(u.V + off, new_v);
+            SSD_ST16(1, u.K + off, new_k);
+            SSD_ST16(1, u.V + off, new_v);
         }
         if (tail) {
             const int last = sg.total > 0 ? sg.total - 1 : 0;    // no rows yet: slot of row 0, inside the unit
@@ -230,7 +231,7 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
         float o[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) o[e] = sm.acc[e] * inv_l;
-        SSD_ST16(a.out + qoff, Elem<T>::pack(o));
+        SSD_ST16(2, a.out + qoff, Elem<T>::pack(o));
     }
 
     if (!tail) return;
@@ -254,8 +255,8 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
         const int slot = is_new ? t_new_slot_se : seg_slot(sg, r);
         const float p = t_accumulate ? fast_exp2(zbuf[r] - m_all) * inv_l : 0.f;
         const float s = (is_new ? 0.f : s_old) + p;
-        if (t_accumulate || is_new) SSD_ST4(&u.score[slot], s);
-        if (is_new) SSD_ST4(&u.pos[slot], t_new_pos);
+        if (t_accumulate || is_new) SSD_ST4(4, &u.score[slot], s);
+        if (is_new) SSD_ST4(4, &u.pos[slot], t_new_pos);
         unsigned long long key = ~0ull;
         if (compress && r < n_cand) {
             key = make_key(s, is_new ? t_new_pos : pos_old);

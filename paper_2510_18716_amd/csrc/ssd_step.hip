@@ -35,6 +35,7 @@ struct StepHot {
     int wave_lds;        // bytes of LDS per wave (logits + selection scratch)
     int probe;           // SSD_PROBE builds only
     int sem_first;       // semantic units have more rows than spatial ones: dispatch them first
+    int late_new_store;  // fused append: store the new token's rows after the stream instead of at its start
     Segs sp, se;         // rows streamed from the cache (fused append: without the new token's slot)
     Geom g;
 };
@@ -82,6 +83,7 @@ static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDes
     a.qscale = __uint_as_float(SSD_W(offsetof(StepHot, qscale)));
     SSD_I(layer_off); SSD_I(new_slot_sp); SSD_I(new_slot_se); SSD_I(new_pos); SSD_I(accumulate); SSD_I(do_compress);
     SSD_I(m); SSD_I(c); SSD_I(base); SSD_I(R); SSD_I(lpr); SSD_I(zcap); SSD_I(wave_lds); SSD_I(probe); SSD_I(sem_first);
+    SSD_I(late_new_store);
     SSD_I(sp.start[0]); SSD_I(sp.start[1]); SSD_I(sp.start[2]); SSD_I(sp.len[0]); SSD_I(sp.len[1]); SSD_I(sp.len[2]); SSD_I(sp.total);
     SSD_I(se.start[0]); SSD_I(se.start[1]); SSD_I(se.start[2]); SSD_I(se.len[0]); SSD_I(se.len[1]); SSD_I(se.len[2]); SSD_I(se.total);
     SSD_P(g.base, char *); SSD_I(g.B); SSD_I(g.H); SSD_I(g.S); SSD_I(g.W); SSD_I(g.M); SSD_I(g.C); SSD_I(g.RW); SSD_I(g.row_bytes);
@@ -103,13 +105,13 @@ static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDes
 // One wave per unit, WPB units (consecutive heads of one sequence and layer) per workgroup;
 // grid = (ceil(H / WPB), B, layers of the launch).  Nothing below needs a workgroup barrier.
 #ifdef SSD_PROBE      // (probe / 100) & bit: the kernel with that class of stores left out (what the write path costs)
-#define SSD_ST16(bit, ptr, val) do { if (!((a.probe / 100) & (bit))) { if ((a.probe / 100) & 8) { const uint4 _v = (val); __builtin_nontemporal_store(__builtin_bit_cast(u32x4_t, _v), reinterpret_cast<u32x4_t *>(ptr)); } else *reinterpret_cast<uint4 *>(ptr) = (val); } } while (0)
-#define SSD_ST4(bit, ptr, val) do { if (!((a.probe / 100) & (bit))) { if ((a.probe / 100) & 8) __builtin_nontemporal_store((val), (ptr)); else *(ptr) = (val); } } while (0)
+#define SSD_ST16(bit, ptr, val) do { if (!((a.probe / 100) & (bit))) { *reinterpret_cast<uint4 *>(ptr) = (val); } } while (0)
+#define SSD_ST4(bit, ptr, val) do { if (!((a.probe / 100) & (bit))) { *(ptr) = (val); } } while (0)
 #else
 #define SSD_ST16(bit, ptr, val) (*reinterpret_cast<uint4 *>(ptr) = (val))
 #define SSD_ST4(bit, ptr, val) (*(ptr) = (val))
 #endif
-// store classes: 1 = new token's rows, 2 = output, 4 = running scores and positions
+// store classes: 1 = new token's rows, 2 = output, 4 = running scores and positions, 8 = promoted row
 
 template <typename T, int D, int CH, int WPB, bool FUSED, bool PF = true>
 __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read through fetch_args
@@ -172,20 +174,21 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
     float pre_score[2] = {0.f, 0.f};
     int pre_pos[2] = {0, 0};
 
-    // Runs once, right after the stream's first loads have been issued, so that nothing here delays them:
-    //  - fused append: the new token's rows go to their slot now and drain during the stream instead of in
-    //    the tail of the unit;
-    //  - the running scores and positions of the first 128 rows (one or two per lane) are requested now and
-    //    have long arrived when the tail needs them.  The loads are unconditional (rows past the end are
-    //    clamped to a valid slot and ignored later): a load under a per-lane condition makes the compiler
-    //    wait for it on the spot.
-    auto after_first_issue = [&]() {
+    // Runs once, right after the stream's first loads have been issued, so that nothing here delays them: the
+    // running scores and positions of the first 128 rows (one or two per lane) are requested now and have
+    // long arrived when the tail needs them.  The loads are unconditional (rows past the end are clamped to a
+    // valid slot and ignored later): a load under a per-lane condition makes the compiler wait for it on the
+    // spot.
+    auto store_new = [&]() {
         if (FUSED && lane < LPR) {
             const int slot = u.sem ? a.new_slot_se : a.new_slot_sp;
             const size_t off = (size_t)slot * (size_t)a.g.row_bytes + (size_t)sub * 16u;
             SSD_ST16(1, u.K + off, new_k);
             SSD_ST16(1, u.V + off, new_v);
         }
+    };
+    auto after_first_issue = [&]() {
+        if (!a.late_new_store) store_new();
         if (tail) {
             const int last = sg.total > 0 ? sg.total - 1 : 0;    // no rows yet: slot of row 0, inside the unit
 #pragma unroll
@@ -233,6 +236,13 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
         for (int e = 0; e < VEC; ++e) o[e] = sm.acc[e] * inv_l;
         SSD_ST16(2, a.out + qoff, Elem<T>::pack(o));
     }
+    // Fused append, the new token's rows.  Stores and loads share one in-order counter per wave, and a store is
+    // acknowledged much later than a load returns: issued at the start of the stream, these two stores keep
+    // the counter up and the stream's "all but the newest chunk" waits wait for more loads than they mean to.
+    // In a launch of one resident round that costs 1.1 us, so there the rows are stored here, after the
+    // stream; where other waves or another stream's kernel fill such gaps anyway, storing them early is
+    // better (the stores drain during the stream and the wave ends sooner).  The host chooses.
+    if (a.late_new_store) store_new();
 
     if (!tail) return;
 #ifdef SSD_PROBE
@@ -301,11 +311,11 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
     const bool ev_staged = e_idx >= t_m;
     const int n_move = n_old - (ev_staged ? 1 : 0);
     if (n_move <= 0) return;
-    wave_global_sync();                                   // rows / scores stored earlier by other lanes of this wave
     const int frag_per_tok = 2 * t_lpr;
     // k-th promoted candidate (oldest first) and k-th free heavy slot
     auto src_idx = [&](int k) { return t_m + k + ((ev_staged && k >= e_idx - t_m) ? 1 : 0); };
     auto dst_slot = [&](int k) { return ev_heavy ? (k == 0 ? e_idx : t_m + k - 1) : t_m + k; };
+    wave_global_sync();                                   // rows stored earlier by other lanes of this wave
     for (int t = lane; t < n_move * frag_per_tok; t += 64) {
         const int k = t / frag_per_tok;
         const int f = t % frag_per_tok;
@@ -313,7 +323,7 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
         char *plane = kv ? u.V : u.K;
         const int from = M + (t_base + (src_idx(k) - t_m)) % C;
         const uint4 v = *reinterpret_cast<const uint4 *>(plane + (size_t)from * t_row_bytes + (size_t)fs * 16u);
-        *reinterpret_cast<uint4 *>(plane + (size_t)dst_slot(k) * t_row_bytes + (size_t)fs * 16u) = v;
+        SSD_ST16(8, plane + (size_t)dst_slot(k) * t_row_bytes + (size_t)fs * 16u, v);
     }
     // position and score travel with the token: its key sits in the registers of lane (index mod 64)
     for (int k0 = 0; k0 < n_move; k0 += 64) {             // wave-uniform trip count: the shuffles need every lane
@@ -358,6 +368,7 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
     // resident round: shallow queues finish sooner.  Many rounds: waves come and go, deeper per-wave
     // queues keep HBM busier.
     const long long units = (long long)H * B * layers;
+    a.late_new_store = g_probe / 1000000 == 1 ? 0 : g_probe / 1000000 == 2 ? 1 : (units > 2048 && units <= 16384 ? 1 : 0);
     int ch = g_tune.ch ? g_tune.ch : (units <= 2048 || units > 16384 ? 4 : 2);
     int wpb = g_tune.wpb ? g_tune.wpb : (units <= 2048 ? 1 : 4);
     a.wave_lds = (int)(((size_t)a.zcap * 4 + (a.do_compress ? select_lds_bytes(M, n_cand, n_old) + 16 : 0) + 15) / 16 * 16);

@@ -105,13 +105,14 @@ static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDes
 // One wave per unit, WPB units (consecutive heads of one sequence and layer) per workgroup;
 // grid = (ceil(H / WPB), B, layers of the launch).  Nothing below needs a workgroup barrier.
 #ifdef SSD_PROBE      // (probe / 100) & bit: the kernel with that class of stores left out (what the write path costs)
-#define SSD_ST16(bit, ptr, val) do { if (!((a.probe / 100) & (bit))) { *reinterpret_cast<uint4 *>(ptr) = (val); } } while (0)
-#define SSD_ST4(bit, ptr, val) do { if (!((a.probe / 100) & (bit))) { *(ptr) = (val); } } while (0)
+#define SSD_ST16(bit, ptr, val) do { if (!((a.probe / 100) & (bit))) { if ((a.probe / 100) & 16) { const uint4 _v = (val); asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" :: "v"((char *)(ptr)), "v"(__builtin_bit_cast(u32x4_t, _v)) : "memory"); } else *reinterpret_cast<uint4 *>(ptr) = (val); } } while (0)
+#define SSD_ST4(bit, ptr, val) do { if (!((a.probe / 100) & (bit))) { if ((a.probe / 100) & 16) asm volatile("global_store_dword %0, %1, off sc0 sc1" :: "v"(ptr), "v"(val) : "memory"); else *(ptr) = (val); } } while (0)
 #else
 #define SSD_ST16(bit, ptr, val) (*reinterpret_cast<uint4 *>(ptr) = (val))
 #define SSD_ST4(bit, ptr, val) (*(ptr) = (val))
 #endif
-// store classes: 1 = new token's rows, 2 = output, 4 = running scores and positions, 8 = promoted row
+// store classes: 1 = new token's rows, 2 = output, 4 = running scores and positions, 8 = promoted row;
+// 16 = all stores written through (system scope) instead of left dirty in L2
 
 template <typename T, int D, int CH, int WPB, bool FUSED, bool PF = true>
 __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read through fetch_args

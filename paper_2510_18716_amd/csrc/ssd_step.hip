@@ -364,13 +364,13 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
     StepHot &a = full.h;
     const int n_old = a.c - a.R, n_cand = a.m + n_old;
     // Launch shape by the number of units (measured on the 7B- and 1B-shaped workloads).  Up to half of
-    // what the chip holds at once (256 CUs x 16 waves): the launch is latency-bound, so spread the waves
-    // over as many CUs as possible (one unit per workgroup) and give each a deep load queue.  Around one
-    // resident round: shallow queues finish sooner.  Many rounds: waves come and go, deeper per-wave
-    // queues keep HBM busier.
+    // what the chip holds at once (256 CUs x 16 waves) the launch is latency-bound: the waves are spread
+    // over as many CUs as possible (one unit per workgroup).  Four wave-loads of K and of V per chunk (two
+    // chunks in flight) are best at every size.  Between half a round and four rounds the new token's
+    // rows are stored after the stream (see the kernel).
     const long long units = (long long)H * B * layers;
     a.late_new_store = g_probe / 1000000 == 1 ? 0 : g_probe / 1000000 == 2 ? 1 : (units > 2048 && units <= 16384 ? 1 : 0);
-    int ch = g_tune.ch ? g_tune.ch : (units <= 2048 || units > 16384 ? 4 : 2);
+    int ch = g_tune.ch ? g_tune.ch : 4;
     int wpb = g_tune.wpb ? g_tune.wpb : (units <= 2048 ? 1 : 4);
     a.wave_lds = (int)(((size_t)a.zcap * 4 + (a.do_compress ? select_lds_bytes(M, n_cand, n_old) + 16 : 0) + 15) / 16 * 16);
     while (wpb > 1 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;

@@ -226,7 +226,7 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
         for (int i = 0; i < CH; ++i) {
             int r = row_begin + (it0 + i * iter_stride) * RPW + grp;
             r = r < row_end ? r : row_end - 1;
-            const uint32_t off = (uint32_t)seg_slot(sg, r) * (uint32_t)row_bytes + lane_off;
+            uint32_t off = (uint32_t)seg_slot(sg, r) * (uint32_t)row_bytes + lane_off;
             kr[i] = *reinterpret_cast<const uint4 *>(Kb + off);
             vr[i] = *reinterpret_cast<const uint4 *>(Vb + off);
         }
@@ -260,9 +260,9 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const int it = it0 + i * iter_stride;
-            if (it < n_iter) {                                   // wave-uniform
+            {
                 const int r = row_begin + it * RPW + grp;
-                const bool ok = r < row_end;
+                const bool ok = it < n_iter && r < row_end;
                 const float p = ok ? fast_exp2(z[i] - m_new) : 0.f;
                 sm.l += p;
                 float vf[VEC];

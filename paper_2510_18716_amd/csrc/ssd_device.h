@@ -259,21 +259,22 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
         for (int e = 0; e < VEC; ++e) sm.acc[e] *= alpha;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
+            // rows past the end were clamped to the unit's last row on loading: finite data, weight 0.  They are
+            // masked rather than skipped, so that every loaded fragment is consumed on every path and no load
+            // stays pending across the loop's back edge (which would cost a full wait at the loop head).
             const int it = it0 + i * iter_stride;
-            {
-                const int r = row_begin + it * RPW + grp;
-                const bool ok = it < n_iter && r < row_end;
-                const float p = ok ? fast_exp2(z[i] - m_new) : 0.f;
-                sm.l += p;
-                float vf[VEC];
-                Elem<T>::unpack(vr[i], vf);
+            const int r = row_begin + it * RPW + grp;
+            const bool ok = it < n_iter && r < row_end;
+            const float p = ok ? fast_exp2(z[i] - m_new) : 0.f;
+            sm.l += p;
+            float vf[VEC];
+            Elem<T>::unpack(vr[i], vf);
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) sm.acc[e] = fmaf(p, vf[e], sm.acc[e]);
-                if (ZBUF) { if (ok && lane_off == 0) zbuf[r] = z[i]; }
-                if (MASS) {
-                    sm.tot += (r >= vis_start) ? p : 0.f;
-                    sm.far += (r >= vis_start && r <= far_last) ? p : 0.f;
-                }
+            for (int e = 0; e < VEC; ++e) sm.acc[e] = fmaf(p, vf[e], sm.acc[e]);
+            if (ZBUF) { if (ok && lane_off == 0) zbuf[r] = z[i]; }
+            if (MASS) {
+                sm.tot += (r >= vis_start) ? p : 0.f;
+                sm.far += (r >= vis_start && r <= far_last) ? p : 0.f;
             }
         }
         sm.m = m_new;

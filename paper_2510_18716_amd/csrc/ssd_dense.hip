@@ -54,7 +54,7 @@ __global__ __launch_bounds__(WPB * 64) void dense_kernel(DenseArgs a) {
     Softmax<VEC> sm;
     sm.init();
     if (r_begin < r_end)
-        stream_rows<T, D, CH, false, true>(Kb, Vb, a.row_bytes, sg, r_begin, r_end, 0, 1, q, a.qscale, sm, nullptr, a.vis_start, a.far_last);
+        stream_rows<T, D, CH, false, true, true, NoHook, false>(Kb, Vb, a.row_bytes, sg, r_begin, r_end, 0, 1, q, a.qscale, sm, nullptr, a.vis_start, a.far_last);
     merge_groups<VEC, LPR, true>(sm);
     if (a.splits == 1) {
         const float inv_l = sm.l > 0.f ? 1.0f / sm.l : 0.f;

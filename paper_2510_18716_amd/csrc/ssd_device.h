@@ -201,7 +201,10 @@ template <int VEC> struct Softmax {
 // needs data requested before the stream (and so returned before it) can go there without delaying it.
 struct NoHook { __device__ __forceinline__ void operator()() const {} };
 
-template <typename T, int D, int CH, bool ZBUF, bool MASS, bool PF = true, typename Hook = NoHook>
+// PAD: every chunk issues its full 2 * CH loads and consumes them all (see `load` and `compute`); this is what
+// launches of few rounds want.  Without it loads and arithmetic past the end are skipped, which is slightly
+// better when many rounds of waves hide each other's waits anyway (the full-cache kernel).
+template <typename T, int D, int CH, bool ZBUF, bool MASS, bool PF = true, typename Hook = NoHook, bool PAD = true>
 static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, const char *__restrict__ Vb,
                                                   int row_bytes, const Segs &sg, int row_begin, int row_end,
                                                   int first_iter, int iter_stride,
@@ -224,6 +227,7 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
     auto load = [&](int it0, uint4 (&kr)[CH], uint4 (&vr)[CH]) {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
+            if (!PAD && it0 + i * iter_stride >= n_iter) continue;   // wave-uniform
             int r = row_begin + (it0 + i * iter_stride) * RPW + grp;
             r = r < row_end ? r : row_end - 1;
             uint32_t off = (uint32_t)seg_slot(sg, r) * (uint32_t)row_bytes + lane_off;
@@ -263,6 +267,7 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
             // masked rather than skipped, so that every loaded fragment is consumed on every path and no load
             // stays pending across the loop's back edge (which would cost a full wait at the loop head).
             const int it = it0 + i * iter_stride;
+            if (!PAD && it >= n_iter) continue;                      // wave-uniform
             const int r = row_begin + it * RPW + grp;
             const bool ok = it < n_iter && r < row_end;
             const float p = ok ? fast_exp2(z[i] - m_new) : 0.f;
@@ -298,12 +303,12 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
     for (int i = 0; i < CH; ++i) { ka[i] = va[i] = kb[i] = vb[i] = make_uint4(0, 0, 0, 0); }
     load(it, ka, va);
     after_first_issue();
-    for (;;) {                                     // the chunk after the last one is requested too (clamped) and dropped
-        load(it + chunk_iters, kb, vb);
+    for (;;) {                                     // PAD: the chunk after the last one is requested too (clamped) and dropped
+        if (PAD || it + chunk_iters < n_iter) load(it + chunk_iters, kb, vb);
         compute(it, ka, va);
         it += chunk_iters;
         if (it >= n_iter) break;
-        load(it + chunk_iters, ka, va);
+        if (PAD || it + chunk_iters < n_iter) load(it + chunk_iters, ka, va);
         compute(it, kb, vb);
         it += chunk_iters;
         if (it >= n_iter) break;

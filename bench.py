@@ -35,7 +35,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes of one step_kernel launch measured with rocprofv3 --pmc (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB,
 # the factors a 1 GiB copy kernel gives for these counters), keyed by (workload, layers per call, fused).
 # Source: profiles/step_kernel_cfg3_pmc.md
-MEASURED_TRAFFIC_BYTES = {("cfg3-7b", 1, True): 143.53e6, ("cfg3-7b", 30, True): 4302.1e6}
+MEASURED_TRAFFIC_BYTES = {("cfg3-7b", 1, True): 143.59e6, ("cfg3-7b", 30, True): 4301.9e6}
 
 
 def row_bytes(wl):

@@ -296,6 +296,22 @@ int ssd_dense_decode_attn(const void *q, const void *K, const void *V, void *out
                           int vis_start, int w, void *workspace, size_t workspace_bytes,
                           void *stream);
 
+/*
+ * Launch-shape knobs for benchmark sweeps and tests.  Process-wide, not
+ * thread-safe, no effect on results; (0, 0, 0) / 0 restore the defaults, which
+ * the library otherwise picks from the launch size.
+ *   ssd_tune_attend : ch = wave-wide loads of K (and of V) per chunk (0, 1, 2,
+ *                     4), wpb = units per workgroup (0, 1, 2, 4) of the
+ *                     attention / fused-step kernel; probe = 0, or 1000000 /
+ *                     2000000 to force the fused step's new rows to be stored
+ *                     at the start / after the end of the row stream (other
+ *                     values select measurement variants in probe builds only)
+ *   ssd_tune_dense  : number of row splits of the full-cache kernel (0..64)
+ * Return SSD_ERR_INVALID_ARG for values outside these sets.
+ */
+int ssd_tune_attend(int ch, int wpb, int probe);
+int ssd_tune_dense(int splits);
+
 /* Text of the calling thread's most recent error ("" if none). Never NULL. */
 const char *ssd_last_error(void);
 

@@ -473,9 +473,9 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
 
 using namespace ssd;
 
-// Launch-shape knobs for benchmarking sweeps (not part of the documented ABI): wave-wide loads per
-// chunk (1, 2, 4; 0 = chosen from the launch size) and units per workgroup (1, 2, 4); (0, 0) restores
-// the default.
+// Launch-shape knobs for benchmark sweeps and tests: wave-wide loads per chunk (1, 2, 4; 0 = the
+// default) and units per workgroup (1, 2, 4; 0 = chosen from the launch size); (0, 0) restores the
+// defaults.
 extern "C" int ssd_tune_attend(int ch, int wpb, int probe) {
     g_probe = probe;
     if (ch == 0 && wpb == 0) { g_tune = DEFAULT_TUNE; return SSD_OK; }

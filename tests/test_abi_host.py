@@ -309,3 +309,21 @@ def test_cfg_mix_rejects_bad_arguments_before_any_launch():
                 dict(dtype=2), dict(gamma=float("inf")), dict(gamma=float("nan"))):
         assert call(**bad) == ssd.SSD_ERR_INVALID_ARG, bad
         assert ssd.ssd_last_error() != ""
+
+
+def test_package_without_its_library_fails_loudly(tmp_path):
+    """No CPU or PyTorch fallback: a copy of the package without the built library, on a machine where it
+    cannot be built either, must refuse to import."""
+    import shutil
+    import subprocess
+    import sys
+    src = os.path.join(ROOT, "paper_2510_18716_amd")
+    dst = tmp_path / "paper_2510_18716_amd"
+    shutil.copytree(src, dst, ignore=shutil.ignore_patterns("*.so", "*.so.tmp*", "__pycache__"))
+    shutil.copytree(os.path.join(ROOT, "include"), tmp_path / "include")
+    env = dict(os.environ, HIPCC="/nonexistent/hipcc", PYTHONPATH=str(tmp_path))
+    r = subprocess.run([sys.executable, "-c", "import paper_2510_18716_amd"], cwd=str(tmp_path), env=env,
+                       stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+    assert r.returncode != 0
+    assert "hipcc" in r.stderr or "No such file" in r.stderr
+    assert not (dst / "libssd_hip.so").exists()

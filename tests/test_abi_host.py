@@ -327,3 +327,22 @@ def test_package_without_its_library_fails_loudly(tmp_path):
     assert r.returncode != 0
     assert "hipcc" in r.stderr or "No such file" in r.stderr
     assert not (dst / "libssd_hip.so").exists()
+
+
+def test_product_and_oracle_do_not_import_each_other():
+    """The oracle is test infrastructure: nothing under the package may name it, and it may not name the package
+    (the two share only the input generator)."""
+    def sources(top, exts):
+        for dirpath, _, files in os.walk(top):
+            for f in files:
+                if f.endswith(exts):
+                    yield os.path.join(dirpath, f)
+    for path in sources(os.path.join(ROOT, "paper_2510_18716_amd"), (".py", ".hip", ".h")):
+        text = open(path).read()
+        assert not re.search(r"^\s*(import|from)\s+oracle\b", text, flags=re.M), path
+        assert "ssd_oracle" not in text, path
+    for path in sources(os.path.join(ROOT, "oracle"), (".py", ".c", ".h")):
+        text = open(path).read()
+        assert "paper_2510_18716_amd" not in text and "ssd.h" not in text and "csrc" not in text, path
+    wl = open(os.path.join(ROOT, "workload", "__init__.py")).read()
+    assert not re.search(r"^\s*(import|from)\s+(oracle|paper_2510_18716_amd)\b", wl, flags=re.M)

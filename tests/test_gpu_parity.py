@@ -311,3 +311,28 @@ def test_config5_large_batch_online_classification_then_decode(frac, W, M):
         upto = wl.n_total if div is None else div + 1
         worst = max(worst, check_outputs(outs[:upto, ui], o_ref[:upto], wl.dtype, "unit %s" % (unit,)))
     say("  max abs output error %.3e" % worst)
+
+
+@pytest.mark.parametrize("seed", range(64))
+def test_random_small_configurations(seed):
+    """Seeded random shapes and policies (both dtypes and head dims, Algorithm 1 and 2, any cadence the row
+    buffer allows, budgets per layer now and then), every unit compared at every step, fused and unfused."""
+    r = np.random.default_rng(1000 + seed)
+    d = int(r.choice([64, 128]))
+    dtype = str(r.choice(["bf16", "f32"]))
+    L, H = int(r.integers(1, 4)), int(r.integers(1, 9))
+    R = int(r.integers(0, 4))
+    cadence = int(r.integers(1, 9))
+    C_ = R + cadence + int(r.integers(0, 3))
+    W, M, S = int(r.integers(1, 40)), int(r.integers(1, 40)), int(r.integers(0, 4))
+    alg2 = bool(r.integers(0, 2))
+    kw = {}
+    if L > 1 and r.random() < 0.4:
+        kw = dict(W_layers=tuple(int(x) for x in r.integers(1, 40, L)), M_layers=tuple(int(x) for x in r.integers(1, 40, L)))
+    wl = workload.Workload("rand%d" % seed, L=L, prompts=int(r.integers(1, 3)), H=H, d=d, dtype=dtype, n0=int(r.integers(1, 12)),
+                           grid_h=int(r.integers(2, 7)), grid_w=int(r.integers(2, 9)), W=W, M=M, S=S, R=R, C=C_, cadence=cadence,
+                           spatial_frac=float(r.choice([0.0, 0.25, 0.5, 0.75, 1.0])), seed=int(r.integers(1 << 30)),
+                           plain=bool(r.integers(0, 2)), alg2=alg2, **kw)
+    lpc = None if r.random() < 0.5 else 1
+    _full_compare(wl, lpc=lpc, fused=False)
+    _full_compare(wl, lpc=lpc, fused=True)

@@ -376,7 +376,7 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
     while (wpb > 1 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;
     size_t lds = (size_t)wpb * a.wave_lds;
 #ifdef SSD_PROBE
-    if ((size_t)(g_probe / 1000) * 1024 > lds) lds = (size_t)(g_probe / 1000) * 1024;   // occupancy experiments: pad the workgroup's LDS
+    if ((size_t)(g_probe % 1000000 / 10000) * 1024 > lds) lds = (size_t)(g_probe % 1000000 / 10000) * 1024;   // occupancy experiments: pad the workgroup's LDS
 #endif
     const dim3 blocks((unsigned)((max_type_heads + wpb - 1) / wpb), (unsigned)B, (unsigned)(2 * layers));
 #define SSD_CASE(CH_, WPB_) if (ch == CH_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_>(full, blocks, lds, fused, s); return hipGetLastError(); }
@@ -439,7 +439,7 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.do_compress = in_kernel ? 1 : 0;
             a.m = at.m; a.c = at.c; a.base = at.base; a.R = cf.recent;
             a.lpr = a.g.row_bytes / 16;
-            a.probe = g_probe;
+            a.probe = g_probe % 1000000;
             int mth = 1;
             for (int l = lb; l < le; ++l) {
                 mth = cache->ldesc[l].n_sp > mth ? cache->ldesc[l].n_sp : mth;

@@ -229,7 +229,7 @@ int ssd_compress_kv(ssd_cache *cache, int layer_begin, int layer_end,
  * result is the score_src argument of ssd_compress_kv's dense-source mode.
  *   Q, K      : dev [n_units, n_src, d] of `dtype` (the K_src layout with the
  *               leading three dimensions flattened)
- *   n_units   : >= 1;  n_src : 1 .. 1024;  d : 64 or 128
+ *   n_units   : >= 1;  n_src : 1 .. 4096 (as ssd_compress_kv);  d : 64 or 128
  *   dtype     : ssd_dtype;  softmax_scale : 0 selects 1/sqrt(d)
  *   score_out : dev float [n_units, n_src], overwritten
  * The products run on the matrix cores with fp32 accumulation; the sum over i
@@ -256,7 +256,7 @@ int ssd_cfg_mix(const void *p, int n_seqs, int V, int dtype, float gamma, float 
  * One whole decode step of the layers in a single launch per layer group:
  * ssd_append_token, then ssd_decode_attn, then (compress != 0) the in-place
  * mode of ssd_compress_kv, with exactly their results.  Each (sequence, head)
- * is handled by one workgroup from append to selection, so the three steps
+ * is handled by one wavefront from append to selection, so the three steps
  * of Algorithm 1 cost one pass over the head's rows.
  *   q, k_new, v_new, out : dev [layer_end - layer_begin, B, H, d], cache dtype
  * Errors as for the three separate calls (overflow is checked first and

@@ -21,6 +21,8 @@
 // arrays are added in a fixed order at the end (bit-reproducible, no atomics).
 // Bound: HBM for the short prompts this is meant for (Q and K of a unit are read once from HBM,
 // re-reads of K tiles hit in L2); at n = 64, d = 128 a unit does 1 MFLOP on 32 KB.
+#include <cmath>
+
 #include "ssd_device.h"
 
 namespace ssd {
@@ -252,10 +254,10 @@ extern "C" int ssd_prefill_scores(const void *Q, const void *K, int n_units, int
     if (!Q || !K || !score_out) return fail(SSD_ERR_INVALID_ARG, "Q, K or score_out is NULL");
     if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(score_out, 4)) return fail(SSD_ERR_INVALID_ARG, "Q / K must be 16-byte aligned");
     if (n_units < 1) return fail(SSD_ERR_INVALID_ARG, "n_units=%d must be >= 1", n_units);
-    if (n_src < 1 || n_src > 1024) return fail(SSD_ERR_INVALID_ARG, "n_src=%d outside 1..1024", n_src);
+    if (n_src < 1 || n_src > 4096) return fail(SSD_ERR_INVALID_ARG, "n_src=%d outside 1..4096", n_src);
     if (d != 64 && d != 128) return fail(SSD_ERR_INVALID_ARG, "head_dim=%d, supported: 64, 128", d);
     if (dtype != SSD_F32 && dtype != SSD_BF16) return fail(SSD_ERR_INVALID_ARG, "bad dtype");
-    if (!(softmax_scale >= 0.f)) return fail(SSD_ERR_INVALID_ARG, "softmax_scale must be >= 0");
+    if (!(softmax_scale >= 0.f) || !std::isfinite(softmax_scale)) return fail(SSD_ERR_INVALID_ARG, "softmax_scale must be finite and >= 0");
     PrefillArgs a;
     a.Q = static_cast<const char *>(Q);
     a.K = static_cast<const char *>(K);

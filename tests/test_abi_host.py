@@ -253,7 +253,7 @@ def test_prefill_scores_rejects_bad_arguments_before_any_launch():
         a = dict(ok, **kw)
         return ssd.lib.ssd_prefill_scores(a["Q"], a["K"], a["n_units"], a["n_src"], a["d"], a["dtype"], a["scale"], a["out"], None)
 
-    for bad in (dict(Q=None), dict(K=None), dict(out=None), dict(Q=FAKE + 8), dict(n_units=0), dict(n_src=0), dict(n_src=1025),
+    for bad in (dict(Q=None), dict(K=None), dict(out=None), dict(Q=FAKE + 8), dict(n_units=0), dict(n_src=0), dict(n_src=4097),
                 dict(d=96), dict(dtype=7), dict(scale=-1.0), dict(scale=float("nan"))):
         assert call(**bad) == ssd.SSD_ERR_INVALID_ARG, bad
         assert ssd.ssd_last_error() != ""

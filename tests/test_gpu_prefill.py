@@ -55,6 +55,8 @@ def test_prefill_scores_match_oracle(dtype, d):
 
 def test_prefill_scores_largest_prompt_and_many_units():
     _case("bf16", 128, 1024, 2, 11, peaky=True)
+    _case("bf16", 128, 4096, 1, 13, peaky=True)                   # the longest prompt the entry point takes
+    _case("f32", 64, 1500, 1, 14)
     got = _case("bf16", 128, 64, 600, 12)                         # more workgroups than compute units
     assert np.isfinite(got).all()
 

@@ -21,7 +21,8 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
-] + (["-DSSD_PROBE"] if os.environ.get("SSD_PROBE") else [])
+] + (["-DSSD_PROBE"] if os.environ.get("SSD_PROBE") else [])      # SSD_PROBE=1: build with the measurement probes
+FLAGS += os.environ.get("SSD_EXTRA_FLAGS", "").split()              # extra compiler flags for experiments
 
 
 def sources():

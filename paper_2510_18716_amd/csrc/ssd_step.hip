@@ -12,6 +12,18 @@
 //
 // Roofline: HBM.  Algorithmic bytes per unit and step = rows * 2 * d * e (K and V) + 2 * d * e
 // (q in, out) + 8 * rows for a semantic unit's score read-modify-write.
+//
+// Measurement probes.  A build with -DSSD_PROBE keeps variants of the kernel that leave work out, selected
+// by the third argument of ssd_tune_attend (decimal fields; 0 = the real kernel):
+//   p % 100         1 or 11: loads only, no arithmetic; 2, 3, >= 10: no K/V stream at all
+//   p % 10          3..6: return before the output store / after it / after the score update / after the
+//                   selection (what each part of the tail costs)
+//   (p / 100) % 100 bit set of store classes to skip: 1 new token's rows, 2 output, 4 scores and positions,
+//                   8 promoted row; 16 = write all stores through at system scope
+//   p / 10000 % 100 pad the workgroup's LDS to that many KB (caps the workgroups per CU)
+//   p / 1000000     1 / 2: force the new token's rows to be stored at the start / after the end of the
+//                   stream (this field also works in ordinary builds)
+// The results of these variants are wrong on purpose; only their timings are used.
 #include "ssd_select.h"
 
 namespace ssd {

@@ -117,8 +117,8 @@ static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDes
 // One wave per unit, WPB units (consecutive heads of one sequence and layer) per workgroup;
 // grid = (ceil(H / WPB), B, layers of the launch).  Nothing below needs a workgroup barrier.
 #ifdef SSD_PROBE      // (probe / 100) & bit: the kernel with that class of stores left out (what the write path costs)
-#define SSD_ST16(bit, ptr, val) do { if (!((a.probe / 100) & (bit))) { if ((a.probe / 100) & 16) { const uint4 _v = (val); asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" :: "v"((char *)(ptr)), "v"(__builtin_bit_cast(u32x4_t, _v)) : "memory"); } else *reinterpret_cast<uint4 *>(ptr) = (val); } } while (0)
-#define SSD_ST4(bit, ptr, val) do { if (!((a.probe / 100) & (bit))) { if ((a.probe / 100) & 16) asm volatile("global_store_dword %0, %1, off sc0 sc1" :: "v"(ptr), "v"(val) : "memory"); else *(ptr) = (val); } } while (0)
+#define SSD_ST16(bit, ptr, val) do { if (!((a.probe / 100 % 100) & (bit))) { if ((a.probe / 100 % 100) & 16) { const uint4 _v = (val); asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" :: "v"((char *)(ptr)), "v"(__builtin_bit_cast(u32x4_t, _v)) : "memory"); } else *reinterpret_cast<uint4 *>(ptr) = (val); } } while (0)
+#define SSD_ST4(bit, ptr, val) do { if (!((a.probe / 100 % 100) & (bit))) { if ((a.probe / 100 % 100) & 16) asm volatile("global_store_dword %0, %1, off sc0 sc1" :: "v"(ptr), "v"(val) : "memory"); else *(ptr) = (val); } } while (0)
 #else
 #define SSD_ST16(bit, ptr, val) (*reinterpret_cast<uint4 *>(ptr) = (val))
 #define SSD_ST4(bit, ptr, val) (*(ptr) = (val))
@@ -388,7 +388,7 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
     while (wpb > 1 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;
     size_t lds = (size_t)wpb * a.wave_lds;
 #ifdef SSD_PROBE
-    if ((size_t)(g_probe % 1000000 / 10000) * 1024 > lds) lds = (size_t)(g_probe % 1000000 / 10000) * 1024;   // occupancy experiments: pad the workgroup's LDS
+    if ((size_t)(g_probe / 10000 % 100) * 1024 > lds) lds = (size_t)(g_probe / 10000 % 100) * 1024;   // occupancy experiments: pad the workgroup's LDS
 #endif
     const dim3 blocks((unsigned)((max_type_heads + wpb - 1) / wpb), (unsigned)B, (unsigned)(2 * layers));
 #define SSD_CASE(CH_, WPB_) if (ch == CH_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_>(full, blocks, lds, fused, s); return hipGetLastError(); }

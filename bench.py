@@ -178,7 +178,12 @@ def main():
     accumulate = not args.no_accumulate
     ht = workload.head_map(wl)
     K_steps, W_steps = args.steps, args.warmup
-    assert K_steps + W_steps < wl.n_total - wl.S - wl.W - 2, "too many steps for this workload"
+    assert K_steps >= 1 and W_steps >= 0
+    # Timed steps are the last ones of a raster decode, when every window and budget is full.  One decode has
+    # room for max_k of them after the fill and the warm-up; more are taken from further decodes of the same image.
+    max_k = wl.n_total - wl.S - wl.W - 3 - W_steps
+    assert max_k >= 1, "too many warm-up steps for this workload"
+    passes = [max_k] * (K_steps // max_k) + ([K_steps % max_k] if K_steps % max_k else [])
     if args.tune:
         t = [int(x) for x in args.tune.split(",")] + [0]
         assert ssd.lib.ssd_tune_attend(t[0], t[1], t[2]) == 0
@@ -192,8 +197,7 @@ def main():
     cfg = make_config(wl.L, wl.B, wl.H, wl.d, wl.dtype, wl.W, wl.S, wl.M, wl.R, wl.C, 0.0, int(wl.alg2))
     cache = ssd.Cache(cfg, ht, device=dev)
     out = torch.empty((wl.L, wl.B, wl.H, wl.d), dtype=wl.torch_dtype, device=dev)
-    p_timed = wl.n_total - K_steps
-    p_warm = p_timed - W_steps
+    p_timed = wl.n_total - passes[0]          # first timed position of the first (usually the only) decode
 
     def measure(lpc, with_events):
         """Decode the whole sequence from an empty cache with `lpc` layers per call; time the last K_steps.
@@ -239,31 +243,37 @@ def main():
             if ev is not None and fused:
                 ev[1].record()
 
-        cache.reset()
-        for p in range(0, wl.n0):                   # the prompt, through ordinary decode steps
-            step(p)
-        torch.cuda.synchronize()
-        t_vis = time.perf_counter()
-        for p in range(wl.n0, p_warm):              # the earlier part of the image (fills every window and budget)
-            step(p)
-        torch.cuda.synchronize()
-        for p in range(p_warm, p_timed):
-            step(p)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for p in range(p_timed, wl.n_total):
-            step(p)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        dt = t1 - t0
-        whole = t1 - t_vis                          # all N visual tokens, two intermediate synchronisations included
+        dt, whole = 0.0, None
+        for k_i in passes:
+            p_t = wl.n_total - k_i
+            p_w = p_t - W_steps
+            cache.reset()
+            for p in range(0, wl.n0):               # the prompt, through ordinary decode steps
+                step(p)
+            torch.cuda.synchronize()
+            t_vis = time.perf_counter()
+            for p in range(wl.n0, p_w):             # the earlier part of the image (fills every window and budget)
+                step(p)
+            torch.cuda.synchronize()
+            for p in range(p_w, p_t):
+                step(p)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for p in range(p_t, wl.n_total):
+                step(p)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            dt += t1 - t0
+            if whole is None:
+                whole = t1 - t_vis                  # all N visual tokens, two intermediate synchronisations included
 
         # algorithmic bytes of the timed launches, from the counters each launch ran with (host-only replay)
         acct = []
         ssd.lib.ssd_cache_set_launch(cache.handle, 0)
-        cache.reset()
-        for p in range(0, wl.n_total):
-            step(p, acct=acct if p >= p_timed else None)
+        for k_i in passes:
+            cache.reset()
+            for p in range(0, wl.n_total):
+                step(p, acct=acct if p >= wl.n_total - k_i else None)
         ssd.lib.ssd_cache_set_launch(cache.handle, 1)
         bytes_launch = float(np.mean(acct))
         res = {"seconds": dt, "ms_per_step": dt / K_steps * 1e3, "value": wl.prompts * K_steps / dt,
@@ -277,15 +287,18 @@ def main():
         # second pass, same decode from an empty cache, with HIP events on the launch stream.  Fused: one
         # event pair around the back-to-back launches of a step (they are all the dominant kernel), so the
         # events themselves do not sit between launches.  Separate: a pair around each attention launch.
-        cache.reset()
-        for p in range(0, p_timed):
-            step(p)
         n_ev = 2 if fused else 2 * len(calls)
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(n_ev)] for _ in range(K_steps)]
-        torch.cuda.synchronize()
-        for i, p in enumerate(range(p_timed, wl.n_total)):
-            step(p, ev=evs[i])
-        torch.cuda.synchronize()
+        evs = []
+        for k_i in passes:
+            cache.reset()
+            for p in range(0, wl.n_total - k_i):
+                step(p)
+            evs_i = [[torch.cuda.Event(enable_timing=True) for _ in range(n_ev)] for _ in range(k_i)]
+            torch.cuda.synchronize()
+            for i, p in enumerate(range(wl.n_total - k_i, wl.n_total)):
+                step(p, ev=evs_i[i])
+            torch.cuda.synchronize()
+            evs += evs_i
         if fused:
             durs = [e[0].elapsed_time(e[1]) / len(calls) for e in evs]
         else:
@@ -318,7 +331,8 @@ def main():
                    "step": "append + attend(+score accumulate) + compress, every layer",
                    "launches_per_step": head["launches_per_step"],
                    "entry_points": "ssd_decode_step" if fused else "ssd_append_token, ssd_decode_attn, ssd_compress_kv",
-                   "timed_at": "last %d tokens of the raster decode (n -> %d)" % (K_steps, wl.n_total)},
+                   "timed_at": "last %d tokens of the raster decode (n -> %d)" % (passes[0], wl.n_total) +
+                               ("" if len(passes) == 1 else ", over %d decodes of the image" % len(passes))},
         "algorithmic_GB_per_step": head["algorithmic_GB_per_step"],
         "whole_step_GBps": head["algorithmic_GB_per_step"] / (head["ms_per_step"] / 1e3),
         "setup_s": {"generate_inputs": round(t_gen, 2)},
@@ -367,11 +381,12 @@ def main():
         for p in range(p_timed, wl.n_total):
             mb_step(p)
         torch.cuda.synchronize()
+        k_mb = wl.n_total - p_timed
         dtm = time.perf_counter() - t0
         result["two_half_batches_two_streams"] = {
-            "value": wl.prompts * K_steps / dtm, "unit": "tokens/s", "ms_per_step": dtm / K_steps * 1e3,
-            "launches_per_step": ns * wl.L, "whole_step_GBps": head["algorithmic_GB_per_step"] / (dtm / K_steps),
-            "frac_of_hbm_peak": head["algorithmic_GB_per_step"] / (dtm / K_steps) / HBM_PEAK_GBS,
+            "value": wl.prompts * k_mb / dtm, "unit": "tokens/s", "ms_per_step": dtm / k_mb * 1e3, "steps": k_mb,
+            "launches_per_step": ns * wl.L, "whole_step_GBps": head["algorithmic_GB_per_step"] / (dtm / k_mb),
+            "frac_of_hbm_peak": head["algorithmic_GB_per_step"] / (dtm / k_mb) / HBM_PEAK_GBS,
             "note": "same step, the sequences split into two caches of %d whose per-layer launches go to two streams: the start and "
                     "the tail of one half's launch overlap the other's; each half keeps its layer order" % Bm}
         del caches

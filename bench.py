@@ -48,14 +48,18 @@ def algorithmic_bytes_attend(wl, ht, layers, state):
     n, m, c = state
     row = row_bytes(wl)
     # Algorithm 2: a spatial head also reads the tokens appended since the last compression (c - R of them)
-    rows_sp = min(n, wl.S + wl.W + (max(c - wl.R, 0) if wl.alg2 else 0))
-    rows_se = m + c
     total = 0
     for l in layers:
-        hs = int((ht[l] == 0).sum())
-        hm = wl.H - hs
-        total += wl.B * hs * (rows_sp * 2 * row + 2 * row)
-        total += wl.B * hm * (rows_se * 2 * row + rows_se * 8 + 2 * row)
+        for h in range(wl.H) if wl.head_budget is not None else (None,):     # budgets per head: head by head
+            heads = 1 if h is not None else None
+            if h is None or ht[l, h] == 0:
+                rows_sp = min(n, wl.S + wl.W_of(l, h) + (max(c - wl.R, 0) if wl.alg2 else 0))
+                hs = int((ht[l] == 0).sum()) if heads is None else 1
+                total += wl.B * hs * (rows_sp * 2 * row + 2 * row)
+            if h is None or ht[l, h] == 1:
+                rows_se = min(m, wl.M_of(l, h)) + c
+                hm = int((ht[l] == 1).sum()) if heads is None else 1
+                total += wl.B * hm * (rows_se * 2 * row + rows_se * 8 + 2 * row)
     return total
 
 
@@ -146,6 +150,8 @@ def main():
     ap.add_argument("--no-accumulate", action="store_true", help="experiment: attention without the running-score update")
     ap.add_argument("--sweep5", action="store_true",
                     help="large-batch sweep (configuration 5): spatial fraction x W x M at B = 512, one JSON line with a list")
+    ap.add_argument("--head-budgets", type=str, default="",
+                    help="LO,HI: head-wise allocation -- every head its own W_h / M_h, seeded uniform in [LO, HI]")
     ap.add_argument("--alg2", action="store_true",
                     help="row-buffer variant (Algorithm 2): both head types read a 24-token row buffer, compression every 24 tokens")
     args = ap.parse_args()
@@ -177,6 +183,13 @@ def main():
         wl = wl.replace(grid_h=args.grid_rows, name=wl.name + "-rows%d" % args.grid_rows)
     accumulate = not args.no_accumulate
     ht = workload.head_map(wl)
+    if args.head_budgets:
+        lo, hi = (int(x) for x in args.head_budgets.split(","))
+        rng = np.random.default_rng(wl.seed)
+        hb = rng.integers(lo, hi + 1, (wl.L, wl.H))
+        # W and M of the description become the largest budgets (what sizes the units and bounds the fill time)
+        wl = wl.replace(head_budget=tuple(tuple(int(x) for x in r) for r in hb), W=int(hb.max()), M=int(hb.max()),
+                        name=wl.name + "-heads%d-%d" % (lo, hi))
     K_steps, W_steps = args.steps, args.warmup
     assert K_steps >= 1 and W_steps >= 0
     # Timed steps are the last ones of a raster decode, when every window and budget is full.  One decode has
@@ -198,7 +211,7 @@ def main():
     t_gen = time.time() - t0
     sched = workload.compress_schedule(wl)
     cfg = make_config(wl.L, wl.B, wl.H, wl.d, wl.dtype, wl.W, wl.S, wl.M, wl.R, wl.C, 0.0, int(wl.alg2))
-    cache = ssd.Cache(cfg, ht, device=dev)
+    cache = ssd.Cache(cfg, ht, device=dev, head_budget=None if wl.head_budget is None else np.asarray(wl.head_budget, np.int32))
     out = torch.empty((wl.L, wl.B, wl.H, wl.d), dtype=wl.torch_dtype, device=dev)
     p_timed = wl.n_total - passes[0]          # first timed position of the first (usually the only) decode
 

@@ -67,7 +67,8 @@ typedef enum ssd_status {
 /*
  * Shape and policy parameters (Algorithm 1 "Parameter" line; Sec. 3.3).
  * One config describes one cache: all layers share S, R, C, and also W and M
- * unless ssd_cache_init_layered gives those per layer.
+ * unless ssd_cache_init_layered gives those per layer or ssd_cache_init_heads
+ * per head.
  */
 typedef struct ssd_config {
     int32_t n_layers;      /* L                                                            */
@@ -124,8 +125,32 @@ size_t ssd_cache_bytes_layered(const ssd_config *cfg, const uint8_t *head_type,
 int ssd_cache_init_layered(const ssd_config *cfg, const uint8_t *head_type,
                            const int32_t *window, const int32_t *budget, void *dev_mem,
                            size_t bytes, ssd_cache **out);
-/* Window and budget of one layer (either output may be NULL). */
+/* Window and budget of one layer (either output may be NULL); with budgets per head, the layer's largest. */
 int ssd_cache_layer_budget(const ssd_cache *cache, int layer, int32_t *window, int32_t *budget);
+
+/*
+ * The same two calls with a budget per head (head-wise adaptive allocation,
+ * which Sec. 5 "Integration with Other Compression Techniques" names beside
+ * the layer-wise one).
+ *   head_budget : host int32 [L*H]; entry [l*H + h] is the window W_h of head h
+ *                 of layer l if head_type says it is a spatial head (1..65535),
+ *                 its heavy-hitter budget M_h if it is a semantic head (>= 1,
+ *                 M_h + C <= 4096).  cfg->window / cfg->budget are ignored
+ *                 except in a layer that has no head of that type.  Copied.
+ * Layout: every unit of a layer keeps one size, that of the layer's largest
+ * W_h (spatial) or M_h (semantic); head h uses a ring of W_h slots, or the
+ * first M_h heavy slots, of its unit, and the row buffer of every semantic
+ * head of the layer starts at slot max_h M_h.  So memory is that of the
+ * largest head, while the rows a step reads are each head's own.  Every call
+ * then takes one launch per layer.  Everything else is unchanged; the host
+ * counter m of ssd_cache_layer_state is the layer's largest (a head has
+ * min(m, M_h) heavy slots in use).
+ */
+size_t ssd_cache_bytes_heads(const ssd_config *cfg, const uint8_t *head_type, const int32_t *head_budget);
+int ssd_cache_init_heads(const ssd_config *cfg, const uint8_t *head_type, const int32_t *head_budget,
+                         void *dev_mem, size_t bytes, ssd_cache **out);
+/* W_h (spatial head) or M_h (semantic head) of one head, whichever init call made the cache. */
+int ssd_cache_head_budget(const ssd_cache *cache, int layer, int head, int32_t *value);
 
 /* Free the descriptor (not dev_mem).  NULL is allowed. */
 void ssd_cache_free(ssd_cache *cache);

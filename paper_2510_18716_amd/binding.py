@@ -49,6 +49,12 @@ lib.ssd_cache_init_layered.argtypes = [C.POINTER(SsdConfig), _vp, _vp, _vp, _vp,
 lib.ssd_cache_init_layered.restype = C.c_int
 lib.ssd_cache_layer_budget.argtypes = [_vp, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
 lib.ssd_cache_layer_budget.restype = C.c_int
+lib.ssd_cache_bytes_heads.argtypes = [C.POINTER(SsdConfig), _vp, _vp]
+lib.ssd_cache_bytes_heads.restype = C.c_size_t
+lib.ssd_cache_init_heads.argtypes = [C.POINTER(SsdConfig), _vp, _vp, _vp, C.c_size_t, C.POINTER(_vp)]
+lib.ssd_cache_init_heads.restype = C.c_int
+lib.ssd_cache_head_budget.argtypes = [_vp, C.c_int, C.c_int, C.POINTER(C.c_int32)]
+lib.ssd_cache_head_budget.restype = C.c_int
 lib.ssd_cache_free.argtypes = [_vp]
 lib.ssd_cache_free.restype = None
 lib.ssd_cache_reset.argtypes = [_vp]
@@ -158,8 +164,21 @@ def _per_layer(x, L):
     return a
 
 
-def ssd_cache_bytes(cfg: SsdConfig, head_type: np.ndarray, window=None, budget=None) -> int:
+def _per_head(x, L, H):
+    """Host int32 [L*H] array of per-head budgets, or None."""
+    if x is None:
+        return None
+    a = np.ascontiguousarray(x, dtype=np.int32)
+    if a.size != L * H:
+        raise ValueError("per-head array must have one entry per (layer, head)")
+    return a.reshape(-1)
+
+
+def ssd_cache_bytes(cfg: SsdConfig, head_type: np.ndarray, window=None, budget=None, head_budget=None) -> int:
     ht = np.ascontiguousarray(head_type, dtype=np.uint8)
+    hb = _per_head(head_budget, cfg.n_layers, cfg.n_heads)
+    if hb is not None:
+        return lib.ssd_cache_bytes_heads(C.byref(cfg), ht.ctypes.data, hb.ctypes.data)
     w, m = _per_layer(window, cfg.n_layers), _per_layer(budget, cfg.n_layers)
     return lib.ssd_cache_bytes_layered(C.byref(cfg), ht.ctypes.data, None if w is None else w.ctypes.data,
                                        None if m is None else m.ctypes.data)
@@ -173,13 +192,20 @@ class Cache:
     on a machine without a GPU.
     """
 
-    def __init__(self, cfg: SsdConfig, head_type: np.ndarray, device="cuda", window=None, budget=None):
-        """window, budget: optional per-layer lists [L] (ssd_cache_init_layered)."""
+    def __init__(self, cfg: SsdConfig, head_type: np.ndarray, device="cuda", window=None, budget=None, head_budget=None):
+        """window, budget: optional per-layer lists [L] (ssd_cache_init_layered);
+        head_budget: optional [L, H] array, W_h of a spatial head / M_h of a semantic head (ssd_cache_init_heads)."""
         self.cfg = cfg
         self.head_type = np.ascontiguousarray(head_type, dtype=np.uint8)
         w, m = _per_layer(window, cfg.n_layers), _per_layer(budget, cfg.n_layers)
+        hb = _per_head(head_budget, cfg.n_layers, cfg.n_heads)
+        if hb is not None and (w is not None or m is not None):
+            raise ValueError("budgets are given per layer or per head, not both")
         wp, mp = (None if w is None else w.ctypes.data), (None if m is None else m.ctypes.data)
-        nbytes = lib.ssd_cache_bytes_layered(C.byref(cfg), self.head_type.ctypes.data, wp, mp)
+        if hb is not None:
+            nbytes = lib.ssd_cache_bytes_heads(C.byref(cfg), self.head_type.ctypes.data, hb.ctypes.data)
+        else:
+            nbytes = lib.ssd_cache_bytes_layered(C.byref(cfg), self.head_type.ctypes.data, wp, mp)
         if nbytes == 0:
             raise SsdError(SSD_ERR_INVALID_ARG, "ssd_cache_bytes")
         self.head_type = self.head_type.reshape(cfg.n_layers, cfg.n_heads)
@@ -191,8 +217,12 @@ class Cache:
         else:
             self.mem = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
             base = (self.mem.data_ptr() + 255) // 256 * 256
-        _check(lib.ssd_cache_init_layered(C.byref(cfg), self.head_type.ctypes.data, wp, mp, base, nbytes, C.byref(self._h)),
-               "ssd_cache_init")
+        if hb is not None:
+            _check(lib.ssd_cache_init_heads(C.byref(cfg), self.head_type.ctypes.data, hb.ctypes.data, base, nbytes, C.byref(self._h)),
+                   "ssd_cache_init_heads")
+        else:
+            _check(lib.ssd_cache_init_layered(C.byref(cfg), self.head_type.ctypes.data, wp, mp, base, nbytes, C.byref(self._h)),
+                   "ssd_cache_init")
         if device is None:
             _check(lib.ssd_cache_set_launch(self._h, 0), "ssd_cache_set_launch")
         self.torch_dtype = torch.bfloat16 if cfg.dtype == SSD_BF16 else torch.float32
@@ -220,6 +250,12 @@ class Cache:
         w, m = C.c_int32(0), C.c_int32(0)
         _check(lib.ssd_cache_layer_budget(self._h, layer, C.byref(w), C.byref(m)), "ssd_cache_layer_budget")
         return w.value, m.value
+
+    def head_budget(self, layer: int, head: int) -> int:
+        """W_h of a spatial head, M_h of a semantic head."""
+        v = C.c_int32(0)
+        _check(lib.ssd_cache_head_budget(self._h, layer, head, C.byref(v)), "ssd_cache_head_budget")
+        return v.value
 
     def layer_window(self, layer: int) -> int:
         out = C.c_int32(0)

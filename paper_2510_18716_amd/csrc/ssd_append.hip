@@ -18,6 +18,8 @@ struct AppendArgs {
     int slot_sp;         // destination slot of spatial heads
     int slot_se;         // destination slot of semantic heads
     int pos;             // absolute position of the token
+    int heads;           // budgets per head: a spatial head's slot follows from its own window
+    HeadTable ht;
 };
 
 __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
@@ -36,7 +38,8 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
     const UnitRef u = unit_ref(a.g, a.lm.layer[lrel], b, h);
     const size_t src_row = ((size_t)(a.layer_off + lrel) * BH + rem) * (size_t)a.g.row_bytes;
     const char *src = (kv ? a.v_new : a.k_new) + src_row + (size_t)sub * 16u;
-    const int slot = u.sem ? a.slot_se : a.slot_sp;
+    int slot = u.sem ? a.slot_se : a.slot_sp;
+    if (a.heads && !u.sem) slot = ring_slot(a.g.S, a.ht.v[h] + (a.g.RW - a.g.W), a.pos);
     char *dst = (kv ? u.V : u.K) + (size_t)slot * (size_t)a.g.row_bytes + (size_t)sub * 16u;
     *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
     if (u.sem && f == 0) {
@@ -79,6 +82,8 @@ extern "C" int ssd_append_token(ssd_cache *cache, int layer_begin, int layer_end
             a.pos = st.n;
             a.slot_sp = spatial_slot(cache, lb, st.n);
             a.slot_se = cache->Ml[lb] + (st.base + st.c) % cf.stage_cap;
+            a.heads = per_head(cache) ? 1 : 0;
+            fill_head_table(cache, lb, &a.ht);
             const long long threads = (long long)a.n_units * 2 * a.lpr;
             const unsigned blocks = (unsigned)((threads + 255) / 256);
             hipLaunchKernelGGL(append_kernel, dim3(blocks), dim3(256), 0, s, a);

@@ -12,6 +12,9 @@
 // S + ((p-S) mod W) holds position p >= S, so the ring always contains the W newest tokens.
 // Semantic slots: 0..M-1 heavy hitters (the first m in use); M..M+C-1 the row buffer of
 // Algorithm 2, used as a ring so that the R protected newest tokens never have to move.
+// W and M may differ per layer (the layout is per layer anyway) and per head: with budgets per head every
+// unit of a layer keeps the size of the layer's largest W_h / M_h, and head h uses a ring of W_h slots, or
+// the first M_h heavy slots, of its unit; the row buffer starts at slot max M_h for every semantic head.
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -76,6 +79,36 @@ static int validate(const ssd_config *c, const uint8_t *head_type, const int32_t
             if (budget[l] < 1) return fail(SSD_ERR_INVALID_ARG, "budget[%d]=%d must be >= 1", l, budget[l]);
             if ((int64_t)budget[l] + c->stage_cap > 4096) return fail(SSD_ERR_INVALID_ARG, "budget[%d] + C = %lld exceeds 4096", l, (long long)budget[l] + c->stage_cap);
         }
+    }
+    return SSD_OK;
+}
+
+// Budgets per head: checks them and reduces them to the per-layer maxima that size the units.
+static int validate_heads(const ssd_config *c, const uint8_t *head_type, const int32_t *head_budget,
+                          std::vector<int32_t> *Wl, std::vector<int32_t> *Ml) {
+    if (!c || !head_type) return fail(SSD_ERR_INVALID_ARG, "config or head_type is NULL");
+    if (!head_budget) return fail(SSD_ERR_INVALID_ARG, "head_budget is NULL");
+    if (c->n_layers < 1 || c->n_layers > 1024 || c->n_heads < 1 || c->n_heads > HMAX)
+        return fail(SSD_ERR_INVALID_ARG, "n_layers=%d or n_heads=%d out of range", c->n_layers, c->n_heads);
+    Wl->assign(c->n_layers, c->window);
+    Ml->assign(c->n_layers, c->budget);
+    for (int l = 0; l < c->n_layers; ++l) {
+        int wmax = 0, mmax = 0;
+        for (int h = 0; h < c->n_heads; ++h) {
+            const size_t i = (size_t)l * c->n_heads + h;
+            const int32_t v = head_budget[i];
+            if (head_type[i] == SSD_SEMANTIC) {
+                if (v < 1 || (int64_t)v + c->stage_cap > 4096)
+                    return fail(SSD_ERR_INVALID_ARG, "head_budget[%d,%d]=%d: a semantic head's M must be >= 1 with M + C <= 4096", l, h, v);
+                mmax = v > mmax ? v : mmax;
+            } else {
+                if (v < 1 || v > 65535)
+                    return fail(SSD_ERR_INVALID_ARG, "head_budget[%d,%d]=%d: a spatial head's W must be in 1..65535", l, h, v);
+                wmax = v > wmax ? v : wmax;
+            }
+        }
+        if (wmax > 0) (*Wl)[l] = wmax;
+        if (mmax > 0) (*Ml)[l] = mmax;
     }
     return SSD_OK;
 }
@@ -160,33 +193,17 @@ void apply_compress_counters(ssd_cache *c, int l) {
     x.c = cf.recent;
 }
 
+void fill_head_table(const ssd_cache *c, int l, HeadTable *out) {
+    const int H = c->cfg.n_heads;
+    for (int h = 0; h < HMAX; ++h) out->v[h] = per_head(c) && h < H ? c->head_budget[(size_t)l * H + h] : 0;
+}
+
 int spatial_slot(const ssd_cache *c, int l, int p) {
-    const int S = c->cfg.n_init_sink;
-    const int RW = c->Wl[l] + (c->cfg.spatial_row_buffer ? c->cfg.stage_cap : 0);
-    return p < S ? p : S + (p - S) % RW;
+    return ring_slot(c->cfg.n_init_sink, c->Wl[l] + (c->cfg.spatial_row_buffer ? c->cfg.stage_cap : 0), p);
 }
 
 Segs spatial_segs(const ssd_cache *c, int l, const LayerState &st) {
-    Segs s = {{0, 0, 0}, {0, 0, 0}, 0};
-    const int S = c->cfg.n_init_sink, W = c->Wl[l];
-    if (!c->cfg.spatial_row_buffer) {
-        // Algorithm 1: the ring fills front to back, so the valid slots are always a prefix
-        const int cap = S + W;
-        s.len[0] = st.n < cap ? st.n : cap;
-        s.total = s.len[0];
-        return s;
-    }
-    // Algorithm 2: sinks, then positions [max(S, nc - W), n) in a ring of W + C slots
-    const int RW = W + c->cfg.stage_cap;
-    s.len[0] = st.n < S ? st.n : S;
-    const int lo = st.nc - W > S ? st.nc - W : S;
-    const int count = st.n > lo ? st.n - lo : 0;
-    const int start = S + (lo - S) % RW;
-    const int first = count < S + RW - start ? count : S + RW - start;
-    s.start[1] = start; s.len[1] = first;
-    s.start[2] = S;     s.len[2] = count - first;
-    s.total = s.len[0] + s.len[1] + s.len[2];
-    return s;
+    return ring_segs(c->cfg.n_init_sink, c->Wl[l], c->cfg.stage_cap, c->cfg.spatial_row_buffer != 0, st.n, st.nc);
 }
 
 Segs semantic_segs(const ssd_cache *c, int l, const LayerState &st) {
@@ -203,22 +220,15 @@ Segs semantic_segs(const ssd_cache *c, int l, const LayerState &st) {
     return s;
 }
 
-Segs spatial_segs_fused(const ssd_cache *c, int l, const LayerState &before, const LayerState &after, int new_slot) {
-    if (c->cfg.spatial_row_buffer) return spatial_segs(c, l, before);   // the new token's slot is never a retained one
-    // Algorithm 1: the new token overwrites the oldest ring slot; stream the prefix around it
-    Segs s = spatial_segs(c, l, after);
-    const int end = s.len[0];
-    if (new_slot < 0 || new_slot >= end) return s;
-    s.start[0] = 0;            s.len[0] = new_slot;
-    s.start[1] = new_slot + 1; s.len[1] = end - new_slot - 1;
-    s.total = end - 1;
-    return s;
+Segs spatial_segs_fused(const ssd_cache *c, int l, const LayerState &before, const LayerState &, int new_slot) {
+    return ring_segs_fused(c->cfg.n_init_sink, c->Wl[l], c->cfg.stage_cap, c->cfg.spatial_row_buffer != 0, before.n, before.nc, new_slot);
 }
 
 static bool same_geom(const ssd_cache *c, int a, int b) { return c->Wl[a] == c->Wl[b] && c->Ml[a] == c->Ml[b]; }
 
 int same_state_run(const ssd_cache *c, int lb, int le) {
     int l = lb + 1;
+    if (per_head(c)) return l;
     // layers with and without semantic heads never share a launch: only the former have a row buffer
     const bool buf = has_buffer(c, lb), has_se = c->ldesc[lb].n_se > 0;
     while (l < le && l - lb < LMAX && c->st[l] == c->st[lb] && same_geom(c, l, lb) && has_buffer(c, l) == buf &&
@@ -229,20 +239,26 @@ int same_state_run(const ssd_cache *c, int lb, int le) {
 
 int same_geom_run(const ssd_cache *c, int lb, int le) {
     int l = lb + 1;
+    if (per_head(c)) return l;
     while (l < le && l - lb < LMAX && same_geom(c, l, lb)) ++l;
     return l;
 }
 
 // ---- export ---------------------------------------------------------------
 
-__global__ void export_kernel(Geom g, LayerDesc ld, LayerState st, Segs se, int lo, int slots, int32_t *pos_out,
-                              int32_t *count_out, float *score_out) {
+__global__ void export_kernel(Geom g, LayerDesc ld, LayerState st, Segs se, int ref, int slots, HeadTable ht, int heads,
+                              int32_t *pos_out, int32_t *count_out, float *score_out) {
     const int unit = blockIdx.x;   // b*H + h
     const int b = unit / g.H, h = unit % g.H;
     const UnitRef u = unit_ref(g, ld, b, h);
     const size_t o = (size_t)unit * (size_t)slots;
     int count;
     if (u.sem) {
+        if (heads) {                                  // this head's share of the heavy slots
+            const int m_h = st.m < ht.v[h] ? st.m : ht.v[h];
+            se.total -= se.len[0] - m_h;
+            se.len[0] = m_h;
+        }
         count = se.total;
         for (int s = threadIdx.x; s < slots; s += blockDim.x) {
             bool valid = false;
@@ -251,7 +267,10 @@ __global__ void export_kernel(Geom g, LayerDesc ld, LayerState st, Segs se, int 
             if (score_out) score_out[o + s] = valid ? u.score[s] : 0.f;
         }
     } else {
-        // retained: sinks and positions [lo, n); lo was computed on the host
+        // retained: sinks and positions [lo, n), the window being cut at `ref` tokens
+        const int W = heads ? ht.v[h] : g.W;
+        const int RW = W + (g.RW - g.W);
+        const int lo = ref - W > g.S ? ref - W : g.S;
         const int n_sink = st.n < g.S ? st.n : g.S;
         const int n_win = st.n > lo ? st.n - lo : 0;
         count = n_sink + n_win;
@@ -259,12 +278,12 @@ __global__ void export_kernel(Geom g, LayerDesc ld, LayerState st, Segs se, int 
             int p = -1;
             if (s < g.S) {
                 p = s < st.n ? s : -1;
-            } else if (s < g.S + g.RW && n_win > 0) {
+            } else if (s < g.S + RW && n_win > 0) {
                 // newest position whose ring slot is s
                 const int j = s - g.S;
                 const int last = st.n - 1;
-                const int kl = (last - g.S) % g.RW;
-                const int cand = last - ((kl - j + g.RW) % g.RW);
+                const int kl = (last - g.S) % RW;
+                const int cand = last - ((kl - j + RW) % RW);
                 p = cand >= lo ? cand : -1;
             }
             if (pos_out) pos_out[o + s] = p;
@@ -290,6 +309,29 @@ size_t ssd_cache_bytes_layered(const ssd_config *cfg, const uint8_t *head_type, 
     clear_error();
     if (validate(cfg, head_type, window, budget) != SSD_OK) return 0;
     return plan_layout(cfg, head_type, window, budget, nullptr);
+}
+
+size_t ssd_cache_bytes_heads(const ssd_config *cfg, const uint8_t *head_type, const int32_t *head_budget) {
+    clear_error();
+    std::vector<int32_t> Wl, Ml;
+    if (validate_heads(cfg, head_type, head_budget, &Wl, &Ml) != SSD_OK) return 0;
+    return ssd_cache_bytes_layered(cfg, head_type, Wl.data(), Ml.data());
+}
+
+int ssd_cache_init_heads(const ssd_config *cfg, const uint8_t *head_type, const int32_t *head_budget, void *dev_mem, size_t bytes,
+                         ssd_cache **out) {
+    clear_error();
+    if (!out) return fail(SSD_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    std::vector<int32_t> Wl, Ml;
+    int rc = validate_heads(cfg, head_type, head_budget, &Wl, &Ml);
+    if (rc != SSD_OK) return rc;
+    rc = ssd_cache_init_layered(cfg, head_type, Wl.data(), Ml.data(), dev_mem, bytes, out);
+    if (rc != SSD_OK) return rc;
+    const size_t n = (size_t)cfg->n_layers * cfg->n_heads;
+    (*out)->head_budget.resize(n);
+    for (size_t i = 0; i < n; ++i) (*out)->head_budget[i] = (uint16_t)head_budget[i];
+    return SSD_OK;
 }
 
 int ssd_cache_init_layered(const ssd_config *cfg, const uint8_t *head_type, const int32_t *window, const int32_t *budget,
@@ -368,6 +410,18 @@ int ssd_cache_layer_budget(const ssd_cache *cache, int layer, int32_t *window, i
     return SSD_OK;
 }
 
+int ssd_cache_head_budget(const ssd_cache *cache, int layer, int head, int32_t *value) {
+    clear_error();
+    int rc = check_layers(cache, layer, layer + 1);
+    if (rc != SSD_OK) return rc;
+    if (head < 0 || head >= cache->cfg.n_heads) return fail(SSD_ERR_INVALID_ARG, "head=%d outside 0..%d", head, cache->cfg.n_heads - 1);
+    if (!value) return fail(SSD_ERR_INVALID_ARG, "output pointer is NULL");
+    const size_t i = (size_t)layer * cache->cfg.n_heads + head;
+    if (per_head(cache)) *value = cache->head_budget[i];
+    else *value = cache->head_type[i] == SSD_SEMANTIC ? cache->Ml[layer] : cache->Wl[layer];
+    return SSD_OK;
+}
+
 int ssd_cache_export_slots(const ssd_cache *cache) {
     if (!cache) return 0;
     int slots = 0;
@@ -390,11 +444,11 @@ int ssd_cache_export(ssd_cache *cache, int layer, int32_t *pos, int32_t *count, 
     const LayerState st = cache->st[layer];
     const Segs se = semantic_segs(cache, layer, st);
     const int units = cache->cfg.n_seqs * cache->cfg.n_heads;
-    const int S = cache->cfg.n_init_sink, W = cache->Wl[layer];
     const int ref = cache->cfg.spatial_row_buffer ? st.nc : st.n;      // Algorithm 1: the window always ends at n
-    const int lo = ref - W > S ? ref - W : S;
-    hipLaunchKernelGGL(export_kernel, dim3(units), dim3(64), 0, s, make_geom(cache, layer), cache->ldesc[layer], st, se, lo,
-                       ssd_cache_export_slots(cache), pos, count, score);
+    HeadTable ht;
+    fill_head_table(cache, layer, &ht);
+    hipLaunchKernelGGL(export_kernel, dim3(units), dim3(64), 0, s, make_geom(cache, layer), cache->ldesc[layer], st, se, ref,
+                       ssd_cache_export_slots(cache), ht, per_head(cache) ? 1 : 0, pos, count, score);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "export launch");
     return SSD_OK;

@@ -14,6 +14,8 @@ struct CompressArgs {
     int base;          // ring index of the oldest buffered token
     int R;
     int lpr;           // 16-byte fragments per row
+    int heads;         // budgets per head
+    HeadTable ht;
 };
 
 // One workgroup per (layer, sequence, head); spatial heads return at once.
@@ -26,15 +28,17 @@ __global__ __launch_bounds__(THREADS) void compress_inplace_kernel(CompressArgs 
     const int rem = unit % BH;
     const UnitRef u = unit_ref(a.g, a.lm.layer[lrel], rem / a.g.H, rem % a.g.H);
     if (!u.sem) return;                       // uniform for the whole workgroup
+    const int Mh = a.heads ? a.ht.v[rem % a.g.H] : a.g.M;     // this head's budget
+    const int m = a.m < Mh ? a.m : Mh;        // heavy slots this head has in use
     const int n_old = a.c - a.R;              // buffered tokens that become candidates (> 0, checked on the host)
-    const int n_cand = a.m + n_old;
+    const int n_cand = m + n_old;
     unsigned long long *keys = reinterpret_cast<unsigned long long *>(lds);
     for (int i = threadIdx.x; i < n_cand; i += THREADS) {
-        const int slot = i < a.m ? i : a.g.M + (a.base + (i - a.m)) % a.g.C;
+        const int slot = i < m ? i : a.g.M + (a.base + (i - m)) % a.g.C;
         keys[i] = make_key(u.score[slot], u.pos[slot]);
     }
     __syncthreads();
-    select_and_move<THREADS, false>(a.g, u, lds, n_cand, a.m, n_old, a.base, a.lpr, threadIdx.x);
+    select_and_move<THREADS, false>(a.g, u, lds, n_cand, m, n_old, a.base, a.lpr, threadIdx.x, Mh);
 }
 
 // ---- dense-source mode -------------------------------------------------------
@@ -49,6 +53,8 @@ struct DenseSrcArgs {
     int n_src;
     int R;
     int lpr;
+    int heads;              // budgets per head
+    HeadTable ht;
 };
 
 template <int THREADS>
@@ -67,7 +73,7 @@ __global__ __launch_bounds__(THREADS) void compress_dense_kernel(DenseSrcArgs a)
 
     if (!u.sem) {
         // positions {0..S-1} and the last W: destination slot as in ssd_append_token
-        const int S = a.g.S, W = a.g.W, RW = a.g.RW;
+        const int S = a.g.S, W = a.heads ? a.ht.v[rem % a.g.H] : a.g.W, RW = W + (a.g.RW - a.g.W);
         const int n_sink = a.n_src < S ? a.n_src : S;
         const int w_begin = a.n_src - W > S ? a.n_src - W : S;
         const int n_win = a.n_src > w_begin ? a.n_src - w_begin : 0;
@@ -84,7 +90,7 @@ __global__ __launch_bounds__(THREADS) void compress_dense_kernel(DenseSrcArgs a)
         return;
     }
 
-    const int M = a.g.M;
+    const int M = a.heads ? a.ht.v[rem % a.g.H] : a.g.M;  // this head's budget; the row buffer starts at slot g.M
     const int n_rec = a.n_src < a.R ? a.n_src : a.R;      // newest tokens that go to the row buffer
     const int n_cand = a.n_src - n_rec;
     const float *sc = a.score_src ? a.score_src + src_unit * (size_t)a.n_src : nullptr;
@@ -127,13 +133,13 @@ __global__ __launch_bounds__(THREADS) void compress_dense_kernel(DenseSrcArgs a)
         const int f = t % frag_per_tok;
         const int kv = f / a.lpr, sub = f % a.lpr;
         const int p = k < nkeep ? kept[k] : n_cand + (k - nkeep);
-        const int slot = k < nkeep ? k : M + (k - nkeep);
+        const int slot = k < nkeep ? k : a.g.M + (k - nkeep);
         const uint4 v = *reinterpret_cast<const uint4 *>((kv ? Vs : Ks) + (size_t)p * a.g.row_bytes + (size_t)sub * 16u);
         *reinterpret_cast<uint4 *>((kv ? u.V : u.K) + (size_t)slot * a.g.row_bytes + (size_t)sub * 16u) = v;
     }
     for (int k = tid; k < n_rows; k += THREADS) {
         const int p = k < nkeep ? kept[k] : n_cand + (k - nkeep);
-        const int slot = k < nkeep ? k : M + (k - nkeep);
+        const int slot = k < nkeep ? k : a.g.M + (k - nkeep);
         u.pos[slot] = p;
         u.score[slot] = sc ? sc[p] : 0.f;
     }
@@ -151,6 +157,8 @@ int launch_compress_inplace(const ssd_cache *cache, int lb, int le, const LayerS
     a.base = st.base;
     a.R = cf.recent;
     a.lpr = cf.head_dim * cache->esize / 16;
+    a.heads = per_head(cache) ? 1 : 0;
+    fill_head_table(cache, lb, &a.ht);
     const int n_cand = st.m + n_old;
     const unsigned units = (unsigned)((le - lb) * cf.n_seqs * cf.n_heads);
     const size_t lds = select_lds_bytes(cache->Ml[lb], n_cand, n_old);
@@ -197,6 +205,8 @@ extern "C" int ssd_compress_kv(ssd_cache *cache, int layer_begin, int layer_end,
                 a.n_src = n_src;
                 a.R = cf.recent;
                 a.lpr = lpr;
+                a.heads = per_head(cache) ? 1 : 0;
+                fill_head_table(cache, lb, &a.ht);
                 const size_t lds = sizeof(unsigned long long) * (size_t)n_cand + sizeof(int) * (size_t)cache->Ml[lb] + (size_t)n_cand + 16;
                 hipLaunchKernelGGL((compress_dense_kernel<256>), dim3((unsigned)((le - lb) * BH)), dim3(256), lds, s, a);
                 hipError_t e = hipGetLastError();

@@ -60,6 +60,56 @@ struct Segs {
     int32_t total;
 };
 
+// Budgets per head (caches made by ssd_cache_init_heads): entry h is head h's own window W_h if it is a
+// spatial head, its own heavy-hitter budget M_h if it is a semantic head.  Units keep the layer-wide size
+// (the largest W_h / M_h of the layer, which is what Geom holds); a head uses only its own share of the slots.
+// One layer per launch, so one table per launch, passed with the kernel arguments.
+static constexpr int HMAX = 128;  // heads per layer
+struct HeadTable {
+    uint16_t v[HMAX];
+};
+
+// ---- slot arithmetic of a spatial unit, the same on the host and in kernels ----
+// S sink slots, then a ring of RW slots (RW = W, or W + C when spatial heads use the row buffer).
+__host__ __device__ inline int ring_slot(int S, int RW, int p) { return p < S ? p : S + (p - S) % RW; }
+
+// Valid slots of a spatial unit that holds n tokens, the last compression having happened at nc tokens.
+__host__ __device__ inline Segs ring_segs(int S, int W, int C, bool row_buffer, int n, int nc) {
+    Segs s = {{0, 0, 0}, {0, 0, 0}, 0};
+    if (!row_buffer) {
+        // Algorithm 1: the ring fills front to back, so the valid slots are always a prefix
+        const int cap = S + W;
+        s.len[0] = n < cap ? n : cap;
+        s.total = s.len[0];
+        return s;
+    }
+    // Algorithm 2: sinks, then positions [max(S, nc - W), n) in a ring of W + C slots
+    const int RW = W + C;
+    s.len[0] = n < S ? n : S;
+    const int lo = nc - W > S ? nc - W : S;
+    const int count = n > lo ? n - lo : 0;
+    const int start = S + (lo - S) % RW;
+    const int first = count < S + RW - start ? count : S + RW - start;
+    s.start[1] = start; s.len[1] = first;
+    s.start[2] = S;     s.len[2] = count - first;
+    s.total = s.len[0] + s.len[1] + s.len[2];
+    return s;
+}
+
+// Rows a fused append + attention streams from a spatial unit that held n tokens before the append: everything
+// retained after it except the new token itself (which the kernel holds in registers), whose slot is new_slot.
+__host__ __device__ inline Segs ring_segs_fused(int S, int W, int C, bool row_buffer, int n, int nc, int new_slot) {
+    if (row_buffer) return ring_segs(S, W, C, true, n, nc);     // the new token's slot is never a retained one
+    // Algorithm 1: the new token overwrites the oldest ring slot; stream the prefix around it
+    Segs s = ring_segs(S, W, C, false, n + 1, nc);
+    const int end = s.len[0];
+    if (new_slot < 0 || new_slot >= end) return s;
+    s.start[0] = 0;            s.len[0] = new_slot;
+    s.start[1] = new_slot + 1; s.len[1] = end - new_slot - 1;
+    s.total = end - 1;
+    return s;
+}
+
 }  // namespace ssd
 
 struct ssd_cache {
@@ -68,7 +118,9 @@ struct ssd_cache {
     int esize;
     std::vector<uint8_t> head_type;           // [L*H]
     std::vector<ssd::LayerDesc> ldesc;        // [L]
-    std::vector<int32_t> Wl, Ml;              // [L] window and budget of each layer (cfg.window / cfg.budget unless given per layer)
+    std::vector<int32_t> Wl, Ml;              // [L] window and budget of each layer (cfg.window / cfg.budget unless given per layer);
+                                              //     with budgets per head: the largest of the layer, which sizes its units
+    std::vector<uint16_t> head_budget;        // [L*H] W_h of a spatial head, M_h of a semantic head; empty unless given per head
     std::vector<ssd::LayerState> st;          // [L]
     char *dev;
     size_t bytes;
@@ -97,7 +149,11 @@ int spatial_slot(const ssd_cache *c, int l, int p);
 void apply_compress_counters(ssd_cache *c, int l);
 // does layer l keep a row buffer (semantic heads, or spatial heads under Algorithm 2)
 bool has_buffer(const ssd_cache *c, int l);
+// budgets per head?  (then every launch covers one layer and carries that layer's HeadTable)
+static inline bool per_head(const ssd_cache *c) { return !c->head_budget.empty(); }
+void fill_head_table(const ssd_cache *c, int l, HeadTable *out);
 // end of the run of layers starting at lb that share layer lb's state, window and budget, at most LMAX long
+// (one layer when budgets are per head)
 int same_state_run(const ssd_cache *c, int lb, int le);
 // the same without the state: layers that share layer lb's window and budget
 int same_geom_run(const ssd_cache *c, int lb, int le);

@@ -67,12 +67,14 @@ static __host__ __device__ inline size_t select_lds_bytes(int M, int n_cand, int
 // aligned) and a barrier of the cooperating threads has made them visible.  On exit the kept candidates occupy
 // heavy slots [0, min(M, n_cand)) with their rows, positions and scores.
 //
+// M is the head's budget (at most g.M, the layer-wide size of the heavy region that the row buffer follows).
+//
 // THREADS threads with ids tid = 0..THREADS-1 cooperate: a whole workgroup (WAVE = false, synchronised
 // with __syncthreads) or a single wave (WAVE = true, THREADS = 64, tid = lane).
 template <int THREADS, bool WAVE>
 static __device__ __forceinline__ void select_and_move(const Geom &g, const UnitRef &u, unsigned char *lds, int n_cand,
-                                                      int m, int n_old, int base, int lpr, int tid) {
-    const int M = g.M, C = g.C;
+                                                      int m, int n_old, int base, int lpr, int tid, int M) {
+    const int C = g.C;
     unsigned long long *keys = reinterpret_cast<unsigned long long *>(lds);   // [n_cand]
     int *dest = reinterpret_cast<int *>(keys + n_cand);                        // [M]     free heavy slots, ascending
     int *src = dest + M;                                                       // [n_old] promoted candidates (indices)
@@ -133,7 +135,7 @@ static __device__ __forceinline__ void select_and_move(const Geom &g, const Unit
         const int f = t % frag_per_tok;
         const int kv = f / lpr, sub = f % lpr;
         char *plane = kv ? u.V : u.K;
-        const int from = M + (base + (src[k] - m)) % C;
+        const int from = g.M + (base + (src[k] - m)) % C;
         const uint4 v = *reinterpret_cast<const uint4 *>(plane + (size_t)from * g.row_bytes + (size_t)sub * 16u);
         *reinterpret_cast<uint4 *>(plane + (size_t)dest[k] * g.row_bytes + (size_t)sub * 16u) = v;
     }

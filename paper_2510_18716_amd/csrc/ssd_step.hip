@@ -48,6 +48,8 @@ struct StepHot {
     int probe;           // SSD_PROBE builds only
     int sem_first;       // semantic units have more rows than spatial ones: dispatch them first
     int late_new_store;  // fused append: store the new token's rows after the stream instead of at its start
+    int n_att, nc;       // budgets per head: tokens the attention sees, tokens held at the last compression,
+    int row_buffer;      //   and whether spatial heads use the row buffer (a spatial unit derives its own rows)
     Segs sp, se;         // rows streamed from the cache (fused append: without the new token's slot)
     Geom g;
 };
@@ -55,6 +57,7 @@ struct StepHot {
 struct StepArgs {
     StepHot h;
     LaunchMeta lm;
+    HeadTable ht;        // budgets per head (one-layer launches only)
 };
 
 // A wave reads its arguments with scalar loads from the kernel-argument segment.  Left to itself the
@@ -72,7 +75,7 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDesc &ld) {
     static_assert(sizeof(StepHot) <= 256, "the fixed part is read as four 64-byte pieces");
     static_assert(sizeof(LayerDesc) == 56, "one table entry is read as three 16-byte pieces and one of 8 bytes");
-    static_assert(sizeof(StepArgs) >= 256 && sizeof(StepArgs) == sizeof(StepHot) + sizeof(LaunchMeta), "layout of the argument block");
+    static_assert(sizeof(StepArgs) >= 256 && sizeof(StepArgs) == sizeof(StepHot) + sizeof(LaunchMeta) + sizeof(HeadTable), "layout of the argument block");
     const SSD_KERNARG char *kp = (const SSD_KERNARG char *)__builtin_amdgcn_kernarg_segment_ptr();
     struct { u32x16_t w[4]; } fixed;
     struct { u32x4_t w[3]; u32x2_t t; } entry;
@@ -95,7 +98,7 @@ static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDes
     a.qscale = __uint_as_float(SSD_W(offsetof(StepHot, qscale)));
     SSD_I(layer_off); SSD_I(new_slot_sp); SSD_I(new_slot_se); SSD_I(new_pos); SSD_I(accumulate); SSD_I(do_compress);
     SSD_I(m); SSD_I(c); SSD_I(base); SSD_I(R); SSD_I(lpr); SSD_I(zcap); SSD_I(wave_lds); SSD_I(probe); SSD_I(sem_first);
-    SSD_I(late_new_store);
+    SSD_I(late_new_store); SSD_I(n_att); SSD_I(nc); SSD_I(row_buffer);
     SSD_I(sp.start[0]); SSD_I(sp.start[1]); SSD_I(sp.start[2]); SSD_I(sp.len[0]); SSD_I(sp.len[1]); SSD_I(sp.len[2]); SSD_I(sp.total);
     SSD_I(se.start[0]); SSD_I(se.start[1]); SSD_I(se.start[2]); SSD_I(se.len[0]); SSD_I(se.len[1]); SSD_I(se.len[2]); SSD_I(se.total);
     SSD_P(g.base, char *); SSD_I(g.B); SSD_I(g.H); SSD_I(g.S); SSD_I(g.W); SSD_I(g.M); SSD_I(g.C); SSD_I(g.RW); SSD_I(g.row_bytes);
@@ -112,6 +115,13 @@ static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDes
 #undef SSD_P
 #undef SSD_Q
 }
+
+// Head h's entry of the launch's HeadTable (a scalar load from the kernel-argument segment).
+static __device__ __forceinline__ int fetch_head_budget(int h) {
+    const SSD_KERNARG char *kp = (const SSD_KERNARG char *)__builtin_amdgcn_kernarg_segment_ptr();
+    const uint32_t w = *reinterpret_cast<const SSD_KERNARG uint32_t *>(kp + sizeof(StepHot) + sizeof(LaunchMeta) + (size_t)(h >> 1) * 4);
+    return (int)((w >> ((h & 1) * 16)) & 0xffffu);
+}
 #undef SSD_KERNARG
 
 // One wave per unit, WPB units (consecutive heads of one sequence and layer) per workgroup;
@@ -126,7 +136,9 @@ static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDes
 // store classes: 1 = new token's rows, 2 = output, 4 = running scores and positions, 8 = promoted row;
 // 16 = all stores written through (system scope) instead of left dirty in L2
 
-template <typename T, int D, int CH, int WPB, bool FUSED, bool PF = true>
+// HEADS: budgets per head.  The launch covers one layer; a unit takes its head's W_h or M_h from the table
+// in the arguments and derives its own rows and slots from it (the host's are those of the largest head).
+template <typename T, int D, int CH, int WPB, bool FUSED, bool PF = true, bool HEADS = false>
 __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read through fetch_args
     constexpr int VEC = Elem<T>::VEC;
     constexpr int LPR = D / VEC;
@@ -135,7 +147,8 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
     LayerDesc ld;
     fetch_args(blockIdx.z >> 1, a, ld);
 
-    const int t_m = a.m, t_c = a.c, t_base = a.base, t_R = a.R, t_lpr = a.lpr, t_new_pos = a.new_pos,
+    int t_m = a.m;
+    const int t_c = a.c, t_base = a.base, t_R = a.R, t_lpr = a.lpr, t_new_pos = a.new_pos,
               t_new_slot_se = a.new_slot_se, t_do_compress = a.do_compress, t_accumulate = a.accumulate,
               t_M = a.g.M, t_C = a.g.C, t_row_bytes = a.g.row_bytes;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: everything per-unit stays uniform
@@ -163,6 +176,21 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
     sg.len[1] = u.sem ? a.se.len[1] : a.sp.len[1];
     sg.len[2] = u.sem ? a.se.len[2] : a.sp.len[2];
     sg.total = u.sem ? a.se.total : a.sp.total;
+    int t_Mh = t_M;                                       // the head's own budget (t_M stays the start of the row buffer)
+    if constexpr (HEADS) {
+        const int hb = fetch_head_budget(h);
+        if (u.sem) {
+            t_Mh = hb;
+            t_m = t_m < hb ? t_m : hb;                    // heavy slots this head has in use
+            sg.total -= sg.len[0] - t_m;
+            sg.len[0] = t_m;
+        } else {
+            const int RW = hb + (a.g.RW - a.g.W);
+            a.new_slot_sp = ring_slot(a.g.S, RW, a.new_pos);
+            sg = FUSED ? ring_segs_fused(a.g.S, hb, a.g.C, a.row_buffer != 0, a.n_att - 1, a.nc, a.new_slot_sp)
+                       : ring_segs(a.g.S, hb, a.g.C, a.row_buffer != 0, a.n_att, a.nc);
+        }
+    }
     const size_t qoff = ((size_t)(a.layer_off + lrel) * (size_t)(a.g.B * a.g.H) + rem) * (size_t)a.g.row_bytes + (size_t)sub * 16u;
     unsigned char *region = lds_raw + (size_t)w * a.wave_lds;
     float *zbuf = reinterpret_cast<float *>(region);                    // [zcap]
@@ -265,7 +293,7 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
     const int M = t_M, C = t_C;
     const int n_old = t_c - t_R;                          // buffered tokens that become candidates
     const int n_cand = t_m + n_old;
-    const int n_evict = n_cand - M;                       // <= 0: everything is kept
+    const int n_evict = n_cand - t_Mh;                    // <= 0: everything is kept
     // At most one eviction among at most 128 candidates (always the case when compressing after every
     // token) is settled in registers; anything else ranks all candidates through LDS.
     const bool general = compress && (n_evict >= 2 || n_cand > 128);
@@ -305,7 +333,7 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
 #endif
     if (general) {
         lds_sync();
-        select_and_move<64, true>(a.g, u, sel, n_cand, t_m, n_old, t_base, t_lpr, lane);
+        select_and_move<64, true>(a.g, u, sel, n_cand, t_m, n_old, t_base, t_lpr, lane, t_Mh);
         return;
     }
     // The promoted buffered tokens and the slots they go to follow from the index of the single evicted
@@ -366,13 +394,21 @@ static Tuning g_tune = DEFAULT_TUNE;
 static constexpr int FUSED_SELECT_MAX = 1024;
 
 template <typename T, int D, int CH, int WPB, bool PF = true>
-static void launch_one(const StepArgs &full, dim3 blocks, size_t lds, bool fused, hipStream_t s) {
+static void launch_one(const StepArgs &full, dim3 blocks, size_t lds, bool fused, bool heads, hipStream_t s) {
+    if (heads) {
+        // budgets per head: one variant (four wave-loads per chunk) per workgroup size
+        if constexpr (PF && CH == 4) {
+            if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, true, true>), blocks, dim3(WPB * 64), lds, s, full);
+            else hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, false, true, true>), blocks, dim3(WPB * 64), lds, s, full);
+        }
+        return;
+    }
     if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, PF>), blocks, dim3(WPB * 64), lds, s, full);
     else hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, false, PF>), blocks, dim3(WPB * 64), lds, s, full);
 }
 
 template <typename T, int D>
-static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, int layers, bool fused, int M, hipStream_t s) {
+static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, int layers, bool fused, bool heads, int M, hipStream_t s) {
     StepHot &a = full.h;
     const int n_old = a.c - a.R, n_cand = a.m + n_old;
     // Launch shape by the number of units (measured on the 7B- and 1B-shaped workloads).  Up to half of
@@ -382,7 +418,7 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
     // rows are stored after the stream (see the kernel).
     const long long units = (long long)H * B * layers;
     a.late_new_store = g_probe / 1000000 == 1 ? 0 : g_probe / 1000000 == 2 ? 1 : (units > 2048 && units <= 16384 ? 1 : 0);
-    int ch = g_tune.ch ? g_tune.ch : 4;
+    int ch = g_tune.ch && !heads ? g_tune.ch : 4;
     int wpb = g_tune.wpb ? g_tune.wpb : (units <= 2048 ? 1 : 4);
     a.wave_lds = (int)(((size_t)a.zcap * 4 + (a.do_compress ? select_lds_bytes(M, n_cand, n_old) + 16 : 0) + 15) / 16 * 16);
     while (wpb > 1 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;
@@ -391,13 +427,13 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
     if ((size_t)(g_probe / 10000 % 100) * 1024 > lds) lds = (size_t)(g_probe / 10000 % 100) * 1024;   // occupancy experiments: pad the workgroup's LDS
 #endif
     const dim3 blocks((unsigned)((max_type_heads + wpb - 1) / wpb), (unsigned)B, (unsigned)(2 * layers));
-#define SSD_CASE(CH_, WPB_) if (ch == CH_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_>(full, blocks, lds, fused, s); return hipGetLastError(); }
+#define SSD_CASE(CH_, WPB_) if (ch == CH_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_>(full, blocks, lds, fused, heads, s); return hipGetLastError(); }
     if constexpr (sizeof(T) == 2 && D == 128) {       // the shape the sweeps are run on has every variant
         SSD_CASE(1, 1) SSD_CASE(2, 1) SSD_CASE(4, 1)
         SSD_CASE(1, 2) SSD_CASE(2, 2) SSD_CASE(4, 2)
         SSD_CASE(1, 4) SSD_CASE(2, 4) SSD_CASE(4, 4)
 #ifdef SSD_PROBE
-#define SSD_CASE_NPF(CODE_, CH_, WPB_) if (ch == CODE_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_, false>(full, blocks, lds, fused, s); return hipGetLastError(); }
+#define SSD_CASE_NPF(CODE_, CH_, WPB_) if (ch == CODE_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_, false>(full, blocks, lds, fused, false, s); return hipGetLastError(); }
         SSD_CASE_NPF(14, 4, 4) SSD_CASE_NPF(18, 8, 4) SSD_CASE_NPF(14, 4, 8) SSD_CASE_NPF(18, 8, 8) SSD_CASE_NPF(18, 8, 2) SSD_CASE(4, 8) SSD_CASE(2, 8)
 #undef SSD_CASE_NPF
 #endif
@@ -451,6 +487,8 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.do_compress = in_kernel ? 1 : 0;
             a.m = at.m; a.c = at.c; a.base = at.base; a.R = cf.recent;
             a.lpr = a.g.row_bytes / 16;
+            a.n_att = at.n; a.nc = before.nc; a.row_buffer = cf.spatial_row_buffer;
+            fill_head_table(cache, lb, &full.ht);
             a.probe = g_probe % 1000000;
             int mth = 1;
             for (int l = lb; l < le; ++l) {
@@ -460,11 +498,11 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.sem_first = a.se.total + (fused ? 1 : 0) >= a.sp.total + (fused ? 1 : 0) ? 1 : 0;
             hipError_t e;
             if (cf.dtype == SSD_BF16)
-                e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s)
-                                       : launch_step<bf16_t, 64>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s);
+                e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, per_head(cache), cache->Ml[lb], s)
+                                       : launch_step<bf16_t, 64>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, per_head(cache), cache->Ml[lb], s);
             else
-                e = cf.head_dim == 128 ? launch_step<float, 128>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s)
-                                       : launch_step<float, 64>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, cache->Ml[lb], s);
+                e = cf.head_dim == 128 ? launch_step<float, 128>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, per_head(cache), cache->Ml[lb], s)
+                                       : launch_step<float, 64>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, per_head(cache), cache->Ml[lb], s);
             if (e != hipSuccess) return hip_fail(e, what);
             if (do_compress && !in_kernel) {
                 const int rc = launch_compress_inplace(cache, lb, le, at, s);

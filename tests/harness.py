@@ -31,7 +31,18 @@ def say(*a):
 
 def make_cache(wl: workload.Workload, ht: np.ndarray, device="cuda") -> ssd.Cache:
     cfg = make_config(wl.L, wl.B, wl.H, wl.d, wl.dtype, wl.W, wl.S, wl.M, wl.R, wl.C, 0.0, int(wl.alg2))
+    if wl.head_budget is not None:
+        return ssd.Cache(cfg, ht, device=device, head_budget=np.asarray(wl.head_budget, np.int32))
     return ssd.Cache(cfg, ht, device=device, window=wl.W_layers, budget=wl.M_layers)
+
+
+def heavy_cap(wl: workload.Workload, ht: np.ndarray, layer: int) -> int:
+    """Slots of the heavy region of a layer's semantic units (where their row buffer starts): the layer's M,
+    or the largest M_h of its semantic heads when budgets are per head."""
+    if wl.head_budget is None:
+        return wl.M_of(layer)
+    sem = [int(wl.head_budget[layer][h]) for h in range(wl.H) if ht[layer, h] == workload.SEMANTIC]
+    return max(sem) if sem else wl.M
 
 
 def flat_index(wl: workload.Workload, units: Sequence[Tuple[int, int, int]]) -> torch.Tensor:
@@ -113,13 +124,16 @@ def gpu_decode(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.ndar
 
 
 def oracle_unit(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.ndarray, schedule: np.ndarray,
-                unit: Tuple[int, int, int], p_end: Optional[int] = None, layer: Optional[int] = None):
+                unit: Tuple[int, int, int], p_end: Optional[int] = None, layer: Optional[int] = None,
+                head: Optional[int] = None):
     """Oracle decode of one unit: (o [steps,d], heavy_log, gap_log, Unit).  `unit` indexes `data` and `ht`;
-    `layer` is the unit's layer in the workload where those are slices (it selects the layer's W and M)."""
+    `layer` and `head` are the unit's layer and head in the workload where those are slices (they select the
+    W and M that apply to it)."""
     l, b, h = unit
     lw = l if layer is None else layer
+    hw = h if head is None else head
     q, K, V = workload.unit_arrays(data, l, b, h)
-    u = oracle.Unit(ht[l, h] == workload.SEMANTIC, wl.W_of(lw), wl.S, wl.M_of(lw), wl.R, wl.C, buffered_spatial=wl.alg2)
+    u = oracle.Unit(ht[l, h] == workload.SEMANTIC, wl.W_of(lw, hw), wl.S, wl.M_of(lw, hw), wl.R, wl.C, buffered_spatial=wl.alg2)
     o, hl, gl = u.run(q, K, V, wl.scale, schedule, p_end=p_end, log=True)
     return o, hl, gl, u
 
@@ -134,11 +148,11 @@ def check_outputs(gpu: np.ndarray, ref: np.ndarray, dtype: str, what: str):
     return float(err.max())
 
 
-def spatial_positions(wl: workload.Workload, n: int, n_c: Optional[int] = None, layer: int = 0) -> List[int]:
+def spatial_positions(wl: workload.Workload, n: int, n_c: Optional[int] = None, layer: int = 0, head: Optional[int] = None) -> List[int]:
     """Closed form of a spatial head's retained set after n tokens; under Algorithm 2 the window is cut at
     n_c, the token count at the last compression."""
     ref = n if not wl.alg2 else n_c
-    return sorted(set(range(min(wl.S, n))) | set(range(max(wl.S, ref - wl.W_of(layer)), n)))
+    return sorted(set(range(min(wl.S, n))) | set(range(max(wl.S, ref - wl.W_of(layer, head)), n)))
 
 
 def compare_unit_sets(wl, ht, unit, layer_index, exports, heavy_log, gap_log, schedule):
@@ -146,7 +160,7 @@ def compare_unit_sets(wl, ht, unit, layer_index, exports, heavy_log, gap_log, sc
     step.  Returns the first step at which a permitted near-tie divergence was seen, or None."""
     l, b, h = unit
     sem = ht[l, h] == workload.SEMANTIC
-    M = wl.M_of(l)
+    M = heavy_cap(wl, ht, l)
     for p in sorted(exports):
         pos, score = exports[p]["post"]
         row = pos[layer_index, b, h]
@@ -154,7 +168,7 @@ def compare_unit_sets(wl, ht, unit, layer_index, exports, heavy_log, gap_log, sc
         n = p + 1
         if not sem:
             n_c = max([s + 1 for s in range(p + 1) if schedule[s]], default=0)
-            assert got == spatial_positions(wl, n, n_c, l), ("spatial set", unit, p)
+            assert got == spatial_positions(wl, n, n_c, l, h), ("spatial set", unit, p)
             continue
         heavy_gpu = sorted(int(x) for x in row[:M] if x >= 0)
         staged_gpu = sorted(int(x) for x in row[M:] if x >= 0)
@@ -194,9 +208,9 @@ def check_selection_on_own_scores(wl, ht, unit, layer_index, exports):
         cand_sc = row_s[valid]
         newest = np.sort(cand_pos)[len(cand_pos) - min(wl.R, len(cand_pos)):] if wl.R > 0 else np.zeros(0, np.int32)
         is_cand = ~np.isin(cand_pos, newest)
-        keep, _ = oracle.top_m(cand_sc[is_cand], cand_pos[is_cand], wl.M_of(l))
+        keep, _ = oracle.top_m(cand_sc[is_cand], cand_pos[is_cand], wl.M_of(l, h))
         want = sorted(int(x) for x in cand_pos[is_cand][keep])
-        got = sorted(int(x) for x in pos1[layer_index, b, h][: wl.M_of(l)] if x >= 0)
+        got = sorted(int(x) for x in pos1[layer_index, b, h][: heavy_cap(wl, ht, l)] if x >= 0)
         assert got == want, ("selection on the GPU's own scores", unit, p)
         # scores travel with their tokens, bit for bit
         after = {int(pp): float(ss) for pp, ss in zip(pos1[layer_index, b, h], sc1[layer_index, b, h]) if pp >= 0}

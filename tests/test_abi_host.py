@@ -298,6 +298,50 @@ def test_per_layer_window_and_budget_layout_counters_and_limits():
         ssd.Cache(cfg, ht, device=None, window=[1, 2])
 
 
+def test_per_head_budgets_layout_counters_and_limits():
+    L, B, H, d, S, R, C_ = 2, 2, 4, 64, 1, 1, 3
+    ht = _ht(L, H)                                   # two spatial, two semantic heads per layer
+    hb = np.array([[8, 3, 5, 12], [16, 2, 7, 1]], np.int32)
+    # (entry = W_h for the spatial heads 0 and 1, M_h for the semantic heads 2 and 3)
+    cfg = make_config(L, B, H, d, "f32", 99, S, 99, R, C_)
+    # units are sized for the largest head of their type in the layer: the layout equals the per-layer one with the maxima
+    Wl = [int(hb[l][ht[l] == 0].max()) for l in range(L)]
+    Ml = [int(hb[l][ht[l] == 1].max()) for l in range(L)]
+    assert ssd.ssd_cache_bytes(cfg, ht, head_budget=hb) == ssd.ssd_cache_bytes(cfg, ht, Wl, Ml)
+    c = ssd.Cache(cfg, ht, device=None, head_budget=hb)
+    assert [c.layer_budget(l) for l in range(L)] == list(zip(Wl, Ml))
+    assert [[c.head_budget(l, h) for h in range(H)] for l in range(L)] == hb.tolist()
+    assert c.export_slots == max(max(S + w for w in Wl), max(m + C_ for m in Ml))
+    # a cache with uniform budgets answers the same query from its layer values
+    cu = ssd.Cache(cfg, ht, device=None)
+    assert [cu.head_budget(0, h) for h in range(H)] == [99] * H
+    # counters: the layer's heavy count is that of its largest semantic head
+    units = [oracle.Unit(True, 1, S, Ml[l], R, C_) for l in range(L)]
+    for step in range(40):
+        ssd.ssd_decode_step(c, 0, L, FAKE, FAKE, FAKE, FAKE, True, step % 2 == 1)
+        for u in units:
+            assert u.append() == 0
+            if step % 2 == 1:
+                u.compress()
+        for l, u in enumerate(units):
+            hp, _, sp, _ = u.state()
+            assert c.layer_state(l)[:3] == (u.n, len(hp), len(sp))
+    assert [c.layer_state(l)[1] for l in range(L)] == Ml
+    # limits hold per entry, by head type; the arrays are not mixed with per-layer ones
+    for l, h, v in ((0, 0, 0), (0, 0, 70000), (1, 3, 0), (1, 3, 4094)):
+        bad = hb.copy()
+        bad[l, h] = v
+        assert ssd.ssd_cache_bytes(cfg, ht, head_budget=bad) == 0
+        with pytest.raises(ssd.SsdError):
+            ssd.Cache(cfg, ht, device=None, head_budget=bad)
+    with pytest.raises(ValueError):
+        ssd.Cache(cfg, ht, device=None, head_budget=hb[:1])
+    with pytest.raises(ValueError):
+        ssd.Cache(cfg, ht, device=None, window=Wl, head_budget=hb)
+    with pytest.raises(ssd.SsdError):
+        c.head_budget(0, H)
+
+
 def test_cfg_mix_rejects_bad_arguments_before_any_launch():
     ok = dict(p=FAKE, n_seqs=4, V=64, dtype=ssd.SSD_BF16, gamma=5.0, out=FAKE)
 

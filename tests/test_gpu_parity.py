@@ -45,7 +45,7 @@ def _full_compare(wl, ht=None, lpc=None, k_units=10 ** 9, export_every=1, seed=0
     for ui, unit in enumerate(units):
         l, b, h = unit
         host = {x: dev_data[x][:, l:l + 1, b:b + 1, h:h + 1].cpu() for x in "qkv"}
-        o_ref, hl, gl, u = oracle_unit(wl, host, ht[l:l + 1, h:h + 1], schedule, (0, 0, 0), layer=l)
+        o_ref, hl, gl, u = oracle_unit(wl, host, ht[l:l + 1, h:h + 1], schedule, (0, 0, 0), layer=l, head=h)
         li = layers.index(l)
         diverged = compare_unit_sets(wl, ht, unit, li, exports, hl, gl, schedule)
         t3 += check_selection_on_own_scores(wl, ht, unit, li, exports)
@@ -134,6 +134,25 @@ def test_window_and_budget_per_layer(fused):
     _full_compare(wl.replace(name="per-layer-calls"), lpc=1, fused=fused)
     wl2 = workload.config(2).replace(name="cfg2-pyramid", L=4, prompts=4, W_layers=(64, 48, 32, 16), M_layers=(96, 64, 32, 16))
     _full_compare(wl2, k_units=32, export_every=50, device_gen=True, fused=fused)
+
+
+@FUSED
+def test_window_and_budget_per_head(fused):
+    # head-wise allocation: every head its own W_h or M_h inside units sized for the layer's largest; includes
+    # W_h = 1, M_h = 1, a budget larger than the sequence, two equal neighbours, and Algorithm 2's row buffer
+    hb = ((24, 5, 1, 7, 200, 3), (9, 9, 30, 2, 1, 17), (13, 40, 6, 6, 11, 1))
+    wl = workload.Workload("per-head", L=3, prompts=1, H=6, d=128, dtype="bf16", n0=7, grid_h=6, grid_w=10, W=99, M=99,
+                           S=1, R=1, C=4, cadence=3, seed=29, plain=True, head_budget=hb)
+    _full_compare(wl, fused=fused)
+    _full_compare(wl.replace(name="per-head-calls"), lpc=1, fused=fused)
+    _full_compare(wl.replace(name="per-head-alg2", alg2=True, R=0, C=5, cadence=5), fused=fused)
+    _full_compare(wl.replace(name="per-head-f32-d64", dtype="f32", d=64, S=2, R=2, C=9, cadence=6), fused=fused)
+    # long row buffer: many evictions per compression, the general selection path with each head's own M_h
+    _full_compare(wl.replace(name="per-head-long-buffer", R=3, C=40, cadence=33), fused=fused)
+    r = np.random.default_rng(5)
+    wl2 = workload.config(2).replace(name="cfg2-per-head", L=3, prompts=4,
+                                     head_budget=tuple(tuple(int(x) for x in r.integers(8, 97, 16)) for _ in range(3)))
+    _full_compare(wl2, k_units=48, export_every=50, device_gen=True, fused=fused)
 
 
 @FUSED
@@ -316,7 +335,7 @@ def test_config5_large_batch_online_classification_then_decode(frac, W, M):
 @pytest.mark.parametrize("seed", range(64))
 def test_random_small_configurations(seed):
     """Seeded random shapes and policies (both dtypes and head dims, Algorithm 1 and 2, any cadence the row
-    buffer allows, budgets per layer now and then), every unit compared at every step, fused and unfused."""
+    buffer allows, budgets per layer or per head now and then), every unit compared at every step, fused and unfused."""
     r = np.random.default_rng(1000 + seed)
     d = int(r.choice([64, 128]))
     dtype = str(r.choice(["bf16", "f32"]))
@@ -334,5 +353,7 @@ def test_random_small_configurations(seed):
                            spatial_frac=float(r.choice([0.0, 0.25, 0.5, 0.75, 1.0])), seed=int(r.integers(1 << 30)),
                            plain=bool(r.integers(0, 2)), alg2=alg2, **kw)
     lpc = None if r.random() < 0.5 else 1
+    if r.random() < 0.35:         # budgets per head instead (drawn last: the other cases keep their draws)
+        wl = wl.replace(W_layers=None, M_layers=None, head_budget=tuple(tuple(int(x) for x in r.integers(1, 40, H)) for _ in range(L)))
     _full_compare(wl, lpc=lpc, fused=False)
     _full_compare(wl, lpc=lpc, fused=True)

@@ -54,6 +54,7 @@ class Workload:
     w_metric: int = 32        # recency window of the sparsity metric
     W_layers: Optional[Sequence[int]] = None    # window per layer (None = W everywhere)
     M_layers: Optional[Sequence[int]] = None    # budget per layer (None = M everywhere)
+    head_budget: Optional[Sequence[Sequence[int]]] = None   # [L][H]: W_h of a spatial head, M_h of a semantic head
 
     @property
     def B(self) -> int:
@@ -75,10 +76,14 @@ class Workload:
     def scale(self) -> float:
         return 1.0 / math.sqrt(self.d)
 
-    def W_of(self, layer: int) -> int:
+    def W_of(self, layer: int, head: Optional[int] = None) -> int:
+        if self.head_budget is not None and head is not None:
+            return int(self.head_budget[layer][head])
         return self.W if self.W_layers is None else int(self.W_layers[layer])
 
-    def M_of(self, layer: int) -> int:
+    def M_of(self, layer: int, head: Optional[int] = None) -> int:
+        if self.head_budget is not None and head is not None:
+            return int(self.head_budget[layer][head])
         return self.M if self.M_layers is None else int(self.M_layers[layer])
 
     def replace(self, **kw) -> "Workload":

@@ -24,6 +24,8 @@
 //   p / 1000000     1 / 2: force the new token's rows to be stored at the start / after the end of the
 //                   stream (this field also works in ordinary builds)
 // The results of these variants are wrong on purpose; only their timings are used.
+#include <algorithm>
+
 #include "ssd_select.h"
 
 namespace ssd {
@@ -54,10 +56,22 @@ struct StepHot {
     Geom g;
 };
 
+// Budgets per head (one-layer launches only): the layer's heads ranked by the rows they stream, longest
+// first, and each one's budget, by rank.  Workgroups are dispatched in rank order, so the units that take
+// longest start first and the short ones fill in behind them.
+struct HeadOrder {
+    uint8_t head[HMAX];      // head index of rank i
+    uint16_t budget[HMAX];   // its W_h (spatial head) or M_h (semantic head)
+};
+
+// Workgroups per block of ranks.  Measured on the 7B shape with budgets of 32..96 rows: dispatching strictly by
+// rank (1) and by sequence first (all 8 workgroups of a sequence together) differ by 7 %; 1, 2 and 4 are within 1 %.
+static constexpr int RANK_GROUPS = 2;
+
 struct StepArgs {
     StepHot h;
     LaunchMeta lm;
-    HeadTable ht;        // budgets per head (one-layer launches only)
+    HeadOrder ho;
 };
 
 // A wave reads its arguments with scalar loads from the kernel-argument segment.  Left to itself the
@@ -75,7 +89,7 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDesc &ld) {
     static_assert(sizeof(StepHot) <= 256, "the fixed part is read as four 64-byte pieces");
     static_assert(sizeof(LayerDesc) == 56, "one table entry is read as three 16-byte pieces and one of 8 bytes");
-    static_assert(sizeof(StepArgs) >= 256 && sizeof(StepArgs) == sizeof(StepHot) + sizeof(LaunchMeta) + sizeof(HeadTable), "layout of the argument block");
+    static_assert(sizeof(StepArgs) >= 256 && sizeof(StepArgs) == sizeof(StepHot) + sizeof(LaunchMeta) + sizeof(HeadOrder), "layout of the argument block");
     const SSD_KERNARG char *kp = (const SSD_KERNARG char *)__builtin_amdgcn_kernarg_segment_ptr();
     struct { u32x16_t w[4]; } fixed;
     struct { u32x4_t w[3]; u32x2_t t; } entry;
@@ -116,11 +130,13 @@ static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDes
 #undef SSD_Q
 }
 
-// Head h's entry of the launch's HeadTable (a scalar load from the kernel-argument segment).
-static __device__ __forceinline__ int fetch_head_budget(int h) {
-    const SSD_KERNARG char *kp = (const SSD_KERNARG char *)__builtin_amdgcn_kernarg_segment_ptr();
-    const uint32_t w = *reinterpret_cast<const SSD_KERNARG uint32_t *>(kp + sizeof(StepHot) + sizeof(LaunchMeta) + (size_t)(h >> 1) * 4);
-    return (int)((w >> ((h & 1) * 16)) & 0xffffu);
+// Entry `rank` of the launch's HeadOrder (two independent scalar loads from the kernel-argument segment).
+static __device__ __forceinline__ void fetch_head_order(int rank, int &head, int &budget) {
+    const SSD_KERNARG char *kp = (const SSD_KERNARG char *)__builtin_amdgcn_kernarg_segment_ptr() + sizeof(StepHot) + sizeof(LaunchMeta);
+    const uint32_t wh = *reinterpret_cast<const SSD_KERNARG uint32_t *>(kp + offsetof(HeadOrder, head) + (size_t)(rank >> 2) * 4);
+    const uint32_t wb = *reinterpret_cast<const SSD_KERNARG uint32_t *>(kp + offsetof(HeadOrder, budget) + (size_t)(rank >> 1) * 4);
+    head = (int)((wh >> ((rank & 3) * 8)) & 0xffu);
+    budget = (int)((wb >> ((rank & 1) * 16)) & 0xffffu);
 }
 #undef SSD_KERNARG
 
@@ -145,7 +161,7 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
     extern __shared__ __align__(16) unsigned char lds_raw[];
     StepHot a;
     LayerDesc ld;
-    fetch_args(blockIdx.z >> 1, a, ld);
+    fetch_args(HEADS ? 0 : blockIdx.z >> 1, a, ld);
 
     int t_m = a.m;
     const int t_c = a.c, t_base = a.base, t_R = a.R, t_lpr = a.lpr, t_new_pos = a.new_pos,
@@ -157,15 +173,33 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
     // grid = (ceil(max heads of a type / WPB), B, 2 * layers): z selects the layer and the head type, the type
     // with more rows first, so that within a layer the long units are dispatched before the short ones and
     // all waves of a workgroup have units of one length
-    const int lrel = blockIdx.z >> 1;
-    const bool sem_unit = ((blockIdx.z & 1) == 0) == (a.sem_first != 0);
-    const int local = blockIdx.x * WPB + w;               // index among the heads of this type in this layer
-    if (local >= (sem_unit ? ld.n_se : ld.n_sp)) return;
-    const uint64_t m0 = sem_unit ? ld.sem_mask[0] : ~ld.sem_mask[0];
-    const uint64_t m1 = sem_unit ? ld.sem_mask[1] : ~ld.sem_mask[1];
-    const int h = kth_set_bit(m0, m1, local);             // spatial heads: bits above H are never reached (local < n_sp)
-    const int rem = blockIdx.y * a.g.H + h;
-    const UnitRef u = unit_ref_local(a.g, ld, blockIdx.y, sem_unit, local);
+    const int lrel = HEADS ? 0 : blockIdx.z >> 1;
+    bool sem_unit;
+    int local, h, seq, hb = 0;
+    if constexpr (HEADS) {
+        // grid = (RANK_GROUPS, B, ceil(H / (WPB * RANK_GROUPS))): z walks the heads in rank order (longest first,
+        // whatever their type), RANK_GROUPS workgroups' worth at a time; inside such a block of ranks the
+        // sequences are the slow index, as in the uniform launch
+        const int rank = (blockIdx.z * RANK_GROUPS + blockIdx.x) * WPB + w;
+        if (rank >= a.g.H) return;
+        fetch_head_order(rank, h, hb);
+        seq = blockIdx.y;
+        const uint64_t word = h < 64 ? ld.sem_mask[0] : ld.sem_mask[1];
+        const uint64_t below = (1ull << (h & 63)) - 1ull;
+        sem_unit = ((word >> (h & 63)) & 1ull) != 0;
+        const int sem_below = h < 64 ? __popcll(ld.sem_mask[0] & below) : __popcll(ld.sem_mask[0]) + __popcll(ld.sem_mask[1] & below);
+        local = sem_unit ? sem_below : h - sem_below;
+    } else {
+        sem_unit = ((blockIdx.z & 1) == 0) == (a.sem_first != 0);
+        local = blockIdx.x * WPB + w;                     // index among the heads of this type in this layer
+        if (local >= (sem_unit ? ld.n_se : ld.n_sp)) return;
+        const uint64_t m0 = sem_unit ? ld.sem_mask[0] : ~ld.sem_mask[0];
+        const uint64_t m1 = sem_unit ? ld.sem_mask[1] : ~ld.sem_mask[1];
+        h = kth_set_bit(m0, m1, local);                   // spatial heads: bits above H are never reached (local < n_sp)
+        seq = blockIdx.y;
+    }
+    const int rem = seq * a.g.H + h;
+    const UnitRef u = unit_ref_local(a.g, ld, seq, sem_unit, local);
     // field by field, constant indices: a choice between two structs, or an index the compiler has not
     // unrolled yet, would pin the argument copy in (scratch) memory
     Segs sg;
@@ -178,7 +212,6 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
     sg.total = u.sem ? a.se.total : a.sp.total;
     int t_Mh = t_M;                                       // the head's own budget (t_M stays the start of the row buffer)
     if constexpr (HEADS) {
-        const int hb = fetch_head_budget(h);
         if (u.sem) {
             t_Mh = hb;
             t_m = t_m < hb ? t_m : hb;                    // heavy slots this head has in use
@@ -393,6 +426,29 @@ static Tuning g_tune = DEFAULT_TUNE;
 // compression kernel (a whole workgroup per head) runs after the attention.
 static constexpr int FUSED_SELECT_MAX = 1024;
 
+// Rank the heads of layer l by the rows this launch streams from their units, longest first (ties: lower head index).
+static void fill_head_order(const ssd_cache *c, int l, const LayerState &before, const LayerState &at, bool fused, HeadOrder *out) {
+    const ssd_config &cf = c->cfg;
+    const int H = cf.n_heads;
+    int rows[HMAX], idx[HMAX];
+    for (int h = 0; h < H; ++h) {
+        const int v = c->head_budget[(size_t)l * H + h];
+        idx[h] = h;
+        if (c->head_type[(size_t)l * H + h] == SSD_SEMANTIC) {
+            rows[h] = (at.m < v ? at.m : v) + at.c;
+        } else {
+            const bool rb = cf.spatial_row_buffer != 0;
+            rows[h] = fused ? ring_segs_fused(cf.n_init_sink, v, cf.stage_cap, rb, before.n, before.nc, -1).total
+                            : ring_segs(cf.n_init_sink, v, cf.stage_cap, rb, at.n, at.nc).total;
+        }
+    }
+    std::stable_sort(idx, idx + H, [&](int x, int y) { return rows[x] > rows[y]; });
+    for (int i = 0; i < HMAX; ++i) {
+        out->head[i] = (uint8_t)(i < H ? idx[i] : 0);
+        out->budget[i] = i < H ? c->head_budget[(size_t)l * H + idx[i]] : 0;
+    }
+}
+
 template <typename T, int D, int CH, int WPB, bool PF = true>
 static void launch_one(const StepArgs &full, dim3 blocks, size_t lds, bool fused, bool heads, hipStream_t s) {
     if (heads) {
@@ -426,7 +482,8 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
 #ifdef SSD_PROBE
     if ((size_t)(g_probe / 10000 % 100) * 1024 > lds) lds = (size_t)(g_probe / 10000 % 100) * 1024;   // occupancy experiments: pad the workgroup's LDS
 #endif
-    const dim3 blocks((unsigned)((max_type_heads + wpb - 1) / wpb), (unsigned)B, (unsigned)(2 * layers));
+    const dim3 blocks = heads ? dim3((unsigned)RANK_GROUPS, (unsigned)B, (unsigned)(((H + wpb - 1) / wpb + RANK_GROUPS - 1) / RANK_GROUPS))   // rank order, see the kernel
+                              : dim3((unsigned)((max_type_heads + wpb - 1) / wpb), (unsigned)B, (unsigned)(2 * layers));
 #define SSD_CASE(CH_, WPB_) if (ch == CH_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_>(full, blocks, lds, fused, heads, s); return hipGetLastError(); }
     if constexpr (sizeof(T) == 2 && D == 128) {       // the shape the sweeps are run on has every variant
         SSD_CASE(1, 1) SSD_CASE(2, 1) SSD_CASE(4, 1)
@@ -488,7 +545,7 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.m = at.m; a.c = at.c; a.base = at.base; a.R = cf.recent;
             a.lpr = a.g.row_bytes / 16;
             a.n_att = at.n; a.nc = before.nc; a.row_buffer = cf.spatial_row_buffer;
-            fill_head_table(cache, lb, &full.ht);
+            if (per_head(cache)) fill_head_order(cache, lb, before, at, fused, &full.ho);
             a.probe = g_probe % 1000000;
             int mth = 1;
             for (int l = lb; l < le; ++l) {

@@ -152,6 +152,8 @@ def main():
                     help="large-batch sweep (configuration 5): spatial fraction x W x M at B = 512, one JSON line with a list")
     ap.add_argument("--head-budgets", type=str, default="",
                     help="LO,HI: head-wise allocation -- every head its own W_h / M_h, seeded uniform in [LO, HI]")
+    ap.add_argument("--rope", type=int, default=0,
+                    help="1 / 2: time ssd_decode_step_rope (q and k rotated inside the step; pairs (i, i + d/2) / (2i, 2i+1))")
     ap.add_argument("--alg2", action="store_true",
                     help="row-buffer variant (Algorithm 2): both head types read a 24-token row buffer, compression every 24 tokens")
     args = ap.parse_args()
@@ -213,6 +215,10 @@ def main():
     cfg = make_config(wl.L, wl.B, wl.H, wl.d, wl.dtype, wl.W, wl.S, wl.M, wl.R, wl.C, 0.0, int(wl.alg2))
     cache = ssd.Cache(cfg, ht, device=dev, head_budget=None if wl.head_budget is None else np.asarray(wl.head_budget, np.int32))
     out = torch.empty((wl.L, wl.B, wl.H, wl.d), dtype=wl.torch_dtype, device=dev)
+    if args.rope:
+        assert fused, "--rope times the fused step"
+        rope_tabs = [torch.from_numpy(t).to(dev) for t in workload.rope_tables(wl.n_total, wl.d)]
+        wl = wl.replace(name=wl.name + "-rope%d" % args.rope)
     p_timed = wl.n_total - passes[0]          # first timed position of the first (usually the only) decode
 
     def measure(lpc, with_events):
@@ -228,6 +234,8 @@ def main():
         h = cache.handle
         L_ = ssd.lib
         acc_i = int(accumulate)
+        if args.rope:
+            cos_p, sin_p = rope_tabs[0].data_ptr(), rope_tabs[1].data_ptr()
 
         def step(p, ev=None, acct=None):
             comp = int(bool(sched[p]))
@@ -240,7 +248,11 @@ def main():
                         n_, m_, c_, _ = cache.layer_state(lb)
                         acct.append(algorithmic_bytes_attend(wl, ht, range(lb, le), (n_ + 1, m_, c_ + 1)) +
                                     algorithmic_bytes_append(wl, ht, range(lb, le)))
-                    rc = L_.ssd_decode_step(h, lb, le, qb + o, kb + o, vb + o, ob + lb * stride_l, acc_i, comp, stream)
+                    if args.rope:
+                        rc = L_.ssd_decode_step_rope(h, lb, le, qb + o, kb + o, vb + o, ob + lb * stride_l, acc_i, comp,
+                                                     cos_p + p * wl.d * 2, sin_p + p * wl.d * 2, args.rope, stream)
+                    else:
+                        rc = L_.ssd_decode_step(h, lb, le, qb + o, kb + o, vb + o, ob + lb * stride_l, acc_i, comp, stream)
                     assert rc == 0, ssd.ssd_last_error()
                     continue
                 rc = L_.ssd_append_token(h, lb, le, kb + o, vb + o, stream)
@@ -346,7 +358,7 @@ def main():
                    "spatial_fraction": wl.spatial_frac, "layers_per_call": lpc,
                    "step": "append + attend(+score accumulate) + compress, every layer",
                    "launches_per_step": head["launches_per_step"],
-                   "entry_points": "ssd_decode_step" if fused else "ssd_append_token, ssd_decode_attn, ssd_compress_kv",
+                   "entry_points": ("ssd_decode_step_rope" if args.rope else "ssd_decode_step") if fused else "ssd_append_token, ssd_decode_attn, ssd_compress_kv",
                    "timed_at": "last %d tokens of the raster decode (n -> %d)" % (passes[0], wl.n_total) +
                                ("" if len(passes) == 1 else ", over %d decodes of the image" % len(passes))},
         "algorithmic_GB_per_step": head["algorithmic_GB_per_step"],

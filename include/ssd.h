@@ -292,6 +292,30 @@ int ssd_decode_step(ssd_cache *cache, int layer_begin, int layer_end, const void
                     int accumulate_scores, int compress, void *stream);
 
 /*
+ * The same step with rotary position embedding (Su et al., "RoFormer") applied
+ * to q and k_new on the way in, so that the rows the projections produce need
+ * no launch of their own before this one.  The paper does not describe the
+ * model's position encoding; this is the standard form used by the LLaMA
+ * family of language models that Janus-Pro builds on.
+ *   cos, sin    : dev float [d/2], 16-byte aligned: cos and sin of the new
+ *                 token's angles theta_i * position, i = 0..d/2-1 (one row of
+ *                 the caller's tables; the same for every layer, sequence and
+ *                 head of the call)
+ *   rope_layout : SSD_ROPE_HALF pairs element i with element i + d/2 ("rotate
+ *                 half"); SSD_ROPE_INTERLEAVED pairs element 2i with 2i+1.
+ * A pair (a, b) becomes (a*cos_i - b*sin_i, b*cos_i + a*sin_i), computed in
+ * fp32 and rounded once to the cache dtype; the rotated k is what the cache
+ * stores, v_new is untouched.  The result equals ssd_decode_step on rows
+ * rotated and rounded beforehand.  Errors as ssd_decode_step, plus
+ * SSD_ERR_INVALID_ARG for a bad layout or missing / misaligned cos, sin.
+ */
+enum { SSD_ROPE_HALF = 1, SSD_ROPE_INTERLEAVED = 2 };
+int ssd_decode_step_rope(ssd_cache *cache, int layer_begin, int layer_end, const void *q,
+                         const void *k_new, const void *v_new, void *out, int accumulate_scores,
+                         int compress, const float *cos, const float *sin, int rope_layout,
+                         void *stream);
+
+/*
  * Test / benchmark export of one layer's index table.
  *   pos   : dev int32 [B, H, slots]  absolute position held by each slot, -1 if unused
  *   score : dev float [B, H, slots]  accumulated score of the slot (0 for spatial heads)

@@ -59,6 +59,8 @@ _lib.ssd_oracle_prefill_scores.argtypes = [_f32p, _f32p, C.c_int, C.c_int, C.c_d
 _lib.ssd_oracle_prefill_scores.restype = None
 _lib.ssd_oracle_cfg_mix.argtypes = [_f32p, C.c_int, C.c_int, C.c_double, _f32p]
 _lib.ssd_oracle_cfg_mix.restype = None
+_lib.ssd_oracle_rope.argtypes = [_f32p, C.c_int, _f32p, _f32p, C.c_int, C.c_int, _f32p]
+_lib.ssd_oracle_rope.restype = None
 _lib.ssd_oracle_top_m.argtypes = [_f32p, _i32p, C.c_int, C.c_int, _i32p, C.POINTER(C.c_double)]
 _lib.ssd_oracle_top_m.restype = C.c_int
 _lib.ssd_oracle_unit_new.argtypes = [C.c_int] * 6
@@ -159,6 +161,24 @@ def cfg_mix(p, gamma):
     out = np.zeros((max(B // 2, 1), max(V, 1)), np.float32)
     _lib.ssd_oracle_cfg_mix(p, B // 2, V, float(gamma), out)
     return out[: B // 2, :V]
+
+
+ROPE_HALF, ROPE_INTERLEAVED = 1, 2
+
+
+def rope(x, cos, sin, layout, single=False):
+    """O7.  Rotary position embedding of rows x [..., d] at one position (cos, sin: [d/2]) -> float32 [..., d].
+    layout ROPE_HALF pairs element i with i + d/2, ROPE_INTERLEAVED pairs 2i with 2i+1.  `single`: float
+    arithmetic in the order the kernel states (for results that are rounded to bfloat16 next)."""
+    x = _f32(x)
+    d = x.shape[-1]
+    cos, sin = _f32(cos), _f32(sin)
+    assert d % 2 == 0 and cos.shape == (d // 2,) and sin.shape == (d // 2,) and layout in (ROPE_HALF, ROPE_INTERLEAVED)
+    rows = np.ascontiguousarray(x.reshape(-1, d))
+    out = np.zeros_like(rows)
+    for i in range(rows.shape[0]):
+        _lib.ssd_oracle_rope(rows[i], d, cos, sin, int(layout), int(bool(single)), out[i])
+    return out.reshape(x.shape)
 
 
 def top_m(score, pos, M):

@@ -24,6 +24,11 @@
  *       attention (prefill branch of Algorithm 2).
  *   O6  classifier-free guidance of the two distributions of a prompt,
  *       Eq. (1) of Sec. 3.1.
+ *   O7  rotary position embedding of a query / key row.  Not from the paper
+ *       (which is silent on the model's position encoding): the definition
+ *       of Su et al., "RoFormer", in the two element pairings in use.  It
+ *       serves the variant of the fused step that rotates q and k on the way
+ *       in.
  *   O4  the per-head cache policy of Algorithm 1 with the additions the text
  *       of Sec. 3.3 makes (initial sink token for spatial heads, reserved
  *       recent window R for semantic heads) and the deferred-compression
@@ -236,6 +241,40 @@ void ssd_oracle_cfg_mix(const float *p, int n_prompts, int V, double gamma, floa
     for (i = 0; i < n_prompts; ++i) {
         const float *c = p + (size_t)(2 * i) * V, *u = p + (size_t)(2 * i + 1) * V;
         for (v = 0; v < V; ++v) out[(size_t)i * V + v] = (float)((double)c[v] + gamma * ((double)c[v] - (double)u[v]));
+    }
+}
+
+/* ------------------------------------------------------------------ O7 -- */
+
+/*
+ * Rotary position embedding of one row x[d] at a position whose angles are
+ * given by cosv[i], sinv[i], i = 0..d/2-1: every pair (a, b) of elements is
+ * rotated in its plane,
+ *     a' = a cos_i - b sin_i,   b' = b cos_i + a sin_i.
+ * layout 1: pair i is (x[i], x[i + d/2]); layout 2: pair i is (x[2i], x[2i+1]).
+ *
+ * single == 0: the definition, in double.
+ * single != 0: the same two expressions in float, each as one product and
+ *   one fused multiply-add (t = b*sin; a' = fma(a, cos, -t)), the precision
+ *   and order the GPU kernel states for itself.  Used where the result is
+ *   rounded to bfloat16 next: that rounding is a quantisation, and both sides
+ *   must take it from the same float.  A test pins this form to the double one.
+ */
+void ssd_oracle_rope(const float *x, int d, const float *cosv, const float *sinv, int layout, int single, float *out)
+{
+    int i;
+    for (i = 0; i < d / 2; ++i) {
+        const int ia = layout == 1 ? i : 2 * i;
+        const int ib = layout == 1 ? i + d / 2 : 2 * i + 1;
+        if (single) {
+            const float ta = x[ib] * sinv[i], tb = x[ia] * sinv[i];
+            out[ia] = fmaf(x[ia], cosv[i], -ta);
+            out[ib] = fmaf(x[ib], cosv[i], tb);
+        } else {
+            const double a = x[ia], b = x[ib], c = cosv[i], s = sinv[i];
+            out[ia] = (float)(a * c - b * s);
+            out[ib] = (float)(b * c + a * s);
+        }
     }
 }
 

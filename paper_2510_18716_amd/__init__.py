@@ -9,5 +9,6 @@ from .binding import (  # noqa: F401
     SSD_ERR_HIP, SSD_ERR_INVALID_ARG, SSD_ERR_LAYER_RANGE, SSD_ERR_ORDER, SSD_ERR_STAGE_OVERFLOW, SSD_OK,
     Cache, SsdConfig, SsdError, lib, lib_path,
     ssd_append_token, ssd_cache_bytes, ssd_cfg_mix, ssd_classify_heads, ssd_compress_kv, ssd_decode_attn, ssd_decode_step,
+    SSD_ROPE_HALF, SSD_ROPE_INTERLEAVED, ssd_decode_step_rope,
     ssd_dense_decode_attn, ssd_dense_workspace_bytes, ssd_last_error, ssd_prefill_scores, ssd_version,
 )

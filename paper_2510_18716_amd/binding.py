@@ -73,6 +73,8 @@ lib.ssd_decode_attn.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, C.c_int, _vp]
 lib.ssd_decode_attn.restype = C.c_int
 lib.ssd_decode_step.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp, _vp, C.c_int, C.c_int, _vp]
 lib.ssd_decode_step.restype = C.c_int
+lib.ssd_decode_step_rope.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp, _vp, C.c_int, C.c_int, _vp, _vp, C.c_int, _vp]
+lib.ssd_decode_step_rope.restype = C.c_int
 lib.ssd_compress_kv.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp, C.c_int, _vp]
 lib.ssd_compress_kv.restype = C.c_int
 lib.ssd_prefill_scores.argtypes = [_vp, _vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, _vp, _vp]
@@ -292,6 +294,16 @@ def ssd_decode_step(cache: Cache, layer_begin: int, layer_end: int, q, k_new, v_
                     compress: bool = True, stream=None) -> None:
     _check(lib.ssd_decode_step(cache.handle, layer_begin, layer_end, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
                                int(bool(accumulate_scores)), int(bool(compress)), _stream(stream)), "ssd_decode_step")
+
+
+SSD_ROPE_HALF, SSD_ROPE_INTERLEAVED = 1, 2
+
+
+def ssd_decode_step_rope(cache: Cache, layer_begin: int, layer_end: int, q, k_new, v_new, out, cos, sin, rope_layout: int,
+                         accumulate_scores: bool = True, compress: bool = True, stream=None) -> None:
+    _check(lib.ssd_decode_step_rope(cache.handle, layer_begin, layer_end, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                    int(bool(accumulate_scores)), int(bool(compress)), _ptr(cos), _ptr(sin), int(rope_layout),
+                                    _stream(stream)), "ssd_decode_step_rope")
 
 
 def ssd_compress_kv(cache: Cache, layer_begin: int, layer_end: int, K_src=None, V_src=None, score_src=None,

@@ -52,6 +52,9 @@ struct StepHot {
     int late_new_store;  // fused append: store the new token's rows after the stream instead of at its start
     int n_att, nc;       // budgets per head: tokens the attention sees, tokens held at the last compression,
     int row_buffer;      //   and whether spatial heads use the row buffer (a spatial unit derives its own rows)
+    int rope_layout;     // rotary embedding of q and k_new on the way in: 0 none, SSD_ROPE_HALF, SSD_ROPE_INTERLEAVED
+    const float *rope_cos;   // [d/2] cosines and sines of the new token's position
+    const float *rope_sin;
     Segs sp, se;         // rows streamed from the cache (fused append: without the new token's slot)
     Geom g;
 };
@@ -112,7 +115,8 @@ static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDes
     a.qscale = __uint_as_float(SSD_W(offsetof(StepHot, qscale)));
     SSD_I(layer_off); SSD_I(new_slot_sp); SSD_I(new_slot_se); SSD_I(new_pos); SSD_I(accumulate); SSD_I(do_compress);
     SSD_I(m); SSD_I(c); SSD_I(base); SSD_I(R); SSD_I(lpr); SSD_I(zcap); SSD_I(wave_lds); SSD_I(probe); SSD_I(sem_first);
-    SSD_I(late_new_store); SSD_I(n_att); SSD_I(nc); SSD_I(row_buffer);
+    SSD_I(late_new_store); SSD_I(n_att); SSD_I(nc); SSD_I(row_buffer); SSD_I(rope_layout);
+    SSD_P(rope_cos, const float *); SSD_P(rope_sin, const float *);
     SSD_I(sp.start[0]); SSD_I(sp.start[1]); SSD_I(sp.start[2]); SSD_I(sp.len[0]); SSD_I(sp.len[1]); SSD_I(sp.len[2]); SSD_I(sp.total);
     SSD_I(se.start[0]); SSD_I(se.start[1]); SSD_I(se.start[2]); SSD_I(se.len[0]); SSD_I(se.len[1]); SSD_I(se.len[2]); SSD_I(se.total);
     SSD_P(g.base, char *); SSD_I(g.B); SSD_I(g.H); SSD_I(g.S); SSD_I(g.W); SSD_I(g.M); SSD_I(g.C); SSD_I(g.RW); SSD_I(g.row_bytes);
@@ -140,6 +144,55 @@ static __device__ __forceinline__ void fetch_head_order(int rank, int &head, int
 }
 #undef SSD_KERNARG
 
+// Rotary position embedding (Su et al., RoFormer) of this lane's 16-byte fragment of a d-element row: pairs of
+// elements are rotated by the position's angles, element a of pair i to a*cos_i - b*sin_i and element b to
+// b*cos_i + a*sin_i.  SSD_ROPE_HALF pairs element i with i + d/2 (the "rotate half" form of the LLaMA family;
+// the partner element sits in the lane LPR/2 away), SSD_ROPE_INTERLEAVED pairs 2i with 2i+1 (both in this
+// fragment).  fp32, as one product and one fused multiply-add per element, rounded to T once.
+template <typename T, int D>
+static __device__ __forceinline__ uint4 rope_fragment(const uint4 &raw, const float *cs, const float *sn, int layout, int sub) {
+    constexpr int VEC = Elem<T>::VEC;
+    constexpr int LPR = D / VEC;
+    float x[VEC], r[VEC];
+    Elem<T>::unpack(raw, x);
+    if (layout == SSD_ROPE_HALF) {
+        uint4 praw;
+        praw.x = __shfl_xor(raw.x, LPR / 2); praw.y = __shfl_xor(raw.y, LPR / 2);
+        praw.z = __shfl_xor(raw.z, LPR / 2); praw.w = __shfl_xor(raw.w, LPR / 2);
+        float y[VEC];
+        Elem<T>::unpack(praw, y);
+        const int i0 = (sub * VEC) % (D / 2);
+        const bool first = sub < LPR / 2;              // this fragment holds the a elements of its pairs
+#pragma unroll
+        for (int e4 = 0; e4 < VEC; e4 += 4) {
+            const float4 c = *reinterpret_cast<const float4 *>(cs + i0 + e4);
+            const float4 s = *reinterpret_cast<const float4 *>(sn + i0 + e4);
+            const float cc[4] = {c.x, c.y, c.z, c.w}, ss[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float t = y[e4 + e] * ss[e];
+                r[e4 + e] = fmaf(x[e4 + e], cc[e], first ? -t : t);
+            }
+        }
+    } else {
+        const int i0 = sub * (VEC / 2);
+#pragma unroll
+        for (int j2 = 0; j2 < VEC / 2; j2 += 2) {
+            const float2 c = *reinterpret_cast<const float2 *>(cs + i0 + j2);
+            const float2 s = *reinterpret_cast<const float2 *>(sn + i0 + j2);
+            const float cc[2] = {c.x, c.y}, ss[2] = {s.x, s.y};
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float xa = x[2 * (j2 + j)], xb = x[2 * (j2 + j) + 1];
+                const float ta = xb * ss[j], tb = xa * ss[j];
+                r[2 * (j2 + j)] = fmaf(xa, cc[j], -ta);
+                r[2 * (j2 + j) + 1] = fmaf(xb, cc[j], tb);
+            }
+        }
+    }
+    return Elem<T>::pack(r);
+}
+
 // One wave per unit, WPB units (consecutive heads of one sequence and layer) per workgroup;
 // grid = (ceil(H / WPB), B, layers of the launch).  Nothing below needs a workgroup barrier.
 #ifdef SSD_PROBE      // (probe / 100) & bit: the kernel with that class of stores left out (what the write path costs)
@@ -154,7 +207,9 @@ static __device__ __forceinline__ void fetch_head_order(int rank, int &head, int
 
 // HEADS: budgets per head.  The launch covers one layer; a unit takes its head's W_h or M_h from the table
 // in the arguments and derives its own rows and slots from it (the host's are those of the largest head).
-template <typename T, int D, int CH, int WPB, bool FUSED, bool PF = true, bool HEADS = false>
+// ROPE: q and the new token's k are rotated by the position's angles on the way in (the rotated k is what the
+// cache receives), so that no separate launch has to touch them between the projections and this kernel.
+template <typename T, int D, int CH, int WPB, bool FUSED, bool PF = true, bool HEADS = false, bool ROPE = false>
 __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read through fetch_args
     constexpr int VEC = Elem<T>::VEC;
     constexpr int LPR = D / VEC;
@@ -229,7 +284,8 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
     float *zbuf = reinterpret_cast<float *>(region);                    // [zcap]
     unsigned char *sel = region + (size_t)a.zcap * 4;                   // selection scratch
 
-    const typename Elem<T>::Q q = Elem<T>::load_q(*reinterpret_cast<const uint4 *>(a.q + qoff));
+    const uint4 raw_q = *reinterpret_cast<const uint4 *>(a.q + qoff);
+    typename Elem<T>::Q q = Elem<T>::load_q(raw_q);       // ROPE: replaced by the rotated query behind the first loads
     Softmax<VEC> sm;
     sm.init();
     const bool want_z = u.sem && t_accumulate;
@@ -262,6 +318,12 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
         }
     };
     auto after_first_issue = [&]() {
+        if constexpr (ROPE) {
+            // here, not before the stream: the rotation waits for q, k_new and the angles, and the first K/V
+            // rows are better requested before that wait than after it
+            q = Elem<T>::load_q(rope_fragment<T, D>(raw_q, a.rope_cos, a.rope_sin, a.rope_layout, sub));
+            new_k = rope_fragment<T, D>(new_k, a.rope_cos, a.rope_sin, a.rope_layout, sub);
+        }
         if (!a.late_new_store) store_new();
         if (tail) {
             const int last = sg.total > 0 ? sg.total - 1 : 0;    // no rows yet: slot of row 0, inside the unit
@@ -451,10 +513,13 @@ static void fill_head_order(const ssd_cache *c, int l, const LayerState &before,
 
 template <typename T, int D, int CH, int WPB, bool PF = true>
 static void launch_one(const StepArgs &full, dim3 blocks, size_t lds, bool fused, bool heads, hipStream_t s) {
-    if (heads) {
-        // budgets per head: one variant (four wave-loads per chunk) per workgroup size
+    const bool rope = full.h.rope_layout != 0;            // fused launches only (checked by the entry point)
+    if (heads || rope) {
+        // budgets per head, rotary embedding: one variant (four wave-loads per chunk) per workgroup size
         if constexpr (PF && CH == 4) {
-            if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, true, true>), blocks, dim3(WPB * 64), lds, s, full);
+            if (rope && heads) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, true, true, true>), blocks, dim3(WPB * 64), lds, s, full);
+            else if (rope) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, true, false, true>), blocks, dim3(WPB * 64), lds, s, full);
+            else if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, true, true>), blocks, dim3(WPB * 64), lds, s, full);
             else hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, false, true, true>), blocks, dim3(WPB * 64), lds, s, full);
         }
         return;
@@ -474,7 +539,7 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
     // rows are stored after the stream (see the kernel).
     const long long units = (long long)H * B * layers;
     a.late_new_store = g_probe / 1000000 == 1 ? 0 : g_probe / 1000000 == 2 ? 1 : (units > 2048 && units <= 16384 ? 1 : 0);
-    int ch = g_tune.ch && !heads ? g_tune.ch : 4;
+    int ch = g_tune.ch && !heads && !a.rope_layout ? g_tune.ch : 4;
     int wpb = g_tune.wpb ? g_tune.wpb : (units <= 2048 ? 1 : 4);
     a.wave_lds = (int)(((size_t)a.zcap * 4 + (a.do_compress ? select_lds_bytes(M, n_cand, n_old) + 16 : 0) + 15) / 16 * 16);
     while (wpb > 1 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;
@@ -503,8 +568,13 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
 }
 
 // Shared by ssd_decode_attn (k_new == NULL, compress == 0) and ssd_decode_step.
+struct Rope {
+    const float *cos, *sin;
+    int layout;
+};
+
 static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new, const void *v_new,
-                    void *out, int accumulate, int compress, void *stream, const char *what) {
+                    void *out, int accumulate, int compress, void *stream, const char *what, Rope rope = {nullptr, nullptr, 0}) {
     const ssd_config &cf = cache->cfg;
     const bool fused = k_new != nullptr;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -545,6 +615,7 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.m = at.m; a.c = at.c; a.base = at.base; a.R = cf.recent;
             a.lpr = a.g.row_bytes / 16;
             a.n_att = at.n; a.nc = before.nc; a.row_buffer = cf.spatial_row_buffer;
+            a.rope_layout = rope.layout; a.rope_cos = rope.cos; a.rope_sin = rope.sin;
             if (per_head(cache)) fill_head_order(cache, lb, before, at, fused, &full.ho);
             a.probe = g_probe % 1000000;
             int mth = 1;
@@ -618,4 +689,25 @@ extern "C" int ssd_decode_step(ssd_cache *cache, int layer_begin, int layer_end,
             return fail(SSD_ERR_STAGE_OVERFLOW, "row buffer overflow: layer %d already buffers %d tokens (C=%d); call ssd_compress_kv",
                         l, cache->st[l].c, cache->cfg.stage_cap);
     return run_step(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, stream, "decode step launch");
+}
+
+extern "C" int ssd_decode_step_rope(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new,
+                                    const void *v_new, void *out, int accumulate_scores, int compress, const float *cos_p,
+                                    const float *sin_p, int rope_layout, void *stream) {
+    clear_error();
+    int rc = check_layers(cache, layer_begin, layer_end);
+    if (rc != SSD_OK) return rc;
+    if (!q || !out || !k_new || !v_new) return fail(SSD_ERR_INVALID_ARG, "q, k_new, v_new or out is NULL");
+    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(k_new, 16) || !aligned(v_new, 16))
+        return fail(SSD_ERR_INVALID_ARG, "q / k_new / v_new / out must be 16-byte aligned");
+    if (rope_layout != SSD_ROPE_HALF && rope_layout != SSD_ROPE_INTERLEAVED)
+        return fail(SSD_ERR_INVALID_ARG, "rope_layout=%d is neither SSD_ROPE_HALF nor SSD_ROPE_INTERLEAVED", rope_layout);
+    if (!cos_p || !sin_p || !aligned(cos_p, 16) || !aligned(sin_p, 16))
+        return fail(SSD_ERR_INVALID_ARG, "cos / sin must be given and 16-byte aligned");
+    for (int l = layer_begin; l < layer_end; ++l)
+        if (has_buffer(cache, l) && cache->st[l].c >= cache->cfg.stage_cap)
+            return fail(SSD_ERR_STAGE_OVERFLOW, "row buffer overflow: layer %d already buffers %d tokens (C=%d); call ssd_compress_kv",
+                        l, cache->st[l].c, cache->cfg.stage_cap);
+    return run_step(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, stream,
+                    "decode step launch (rotary)", Rope{cos_p, sin_p, rope_layout});
 }

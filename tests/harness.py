@@ -70,13 +70,15 @@ def sample_units(wl: workload.Workload, ht: np.ndarray, k: int, seed: int = 0) -
 def gpu_decode(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.ndarray, schedule: np.ndarray,
                units: Sequence[Tuple[int, int, int]], layers_per_call: Optional[int] = None,
                export_steps: Optional[Sequence[int]] = None, p_end: Optional[int] = None,
-               cache: Optional[ssd.Cache] = None, p_begin: int = 0, accumulate: bool = True, fused: bool = False):
+               cache: Optional[ssd.Cache] = None, p_begin: int = 0, accumulate: bool = True, fused: bool = False,
+               rope: int = 0):
     """Decode positions [p_begin, p_end) on the GPU.  Returns
          outs   float32 numpy [steps, len(units), d]  outputs of the sampled units
          exports {step: {"pre": (pos, score) or None, "post": (pos, score)}} numpy [len(layers), B, H, slots]
          cache
     `export_steps`: steps at which the index tables of the sampled units' layers are exported, both
-    before the compression of that step (if one is due) and after it."""
+    before the compression of that step (if one is due) and after it.
+    `rope`: 0, or the element pairing with which the fused step rotates q and k on the way in (fused only)."""
     dev = data["q"].device
     p_end = wl.n_total if p_end is None else p_end
     cache = make_cache(wl, ht, dev) if cache is None else cache
@@ -88,6 +90,9 @@ def gpu_decode(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.ndar
     export_steps = set(export_steps or [])
     layers = sorted(set(l for (l, _, _) in units))
     exports = {}
+    if rope:
+        assert fused
+        cos_t, sin_t = (torch.from_numpy(t).to(dev) for t in workload.rope_tables(wl.n_total, wl.d))
 
     def export_layers():
         pos, sc = [], []
@@ -103,7 +108,10 @@ def gpu_decode(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.ndar
         fuse_now = fused
         for lb in range(0, wl.L, lpc):
             le = min(wl.L, lb + lpc)
-            if fuse_now:
+            if fuse_now and rope:
+                ssd.ssd_decode_step_rope(cache, lb, le, q[lb:le], k[lb:le], v[lb:le], out[lb:le], cos_t[p], sin_t[p], rope,
+                                         accumulate, bool(schedule[p]))
+            elif fuse_now:
                 ssd.ssd_decode_step(cache, lb, le, q[lb:le], k[lb:le], v[lb:le], out[lb:le], accumulate, bool(schedule[p]))
             else:
                 ssd.ssd_append_token(cache, lb, le, k[lb:le], v[lb:le])
@@ -121,6 +129,16 @@ def gpu_decode(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.ndar
             exports[p] = rec
     torch.cuda.synchronize()
     return outs.cpu().numpy(), exports, cache
+
+
+def rotate_rows(wl: workload.Workload, x: torch.Tensor, rope: int) -> torch.Tensor:
+    """Oracle-side rotary embedding of x [n_total, ..., d] (row p at position p), rounded to the workload dtype
+    the way the cache holds it.  bf16: the float form of the oracle's routine (the rounding that follows is a
+    quantisation both sides must take from the same float); f32: the definition in double."""
+    cos_t, sin_t = workload.rope_tables(wl.n_total, wl.d)
+    xf = x.to(torch.float32).cpu().numpy()
+    out = np.stack([oracle.rope(xf[p], cos_t[p], sin_t[p], rope, single=(wl.dtype == "bf16")) for p in range(xf.shape[0])])
+    return torch.from_numpy(out).to(wl.torch_dtype)
 
 
 def oracle_unit(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.ndarray, schedule: np.ndarray,

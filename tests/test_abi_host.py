@@ -355,6 +355,29 @@ def test_cfg_mix_rejects_bad_arguments_before_any_launch():
         assert ssd.ssd_last_error() != ""
 
 
+def test_rotary_step_rejects_bad_arguments_and_keeps_the_counters():
+    L, B, H, d = 2, 2, 4, 64
+    c = ssd.Cache(make_config(L, B, H, d, "bf16", 8, 1, 4, 1, 3), _ht(L, H), device=None)
+    ok = dict(q=FAKE, k=FAKE, v=FAKE, out=FAKE, cos=FAKE, sin=FAKE, layout=ssd.SSD_ROPE_HALF)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return ssd.lib.ssd_decode_step_rope(c.handle, 0, L, a["q"], a["k"], a["v"], a["out"], 1, 1, a["cos"], a["sin"], a["layout"], None)
+
+    for bad in (dict(cos=None), dict(sin=None), dict(cos=FAKE + 4), dict(sin=FAKE + 8), dict(layout=0), dict(layout=3), dict(q=None),
+                dict(k=FAKE + 2)):
+        assert call(**bad) == ssd.SSD_ERR_INVALID_ARG, bad
+        assert ssd.ssd_last_error() != ""
+        assert c.layer_state(0)[0] == 0                  # a refused call appends nothing
+    assert ssd.lib.ssd_decode_step_rope(c.handle, 0, L + 1, FAKE, FAKE, FAKE, FAKE, 1, 1, FAKE, FAKE, 1, None) == ssd.SSD_ERR_LAYER_RANGE
+    # accepted calls move the counters exactly like the plain fused step
+    c2 = ssd.Cache(make_config(L, B, H, d, "bf16", 8, 1, 4, 1, 3), _ht(L, H), device=None)
+    for step in range(12):
+        assert call(layout=1 + step % 2) == ssd.SSD_OK
+        ssd.ssd_decode_step(c2, 0, L, FAKE, FAKE, FAKE, FAKE, True, True)
+        assert [c.layer_state(l) for l in range(L)] == [c2.layer_state(l) for l in range(L)]
+
+
 def test_package_without_its_library_fails_loudly(tmp_path):
     """No CPU or PyTorch fallback: a copy of the package without the built library, on a machine where it
     cannot be built either, must refuse to import."""

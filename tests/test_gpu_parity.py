@@ -11,7 +11,7 @@ import oracle
 import paper_2510_18716_amd as ssd
 import workload
 from harness import (GAP_MARGIN, check_outputs, check_selection_on_own_scores, compare_unit_sets, gpu_decode,
-                     make_cache, oracle_unit, sample_units, say)
+                     make_cache, oracle_unit, rotate_rows, sample_units, say)
 
 pytestmark = pytest.mark.gpu
 
@@ -20,7 +20,7 @@ def _to_cuda(data):
     return {k: v.cuda() for k, v in data.items()}
 
 
-def _full_compare(wl, ht=None, lpc=None, k_units=10 ** 9, export_every=1, seed=0, device_gen=False, fused=False):
+def _full_compare(wl, ht=None, lpc=None, k_units=10 ** 9, export_every=1, seed=0, device_gen=False, fused=False, rope=0):
     ht = workload.head_map(wl) if ht is None else ht
     schedule = workload.compress_schedule(wl)
     say("case", wl.name, wl.dtype, "L%d B%d H%d d%d n0=%d N=%d W%d S%d M%d R%d C%d cadence%d lpc=%s fused=%s" % (
@@ -36,7 +36,8 @@ def _full_compare(wl, ht=None, lpc=None, k_units=10 ** 9, export_every=1, seed=0
     else:
         comp = [p for p in range(wl.n_total) if schedule[p]]
         steps = sorted(set(range(0, wl.n_total, export_every)) | {wl.n_total - 1} | set(comp[:: max(1, len(comp) // 8)]))
-    outs, exports, cache = gpu_decode(wl, dev_data, ht, schedule, units, layers_per_call=lpc, export_steps=steps, fused=fused)
+    outs, exports, cache = gpu_decode(wl, dev_data, ht, schedule, units, layers_per_call=lpc, export_steps=steps, fused=fused,
+                                      rope=rope)
     say("  gpu decode done: %d units, %d exported steps" % (len(units), len(exports)))
     # sampled units back on the host: the oracle sees the very same bits
     layers = sorted(set(l for (l, _, _) in units))
@@ -45,6 +46,8 @@ def _full_compare(wl, ht=None, lpc=None, k_units=10 ** 9, export_every=1, seed=0
     for ui, unit in enumerate(units):
         l, b, h = unit
         host = {x: dev_data[x][:, l:l + 1, b:b + 1, h:h + 1].cpu() for x in "qkv"}
+        if rope:        # the oracle gets q and k rotated by its own routine, then takes the ordinary route
+            host["q"], host["k"] = rotate_rows(wl, host["q"], rope), rotate_rows(wl, host["k"], rope)
         o_ref, hl, gl, u = oracle_unit(wl, host, ht[l:l + 1, h:h + 1], schedule, (0, 0, 0), layer=l, head=h)
         li = layers.index(l)
         diverged = compare_unit_sets(wl, ht, unit, li, exports, hl, gl, schedule)
@@ -153,6 +156,44 @@ def test_window_and_budget_per_head(fused):
     wl2 = workload.config(2).replace(name="cfg2-per-head", L=3, prompts=4,
                                      head_budget=tuple(tuple(int(x) for x in r.integers(8, 97, 16)) for _ in range(3)))
     _full_compare(wl2, k_units=48, export_every=50, device_gen=True, fused=fused)
+
+
+@pytest.mark.parametrize("rope", [ssd.SSD_ROPE_HALF, ssd.SSD_ROPE_INTERLEAVED], ids=["half", "interleaved"])
+def test_fused_step_with_rotary_embedding(rope):
+    # q and k rotated inside the fused step against the oracle's rotation followed by the ordinary oracle route:
+    # all four (dtype, head dim), budgets per head, Algorithm 2, and the 1B shape on sampled units
+    for dtype, d in (("bf16", 128), ("bf16", 64), ("f32", 128), ("f32", 64)):
+        wl = workload.Workload("rope-%s-%d" % (dtype, d), L=2, prompts=2, H=6, d=d, dtype=dtype, n0=9, grid_h=7, grid_w=9,
+                               W=13, M=10, S=2, R=2, C=7, cadence=5, seed=81, plain=True)
+        _full_compare(wl, fused=True, rope=rope)
+    hb = ((24, 5, 1, 7, 40, 3), (9, 9, 30, 2, 1, 17))
+    wl = workload.Workload("rope-per-head", L=2, prompts=1, H=6, d=128, dtype="bf16", n0=7, grid_h=6, grid_w=10, W=99, M=99,
+                           S=1, R=1, C=4, cadence=3, seed=31, plain=True, head_budget=hb)
+    _full_compare(wl, fused=True, rope=rope)
+    _full_compare(wl.replace(name="rope-alg2", head_budget=None, W=9, M=7, alg2=True, R=0, C=5, cadence=5), lpc=1, fused=True, rope=rope)
+    wl2 = workload.config(2).replace(name="cfg2-rope", L=2, prompts=4)
+    _full_compare(wl2, lpc=1, k_units=32, export_every=50, device_gen=True, fused=True, rope=rope)
+
+
+def test_rotary_step_equals_plain_step_on_rotated_rows():
+    # the stated equivalence, bit for bit: rotating and rounding q and k beforehand (by the oracle's float-form
+    # routine: one product and one fused multiply-add per element, as in the kernel) and calling the plain step
+    # gives the same outputs and the same cache
+    wl = workload.Workload("rope-equiv", L=2, prompts=2, H=8, d=128, dtype="bf16", n0=5, grid_h=6, grid_w=8, W=11, M=9,
+                           S=1, R=1, C=3, cadence=2, seed=83, plain=True)
+    ht = workload.head_map(wl)
+    data = _to_cuda(workload.generate(wl, head_type=ht))
+    sched = workload.compress_schedule(wl)
+    units = sample_units(wl, ht, 10 ** 9)
+    for rope in (ssd.SSD_ROPE_HALF, ssd.SSD_ROPE_INTERLEAVED):
+        o1, e1, _ = gpu_decode(wl, data, ht, sched, units, export_steps=[wl.n_total - 1], fused=True, rope=rope)
+        rot = dict(data)
+        rot["q"] = rotate_rows(wl, data["q"], rope).cuda()
+        rot["k"] = rotate_rows(wl, data["k"], rope).cuda()
+        o2, e2, _ = gpu_decode(wl, rot, ht, sched, units, export_steps=[wl.n_total - 1], fused=True)
+        assert np.array_equal(o1, o2)
+        for a, b in zip(e1[wl.n_total - 1]["post"], e2[wl.n_total - 1]["post"]):
+            assert np.array_equal(a, b)
 
 
 @FUSED

@@ -163,3 +163,77 @@ def test_cfg_mix_matches_numpy_and_keeps_the_total_mass():
     # the pair order matters: swapping conditional and unconditional changes the result
     sw = p.reshape(3, 2, 37)[:, ::-1].reshape(6, 37)
     assert not np.allclose(oracle.cfg_mix(sw, 5.0), oracle.cfg_mix(p, 5.0))
+
+
+# ---- O7: rotary position embedding (not from the paper; Su et al., "RoFormer") ----------------------
+
+def _perm_half_to_interleaved(d):
+    """index map: position in the interleaved layout of each element of the half layout"""
+    return np.array([2 * i for i in range(d // 2)] + [2 * i + 1 for i in range(d // 2)])
+
+
+def test_rope_special_cases_and_invariants():
+    r = np.random.default_rng(0)
+    for d in (2, 8, 64, 128):
+        x = r.standard_normal((5, d)).astype(np.float32)
+        cos_t, sin_t = workload.rope_tables(40, d)
+        for layout in (oracle.ROPE_HALF, oracle.ROPE_INTERLEAVED):
+            # position 0 turns nothing; any position keeps every pair's (hence the row's) length
+            np.testing.assert_array_equal(oracle.rope(x, cos_t[0], sin_t[0], layout), x)
+            y = oracle.rope(x, cos_t[17], sin_t[17], layout)
+            np.testing.assert_allclose((y.astype(np.float64) ** 2).sum(-1), (x.astype(np.float64) ** 2).sum(-1), rtol=1e-6)
+            # rotating to position p and then by the angles of position s lands at position p + s
+            z = oracle.rope(oracle.rope(x, cos_t[5], sin_t[5], layout), cos_t[12], sin_t[12], layout)
+            np.testing.assert_allclose(z, y, atol=2e-6)
+    # a quarter turn of one pair: (a, b) -> (-b, a); which elements form the pair is what the layouts differ in
+    x = np.array([1.0, 2.0, 3.0, 4.0], np.float32)
+    c, s = np.zeros(2, np.float32), np.ones(2, np.float32)
+    np.testing.assert_array_equal(oracle.rope(x, c, s, oracle.ROPE_HALF), [-3.0, -4.0, 1.0, 2.0])
+    np.testing.assert_array_equal(oracle.rope(x, c, s, oracle.ROPE_INTERLEAVED), [-2.0, 1.0, -4.0, 3.0])
+    # only the second pair turned
+    c, s = np.array([1.0, 0.0], np.float32), np.array([0.0, 1.0], np.float32)
+    np.testing.assert_array_equal(oracle.rope(x, c, s, oracle.ROPE_HALF), [1.0, -4.0, 3.0, 2.0])
+    np.testing.assert_array_equal(oracle.rope(x, c, s, oracle.ROPE_INTERLEAVED), [1.0, 2.0, -4.0, 3.0])
+
+
+def test_rope_is_complex_multiplication_and_depends_on_relative_position_only():
+    r = np.random.default_rng(1)
+    d, n = 64, 50
+    cos_t, sin_t = workload.rope_tables(n, d)
+    q = r.standard_normal(d).astype(np.float32)
+    k = r.standard_normal(d).astype(np.float32)
+    # the textbook statement: pair i as a complex number times e^{i * angle_i}
+    ang = np.arctan2(sin_t[23].astype(np.float64), cos_t[23].astype(np.float64))
+    zi = (q[0::2].astype(np.float64) + 1j * q[1::2]) * np.exp(1j * ang)
+    want_i = np.empty(d)
+    want_i[0::2], want_i[1::2] = zi.real, zi.imag
+    np.testing.assert_allclose(oracle.rope(q, cos_t[23], sin_t[23], oracle.ROPE_INTERLEAVED), want_i, atol=1e-6)
+    zh = (q[: d // 2].astype(np.float64) + 1j * q[d // 2:]) * np.exp(1j * ang)
+    np.testing.assert_allclose(oracle.rope(q, cos_t[23], sin_t[23], oracle.ROPE_HALF), np.concatenate([zh.real, zh.imag]), atol=1e-6)
+    # the two layouts are one rotation seen through a permutation of the elements
+    perm = _perm_half_to_interleaved(d)
+    xi = np.empty(d, np.float32)
+    xi[perm] = q
+    np.testing.assert_array_equal(oracle.rope(xi, cos_t[23], sin_t[23], oracle.ROPE_INTERLEAVED)[perm],
+                                  oracle.rope(q, cos_t[23], sin_t[23], oracle.ROPE_HALF))
+    # the property the embedding exists for: <R_p q, R_s k> depends on p - s only
+    for layout in (oracle.ROPE_HALF, oracle.ROPE_INTERLEAVED):
+        ref = float(np.dot(oracle.rope(q, cos_t[9], sin_t[9], layout).astype(np.float64), k))
+        for p, s_ in ((9, 0), (20, 11), (49, 40)):
+            got = float(np.dot(oracle.rope(q, cos_t[p], sin_t[p], layout).astype(np.float64),
+                               oracle.rope(k, cos_t[s_], sin_t[s_], layout).astype(np.float64)))
+            assert abs(got - ref) < 2e-4 * (1 + abs(ref))
+        other = float(np.dot(oracle.rope(q, cos_t[10], sin_t[10], layout).astype(np.float64), k))
+        assert abs(other - ref) > 1e-3      # and it does depend on it
+
+
+def test_rope_float_form_stays_within_rounding_of_the_definition():
+    r = np.random.default_rng(2)
+    d = 128
+    x = (r.standard_normal((64, d)) * 3).astype(np.float32)
+    cos_t, sin_t = workload.rope_tables(600, d)
+    for layout in (oracle.ROPE_HALF, oracle.ROPE_INTERLEAVED):
+        a = oracle.rope(x, cos_t[577], sin_t[577], layout, single=False)
+        b = oracle.rope(x, cos_t[577], sin_t[577], layout, single=True)
+        assert np.abs(a - b).max() <= 2 ** -22 * np.abs(x).max()      # one product's rounding, at most
+        assert (a != b).mean() < 0.5                                   # and mostly the very same float

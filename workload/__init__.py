@@ -182,6 +182,14 @@ def generate(wl: Workload, device="cpu", head_type: Optional[np.ndarray] = None,
     return out
 
 
+def rope_tables(n: int, d: int, base: float = 10000.0):
+    """cos, sin float32 [n, d/2] of the angles position * base^(-2i/d): the tables a caller of the rotary variant
+    of the fused step holds (an input to both sides; computed in float64, stored as float32)."""
+    inv = base ** (-np.arange(0, d, 2, dtype=np.float64) / d)
+    ang = np.arange(n, dtype=np.float64)[:, None] * inv[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
 def unit_arrays(data: Dict[str, torch.Tensor], li: int, b: int, h: int):
     """(q, K, V) of one (layer index within data, sequence, head) as float32 numpy [n_total, d]."""
     return tuple(

@@ -209,6 +209,32 @@ def test_algorithm2_spatial_heads_read_the_row_buffer(fused):
     _full_compare(wl, k_units=32, export_every=50, device_gen=True, fused=fused)
 
 
+@FUSED
+def test_maximum_sizes(fused):
+    # 128 heads (both words of the head mask, the type lists reversed in the odd layer)
+    wl = workload.Workload("H128", L=2, prompts=1, H=128, d=64, dtype="bf16", n0=3, grid_h=5, grid_w=6, W=7, M=5, S=1, R=1,
+                           C=3, cadence=2, spatial_frac=0.5, seed=41, plain=True)
+    _full_compare(wl, k_units=96, fused=fused)
+    _full_compare(wl.replace(name="H128-uneven", spatial_frac=0.25), k_units=96, lpc=1, fused=fused)
+    r = np.random.default_rng(7)
+    _full_compare(wl.replace(name="H128-per-head", head_budget=tuple(tuple(int(x) for x in r.integers(1, 12, 128)) for _ in range(2))),
+                  k_units=96, fused=fused)
+    # the largest batch the config accepts (65534 sequences: the grid's y extent), sampled units
+    wl = workload.Workload("B65534", L=1, prompts=32767, H=2, d=64, dtype="bf16", n0=2, grid_h=3, grid_w=4, W=3, M=2, S=1, R=1,
+                           C=2, cadence=1, spatial_frac=0.5, seed=45, plain=True)
+    _full_compare(wl, k_units=64, device_gen=True, fused=fused)
+    # the largest window the config accepts (a ring that never wraps here: everything is retained)
+    wl = workload.Workload("W65535", L=1, prompts=1, H=2, d=128, dtype="bf16", n0=4, grid_h=6, grid_w=8, W=65535, M=4, S=0,
+                           R=1, C=2, cadence=1, spatial_frac=1.0, seed=43, plain=True)
+    _full_compare(wl, fused=fused)
+    # M + C = 4096, the largest semantic unit: 4096 rows attended per step at the end, a compression that ranks
+    # 3904 candidates and evicts 904 of them (stand-alone kernel, a whole workgroup per head), a spatial window
+    # of 3500 rows beside it
+    wl = workload.Workload("M+C=4096", L=1, prompts=1, H=2, d=64, dtype="bf16", n0=4, grid_h=64, grid_w=64, W=3500, M=3000,
+                           S=2, R=96, C=1096, cadence=1000, spatial_frac=0.5, seed=47, plain=True)
+    _full_compare(wl, export_every=500, fused=fused)
+
+
 def test_unbounded_window_and_budget_equal_dense_kernel():
     wl = workload.Workload("unbounded", L=1, prompts=1, H=4, d=128, dtype="bf16", n0=5, grid_h=6, grid_w=7, W=64,
                            M=64, S=0, R=1, C=2, cadence=1, seed=11, plain=True)

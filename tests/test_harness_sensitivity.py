@@ -66,3 +66,28 @@ def test_closed_form_window_sets_used_by_the_harness():
     assert spatial_positions(wl, 6) == [0, 3, 4, 5]
     assert spatial_positions(wl.replace(alg2=True), 6, 4) == [0, 1, 2, 3, 4, 5]
     assert spatial_positions(wl.replace(alg2=True), 6, 6) == [0, 3, 4, 5]
+
+
+def _rope_unit(wl, ht, data, h, layout_q, layout_k, shift_k=0, flip_k=False, rotate_q=True):
+    q, K, V = workload.unit_arrays(data, 0, 0, h)
+    cos_t, sin_t = workload.rope_tables(wl.n_total + 1, wl.d)
+    import torch
+    rnd = lambda x: torch.from_numpy(x).to(torch.bfloat16).float().numpy()
+    qr = np.stack([oracle.rope(q[p], cos_t[p], sin_t[p], layout_q, single=True) for p in range(wl.n_total)]) if rotate_q else q
+    kr = np.stack([oracle.rope(K[p], cos_t[p + shift_k], (-sin_t if flip_k else sin_t)[p + shift_k], layout_k, single=True)
+                   for p in range(wl.n_total)])
+    u = oracle.Unit(ht[0, h] == workload.SEMANTIC, wl.W, wl.S, wl.M, wl.R, wl.C)
+    o, hl, _ = u.run(rnd(qr), rnd(kr), V, wl.scale, workload.compress_schedule(wl), log=True)
+    return o, hl
+
+
+@pytest.mark.parametrize("h", [0, 3])
+@pytest.mark.parametrize("bad", [dict(layout_q=2, layout_k=2), dict(layout_q=1, layout_k=2), dict(shift_k=1), dict(flip_k=True),
+                                 dict(rotate_q=False)])
+def test_planted_rotary_mistake_is_detected(case, h, bad):
+    # wrong pairing, k one position off, k turned the other way, q left unrotated
+    wl, ht, data = case
+    o_ref, hl_ref = _rope_unit(wl, ht, data, h, 1, 1)
+    o_bad, hl_bad = _rope_unit(wl, ht, data, h, **dict(dict(layout_q=1, layout_k=1), **bad))
+    sets_differ = ht[0, h] == workload.SEMANTIC and not np.array_equal(hl_ref, hl_bad)
+    assert _rejected(wl, o_ref, o_bad) or sets_differ, bad

@@ -3,6 +3,8 @@
 Small shapes compare every unit at every step; the Janus-Pro-shaped configurations run at full size in
 the benchmark's launch configuration and compare sampled units.  Index sets are compared exactly,
 outputs within the stated tolerance."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -399,10 +401,14 @@ def test_config5_large_batch_online_classification_then_decode(frac, W, M):
     say("  max abs output error %.3e" % worst)
 
 
-@pytest.mark.parametrize("seed", range(64))
+# SSD_RANDOM_SEEDS=a:b widens the sweep for a one-off run (default: the 64 committed seeds)
+_SEEDS = range(*(int(x) for x in os.environ.get("SSD_RANDOM_SEEDS", "0:64").split(":")))
+
+
+@pytest.mark.parametrize("seed", _SEEDS)
 def test_random_small_configurations(seed):
     """Seeded random shapes and policies (both dtypes and head dims, Algorithm 1 and 2, any cadence the row
-    buffer allows, budgets per layer or per head now and then), every unit compared at every step, fused and unfused."""
+    buffer allows, budgets per layer or per head and the rotary step now and then), every unit compared at every step, fused and unfused."""
     r = np.random.default_rng(1000 + seed)
     d = int(r.choice([64, 128]))
     dtype = str(r.choice(["bf16", "f32"]))
@@ -422,5 +428,6 @@ def test_random_small_configurations(seed):
     lpc = None if r.random() < 0.5 else 1
     if r.random() < 0.35:         # budgets per head instead (drawn last: the other cases keep their draws)
         wl = wl.replace(W_layers=None, M_layers=None, head_budget=tuple(tuple(int(x) for x in r.integers(1, 40, H)) for _ in range(L)))
+    rope = int(r.choice([0, 0, ssd.SSD_ROPE_HALF, ssd.SSD_ROPE_INTERLEAVED]))    # the fused leg, now and then with rotary embedding
     _full_compare(wl, lpc=lpc, fused=False)
-    _full_compare(wl, lpc=lpc, fused=True)
+    _full_compare(wl, lpc=lpc, fused=True, rope=rope)

@@ -159,7 +159,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every (layer, sequence, head) unit is independent, so it "
-              "shards without communication; see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+              "shards over GPUs without communication, but nothing here drives a second GPU); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

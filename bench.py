@@ -152,6 +152,9 @@ def main():
                     help="large-batch sweep (configuration 5): spatial fraction x W x M at B = 512, one JSON line with a list")
     ap.add_argument("--head-budgets", type=str, default="",
                     help="LO,HI: head-wise allocation -- every head its own W_h / M_h, seeded uniform in [LO, HI]")
+    ap.add_argument("--replicas", type=int, default=1,
+                    help="decode this many copies of the cache side by side (every step runs on each in turn), so that a small "
+                         "configuration's working set exceeds the 256 MB memory-side cache and its figure is an HBM figure")
     ap.add_argument("--rope", type=int, default=0,
                     help="1 / 2: time ssd_decode_step_rope (q and k rotated inside the step; pairs (i, i + d/2) / (2i, 2i+1))")
     ap.add_argument("--alg2", action="store_true",
@@ -214,7 +217,10 @@ def main():
     t_gen = time.time() - t0
     sched = workload.compress_schedule(wl)
     cfg = make_config(wl.L, wl.B, wl.H, wl.d, wl.dtype, wl.W, wl.S, wl.M, wl.R, wl.C, 0.0, int(wl.alg2))
-    cache = ssd.Cache(cfg, ht, device=dev, head_budget=None if wl.head_budget is None else np.asarray(wl.head_budget, np.int32))
+    caches = [ssd.Cache(cfg, ht, device=dev, head_budget=None if wl.head_budget is None else np.asarray(wl.head_budget, np.int32))
+              for _ in range(max(1, args.replicas))]
+    cache = caches[0]
+    R_rep = len(caches)
     out = torch.empty((wl.L, wl.B, wl.H, wl.d), dtype=wl.torch_dtype, device=dev)
     if args.rope:
         assert fused, "--rope times the fused step"
@@ -232,7 +238,6 @@ def main():
         stride_p = wl.L * stride_l
         qb, kb, vb, ob = data["q"].data_ptr(), data["k"].data_ptr(), data["v"].data_ptr(), out.data_ptr()
         stream = torch.cuda.current_stream().cuda_stream
-        h = cache.handle
         L_ = ssd.lib
         acc_i = int(accumulate)
         if args.rope:
@@ -242,6 +247,12 @@ def main():
             comp = int(bool(sched[p]))
             if ev is not None and fused:
                 ev[0].record()
+            for c_i in caches:                      # every replica takes the step (one replica unless --replicas)
+                step_one(c_i.handle, p, comp, ev, acct if c_i is cache else None)
+            if ev is not None and fused:
+                ev[1].record()
+
+        def step_one(h, p, comp, ev, acct):
             for ci, (lb, le) in enumerate(calls):
                 o = p * stride_p + lb * stride_l
                 if fused:
@@ -269,14 +280,13 @@ def main():
                 if comp:
                     rc = L_.ssd_compress_kv(h, lb, le, None, None, None, 0, stream)
                     assert rc == 0, ssd.ssd_last_error()
-            if ev is not None and fused:
-                ev[1].record()
 
         dt, whole = 0.0, None
         for k_i in passes:
             p_t = wl.n_total - k_i
             p_w = p_t - W_steps
-            cache.reset()
+            for c_i in caches:
+                c_i.reset()
             for p in range(0, wl.n0):               # the prompt, through ordinary decode steps
                 step(p)
             torch.cuda.synchronize()
@@ -298,15 +308,18 @@ def main():
 
         # algorithmic bytes of the timed launches, from the counters each launch ran with (host-only replay)
         acct = []
-        ssd.lib.ssd_cache_set_launch(cache.handle, 0)
+        for c_i in caches:
+            ssd.lib.ssd_cache_set_launch(c_i.handle, 0)
         for k_i in passes:
-            cache.reset()
+            for c_i in caches:
+                c_i.reset()
             for p in range(0, wl.n_total):
                 step(p, acct=acct if p >= wl.n_total - k_i else None)
-        ssd.lib.ssd_cache_set_launch(cache.handle, 1)
+        for c_i in caches:
+            ssd.lib.ssd_cache_set_launch(c_i.handle, 1)
         bytes_launch = float(np.mean(acct))
-        res = {"seconds": dt, "ms_per_step": dt / K_steps * 1e3, "value": wl.prompts * K_steps / dt,
-               "whole_decode": {"visual_tokens": wl.N, "seconds": whole, "value": wl.prompts * wl.N / whole, "unit": "tokens/s",
+        res = {"seconds": dt, "ms_per_step": dt / (K_steps * R_rep) * 1e3, "value": wl.prompts * K_steps * R_rep / dt,
+               "whole_decode": {"visual_tokens": wl.N, "seconds": whole, "value": wl.prompts * wl.N * R_rep / whole, "unit": "tokens/s",
                                 "note": "all %d visual tokens of the raster decode from the end of the prompt, cache filling up "
                                         "on the way" % wl.N},
                "launches_per_step": len(calls) * (1 if fused else 3), "bytes_per_launch": bytes_launch,
@@ -319,7 +332,8 @@ def main():
         n_ev = 2 if fused else 2 * len(calls)
         evs = []
         for k_i in passes:
-            cache.reset()
+            for c_i in caches:
+                c_i.reset()
             for p in range(0, wl.n_total - k_i):
                 step(p)
             evs_i = [[torch.cuda.Event(enable_timing=True) for _ in range(n_ev)] for _ in range(k_i)]
@@ -329,7 +343,7 @@ def main():
             torch.cuda.synchronize()
             evs += evs_i
         if fused:
-            durs = [e[0].elapsed_time(e[1]) / len(calls) for e in evs]
+            durs = [e[0].elapsed_time(e[1]) / (len(calls) * R_rep) for e in evs]
         else:
             durs = [e[2 * ci].elapsed_time(e[2 * ci + 1]) for e in evs for ci in range(len(calls))]
         avg_ms = float(np.mean(durs))
@@ -356,7 +370,7 @@ def main():
         "config": {"workload": wl.name, "layers": wl.L, "prompts": wl.prompts, "sequences": wl.B, "heads": wl.H,
                    "head_dim": wl.d, "prompt_tokens": wl.n0, "visual_tokens": wl.N, "window": wl.W, "budget": wl.M,
                    "init_sink": wl.S, "recent": wl.R, "stage_cap": wl.C, "cadence": wl.cadence,
-                   "spatial_fraction": wl.spatial_frac, "layers_per_call": lpc,
+                   "spatial_fraction": wl.spatial_frac, "layers_per_call": lpc, "replicas": R_rep,
                    "step": "append + attend(+score accumulate) + compress, every layer",
                    "launches_per_step": head["launches_per_step"],
                    "entry_points": ("ssd_decode_step_rope" if args.rope else "ssd_decode_step") if fused else "ssd_append_token, ssd_decode_attn, ssd_compress_kv",

@@ -213,8 +213,11 @@ static __device__ __forceinline__ uint4 rope_fragment(const uint4 &raw, const fl
 // in the arguments and derives its own rows and slots from it (the host's are those of the largest head).
 // ROPE: q and the new token's k are rotated by the position's angles on the way in (the rotated k is what the
 // cache receives), so that no separate launch has to touch them between the projections and this kernel.
-template <typename T, int D, int CH, int WPB, bool FUSED, bool PF = true, bool HEADS = false, bool ROPE = false>
-__global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read through fetch_args
+// SPLIT > 1 (with WPB = 1): SPLIT waves share one unit, taking every SPLIT-th wave-load of its rows, and meet
+// once in LDS; wave 0 carries on alone.  For launches of few, long units, which would leave most of the chip's
+// wave slots empty.
+template <typename T, int D, int CH, int WPB, bool FUSED, bool PF = true, bool HEADS = false, bool ROPE = false, int SPLIT = 1>
+__global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {      // read through fetch_args
     constexpr int VEC = Elem<T>::VEC;
     constexpr int LPR = D / VEC;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -226,7 +229,10 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
     const int t_c = a.c, t_base = a.base, t_R = a.R, t_lpr = a.lpr, t_new_pos = a.new_pos,
               t_new_slot_se = a.new_slot_se, t_do_compress = a.do_compress, t_accumulate = a.accumulate,
               t_M = a.g.M, t_C = a.g.C, t_row_bytes = a.g.row_bytes;
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: everything per-unit stays uniform
+    static_assert(SPLIT == 1 || (WPB == 1 && !HEADS), "a split unit has its workgroup to itself");
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: everything per-unit stays uniform
+    const int w = SPLIT > 1 ? 0 : wave;                   // unit of this workgroup the wave works on
+    const int part = SPLIT > 1 ? wave : 0;                // its share of that unit's rows
     const int lane = threadIdx.x & 63;
     const int sub = lane % LPR;
     // grid = (ceil(max heads of a type / WPB), B, 2 * layers): z selects the layer and the head type, the type
@@ -314,7 +320,7 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
     // valid slot and ignored later): a load under a per-lane condition makes the compiler wait for it on the
     // spot.
     auto store_new = [&]() {
-        if (FUSED && lane < LPR) {
+        if (FUSED && lane < LPR && part == 0) {
             const int slot = u.sem ? a.new_slot_se : a.new_slot_sp;
             const size_t off = (size_t)slot * (size_t)a.g.row_bytes + (size_t)sub * 16u;
             SSD_ST16(1, u.K + off, new_k);
@@ -329,7 +335,7 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
             new_k = rope_fragment<T, D>(new_k, a.rope_cos, a.rope_sin, a.rope_layout, sub);
         }
         if (!a.late_new_store) store_new();
-        if (tail) {
+        if (tail && part == 0) {
             const int last = sg.total > 0 ? sg.total - 1 : 0;    // no rows yet: slot of row 0, inside the unit
 #pragma unroll
             for (int k = 0; k < 2; ++k) {
@@ -344,10 +350,10 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
     if (a.probe % 100 == 2 || a.probe % 100 == 3 || a.probe % 100 >= 10) { sm.l = 1.f; after_first_issue(); } else
 #endif
     if (want_z)
-        stream_rows<T, D, CH, true, false, PF>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, zbuf, 0, 0, a.probe, after_first_issue);
+        stream_rows<T, D, CH, true, false, PF>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, part, SPLIT, q, a.qscale, sm, zbuf, 0, 0, a.probe, after_first_issue);
     else
-        stream_rows<T, D, CH, false, false, PF>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, 0, 1, q, a.qscale, sm, nullptr, 0, 0, a.probe, after_first_issue);
-    if (FUSED) {
+        stream_rows<T, D, CH, false, false, PF>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, part, SPLIT, q, a.qscale, sm, nullptr, 0, 0, a.probe, after_first_issue);
+    if (FUSED && part == 0) {
         // The new token, from the registers it was loaded into, is folded into lane group 0's softmax as
         // one more row (index sg.total).
         const float z = group_sum<LPR>(Elem<T>::dot(q, new_k)) * a.qscale;
@@ -365,6 +371,34 @@ __global__ __launch_bounds__(WPB * 64) void step_kernel(StepArgs) {      // read
         }
     }
     merge_groups<VEC, LPR, false>(sm);
+    if constexpr (SPLIT > 1) {
+        // the waves of the unit leave their partial (max, sum, output) in LDS; wave 0 combines them and goes on alone
+        float *mg = reinterpret_cast<float *>(lds_raw + a.wave_lds);       // [SPLIT][2 + D]
+        float *mine = mg + part * (2 + D);
+        if (lane == 0) { mine[0] = sm.m; mine[1] = sm.l; }
+        if (lane < LPR) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) mine[2 + sub * VEC + e] = sm.acc[e];
+        }
+        __syncthreads();                                  // also publishes every wave's logits in zbuf
+        if (part != 0) return;
+        float m_u = NEG_BIG;
+#pragma unroll
+        for (int p = 0; p < SPLIT; ++p) m_u = fmaxf(m_u, mg[p * (2 + D)]);
+        float l_u = 0.f, acc_u[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc_u[e] = 0.f;
+#pragma unroll
+        for (int p = 0; p < SPLIT; ++p) {
+            const float f = fast_exp2(mg[p * (2 + D)] - m_u);
+            l_u = fmaf(mg[p * (2 + D) + 1], f, l_u);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc_u[e] = fmaf(mg[p * (2 + D) + 2 + sub * VEC + e], f, acc_u[e]);
+        }
+        sm.m = m_u; sm.l = l_u;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sm.acc[e] = acc_u[e];
+    }
     const float m_all = sm.m;
     const float inv_l = sm.l > 0.f ? 1.0f / sm.l : 0.f;
 #ifdef SSD_PROBE
@@ -515,6 +549,12 @@ static void fill_head_order(const ssd_cache *c, int l, const LayerState &before,
     }
 }
 
+template <typename T, int D, int CH, int SPLIT>
+static void launch_split(const StepArgs &full, dim3 blocks, size_t lds, bool fused, hipStream_t s) {
+    if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, 1, true, true, false, false, SPLIT>), blocks, dim3(SPLIT * 64), lds, s, full);
+    else hipLaunchKernelGGL((step_kernel<T, D, CH, 1, false, true, false, false, SPLIT>), blocks, dim3(SPLIT * 64), lds, s, full);
+}
+
 template <typename T, int D, int CH, int WPB, bool PF = true>
 static void launch_one(const StepArgs &full, dim3 blocks, size_t lds, bool fused, bool heads, hipStream_t s) {
     const bool rope = full.h.rope_layout != 0;            // fused launches only (checked by the entry point)
@@ -545,14 +585,21 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
     a.late_new_store = g_probe / 1000000 == 1 ? 0 : g_probe / 1000000 == 2 ? 1 : (units > 2048 && units <= 16384 ? 1 : 0);
     int ch = g_tune.ch && !heads && !a.rope_layout ? g_tune.ch : 4;
     int wpb = g_tune.wpb ? g_tune.wpb : (units <= 2048 ? 1 : 4);
+    // few and long units (the high-resolution shape: 2048 units of 129 to 385 rows): four waves share a unit (code 14)
+    const int longest = a.se.total > a.sp.total ? a.se.total : a.sp.total;
+    if (!g_tune.wpb && !heads && !a.rope_layout && units <= 2048 && longest >= 96) wpb = 14;
     a.wave_lds = (int)(((size_t)a.zcap * 4 + (a.do_compress ? select_lds_bytes(M, n_cand, n_old) + 16 : 0) + 15) / 16 * 16);
-    while (wpb > 1 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;
+    while (wpb > 1 && wpb < 10 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;
     size_t lds = (size_t)wpb * a.wave_lds;
 #ifdef SSD_PROBE
     if ((size_t)(g_probe / 10000 % 100) * 1024 > lds) lds = (size_t)(g_probe / 10000 % 100) * 1024;   // occupancy experiments: pad the workgroup's LDS
 #endif
     const dim3 blocks = heads ? dim3((unsigned)RANK_GROUPS, (unsigned)B, (unsigned)(((H + wpb - 1) / wpb + RANK_GROUPS - 1) / RANK_GROUPS))   // rank order, see the kernel
                               : dim3((unsigned)((max_type_heads + wpb - 1) / wpb), (unsigned)B, (unsigned)(2 * layers));
+    // wpb codes 12 and 14: one unit per workgroup, shared by 2 or 4 waves
+#define SSD_SPLIT(CH_, SPLIT_) if (ch == CH_ && wpb == 10 + SPLIT_ && !heads && !a.rope_layout) { launch_split<T, D, CH_, SPLIT_>(full, dim3((unsigned)max_type_heads, (unsigned)B, (unsigned)(2 * layers)), (size_t)a.wave_lds + SPLIT_ * (2 + D) * sizeof(float), fused, s); return hipGetLastError(); }
+    SSD_SPLIT(2, 2) SSD_SPLIT(4, 2) SSD_SPLIT(2, 4) SSD_SPLIT(4, 4)
+#undef SSD_SPLIT
 #define SSD_CASE(CH_, WPB_) if (ch == CH_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_>(full, blocks, lds, fused, heads, s); return hipGetLastError(); }
     if constexpr (sizeof(T) == 2 && D == 128) {       // the shape the sweeps are run on has every variant
         SSD_CASE(1, 1) SSD_CASE(2, 1) SSD_CASE(4, 1)
@@ -662,7 +709,7 @@ extern "C" int ssd_tune_attend(int ch, int wpb, int probe) {
     g_probe = probe;
     if (ch == 0 && wpb == 0) { g_tune = DEFAULT_TUNE; return SSD_OK; }
 #ifndef SSD_PROBE
-    if ((ch != 0 && ch != 1 && ch != 2 && ch != 4) || (wpb != 0 && wpb != 1 && wpb != 2 && wpb != 4)) return SSD_ERR_INVALID_ARG;
+    if ((ch != 0 && ch != 1 && ch != 2 && ch != 4) || (wpb != 0 && wpb != 1 && wpb != 2 && wpb != 4 && wpb != 12 && wpb != 14)) return SSD_ERR_INVALID_ARG;
 #endif
     g_tune.ch = ch; g_tune.wpb = wpb;
     return SSD_OK;

@@ -237,6 +237,15 @@ def test_maximum_sizes(fused):
     _full_compare(wl, export_every=500, fused=fused)
 
 
+@FUSED
+def test_few_long_units_take_the_shared_unit_launch(fused):
+    # the launch the library picks by itself for at most 2048 units of at least 96 rows: four waves per unit
+    wl = workload.Workload("few-long", L=2, prompts=2, H=4, d=128, dtype="bf16", n0=6, grid_h=12, grid_w=14, W=100, M=97,
+                           S=1, R=2, C=30, cadence=25, seed=53, plain=True)
+    _full_compare(wl, fused=fused)
+    _full_compare(wl.replace(name="few-long-f32", dtype="f32", d=64, alg2=True, R=0, C=25), lpc=1, fused=fused)
+
+
 def test_unbounded_window_and_budget_equal_dense_kernel():
     wl = workload.Workload("unbounded", L=1, prompts=1, H=4, d=128, dtype="bf16", n0=5, grid_h=6, grid_w=7, W=64,
                            M=64, S=0, R=1, C=2, cadence=1, seed=11, plain=True)
@@ -280,15 +289,21 @@ def test_config3_headline_shape_per_layer_fused_sampled_units():
     _full_compare(wl, lpc=1, k_units=64, export_every=128, device_gen=True, fused=True)
 
 
-@pytest.mark.parametrize("ch,wpu", [(1, 1), (2, 1), (4, 1), (1, 2), (2, 2), (4, 2), (1, 4), (2, 4), (4, 4)])
+@pytest.mark.parametrize("ch,wpu", [(1, 1), (2, 1), (4, 1), (1, 2), (2, 2), (4, 2), (1, 4), (2, 4), (4, 4),
+                                    (2, 12), (4, 12), (2, 14), (4, 14)])
 def test_every_launch_shape_variant(ch, wpu):
-    # all kernel variants the tuning knobs can select must give the same results
+    # all kernel variants the tuning knobs can select must give the same results (12, 14: two / four waves share a unit)
     wl = workload.Workload("variant", L=2, prompts=1, H=6, d=128, dtype="bf16", n0=7, grid_h=9, grid_w=10, W=37,
                            M=21, S=2, R=2, C=9, cadence=6, seed=13, plain=True)
     assert ssd.lib.ssd_tune_attend(ch, wpu, 0) == 0
     try:
         _full_compare(wl, fused=False)
         _full_compare(wl, fused=True)
+        if wpu > 4:           # also the other dtype and head dim, a long row buffer (general selection) and Algorithm 2
+            _full_compare(wl.replace(name="variant-f32-64", dtype="f32", d=64), fused=True)
+            _full_compare(wl.replace(name="variant-long", R=3, C=40, cadence=33), fused=True)
+            _full_compare(wl.replace(name="variant-alg2", alg2=True, R=0, C=6, cadence=6), fused=True)
+            _full_compare(wl.replace(name="variant-empty-parts", W=3, M=2, S=0, R=1, C=2, cadence=1), fused=True)
     finally:
         assert ssd.lib.ssd_tune_attend(0, 0, 0) == 0
 

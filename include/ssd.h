@@ -350,7 +350,9 @@ int ssd_dense_decode_attn(const void *q, const void *K, const void *V, void *out
  * thread-safe, no effect on results; (0, 0, 0) / 0 restore the defaults, which
  * the library otherwise picks from the launch size.
  *   ssd_tune_attend : ch = wave-wide loads of K (and of V) per chunk (0, 1, 2,
- *                     4), wpb = units per workgroup (0, 1, 2, 4) of the
+ *                     4), wpb = units per workgroup (0, 1, 2, 4; or 12 / 14:
+ *                     one unit per workgroup shared by 2 / 4 wavefronts, with
+ *                     ch = 2 or 4) of the
  *                     attention / fused-step kernel; probe = 0, or 1000000 /
  *                     2000000 to force the fused step's new rows to be stored
  *                     at the start / after the end of the row stream (other

@@ -13,9 +13,10 @@
 // Roofline: HBM.  Algorithmic bytes per unit and step = rows * 2 * d * e (K and V) + 2 * d * e
 // (q in, out) + 8 * rows for a semantic unit's score read-modify-write.
 //
-// Two optional variants of the same kernel: HEADS (every head its own window or budget, taken from a table in
-// the arguments; heads dispatched longest first) and ROPE (the fused step rotates q and the new k by the
-// token's position on the way in).  The plain kernel pays for neither.
+// Optional variants of the same kernel: HEADS (every head its own window or budget, taken from a table in the
+// arguments; heads dispatched longest first), ROPE (the fused step rotates q and the new k by the token's
+// position on the way in) and SPLIT (several waves share a unit: for launches of few, long units).  The plain
+// kernel pays for none of them.
 //
 // Measurement probes.  A build with -DSSD_PROBE keeps variants of the kernel that leave work out, selected
 // by the third argument of ssd_tune_attend (decimal fields; 0 = the real kernel):

@@ -446,3 +446,23 @@ def test_random_small_configurations(seed):
     rope = int(r.choice([0, 0, ssd.SSD_ROPE_HALF, ssd.SSD_ROPE_INTERLEAVED]))    # the fused leg, now and then with rotary embedding
     _full_compare(wl, lpc=lpc, fused=False)
     _full_compare(wl, lpc=lpc, fused=True, rope=rope)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_long_units(seed):
+    """Seeded random shapes whose units are few and long enough (at least 96 rows once filled) for the launch in
+    which four waves share a unit; every unit compared at every step, fused and unfused."""
+    r = np.random.default_rng(5000 + seed)
+    d = int(r.choice([64, 128]))
+    dtype = str(r.choice(["bf16", "f32"]))
+    R = int(r.integers(0, 6))
+    cadence = int(r.integers(1, 40))
+    C_ = R + cadence + int(r.integers(0, 3))
+    wl = workload.Workload("long%d" % seed, L=int(r.integers(1, 3)), prompts=1, H=int(r.integers(1, 5)), d=d, dtype=dtype,
+                           n0=int(r.integers(1, 20)), grid_h=int(r.integers(10, 16)), grid_w=int(r.integers(12, 20)),
+                           W=int(r.integers(96, 200)), M=int(r.integers(96, 200)), S=int(r.integers(0, 4)), R=R, C=C_, cadence=cadence,
+                           spatial_frac=float(r.choice([0.0, 0.5, 1.0])), seed=int(r.integers(1 << 30)), plain=True,
+                           alg2=bool(r.integers(0, 2)))
+    lpc = None if r.random() < 0.5 else 1
+    _full_compare(wl, lpc=lpc, fused=False)
+    _full_compare(wl, lpc=lpc, fused=True)

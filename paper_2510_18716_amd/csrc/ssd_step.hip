@@ -589,6 +589,7 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
     // few and long units (the high-resolution shape: 2048 units of 129 to 385 rows): four waves share a unit (code 14)
     const int longest = a.se.total > a.sp.total ? a.se.total : a.sp.total;
     if (!g_tune.wpb && !heads && !a.rope_layout && units <= 2048 && longest >= 96) wpb = 14;
+    if (wpb > 10 && ch == 1) ch = 2;                      // the shared-unit launch exists with two and four loads per chunk
     a.wave_lds = (int)(((size_t)a.zcap * 4 + (a.do_compress ? select_lds_bytes(M, n_cand, n_old) + 16 : 0) + 15) / 16 * 16);
     while (wpb > 1 && wpb < 10 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;
     size_t lds = (size_t)wpb * a.wave_lds;
@@ -619,12 +620,12 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
     return hipErrorInvalidValue;
 }
 
-// Shared by ssd_decode_attn (k_new == NULL, compress == 0) and ssd_decode_step.
 struct Rope {
     const float *cos, *sin;
     int layout;
 };
 
+// Shared by ssd_decode_attn (k_new == NULL, compress == 0), ssd_decode_step and ssd_decode_step_rope.
 static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new, const void *v_new,
                     void *out, int accumulate, int compress, void *stream, const char *what, Rope rope = {nullptr, nullptr, 0}) {
     const ssd_config &cf = cache->cfg;
@@ -669,6 +670,7 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.n_att = at.n; a.nc = before.nc; a.row_buffer = cf.spatial_row_buffer;
             a.rope_layout = rope.layout; a.rope_cos = rope.cos; a.rope_sin = rope.sin;
             if (per_head(cache)) fill_head_order(cache, lb, before, at, fused, &full.ho);
+            else full.ho = HeadOrder{};                  // never read then; keeps the argument bytes defined
             a.probe = g_probe % 1000000;
             int mth = 1;
             for (int l = lb; l < le; ++l) {

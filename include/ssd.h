@@ -152,6 +152,20 @@ int ssd_cache_init_heads(const ssd_config *cfg, const uint8_t *head_type, const 
 /* W_h (spatial head) or M_h (semantic head) of one head, whichever init call made the cache. */
 int ssd_cache_head_budget(const ssd_cache *cache, int layer, int head, int32_t *value);
 
+/*
+ * Test hooks for the slot arithmetic (host only, nothing is enqueued): the same
+ * functions the kernels evaluate.
+ *   ssd_cache_head_runs    : the up to three runs of consecutive valid slots of
+ *                            one head's unit at the layer's current counters,
+ *                            in the order the attention streams them
+ *                            (start[k], len[k]; unused runs have len 0)
+ *   ssd_cache_spatial_slot : slot that holds `position` in a spatial head's
+ *                            unit (sink slot, else ring slot S + (p-S) mod ring
+ *                            size); SSD_ERR_INVALID_ARG for a semantic head
+ */
+int ssd_cache_head_runs(const ssd_cache *cache, int layer, int head, int32_t start[3], int32_t len[3]);
+int ssd_cache_spatial_slot(const ssd_cache *cache, int layer, int head, int position, int32_t *slot);
+
 /* Free the descriptor (not dev_mem).  NULL is allowed. */
 void ssd_cache_free(ssd_cache *cache);
 

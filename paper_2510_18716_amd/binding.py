@@ -55,6 +55,10 @@ lib.ssd_cache_init_heads.argtypes = [C.POINTER(SsdConfig), _vp, _vp, _vp, C.c_si
 lib.ssd_cache_init_heads.restype = C.c_int
 lib.ssd_cache_head_budget.argtypes = [_vp, C.c_int, C.c_int, C.POINTER(C.c_int32)]
 lib.ssd_cache_head_budget.restype = C.c_int
+lib.ssd_cache_head_runs.argtypes = [_vp, C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+lib.ssd_cache_head_runs.restype = C.c_int
+lib.ssd_cache_spatial_slot.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32)]
+lib.ssd_cache_spatial_slot.restype = C.c_int
 lib.ssd_cache_free.argtypes = [_vp]
 lib.ssd_cache_free.restype = None
 lib.ssd_cache_reset.argtypes = [_vp]
@@ -257,6 +261,17 @@ class Cache:
         """W_h of a spatial head, M_h of a semantic head."""
         v = C.c_int32(0)
         _check(lib.ssd_cache_head_budget(self._h, layer, head, C.byref(v)), "ssd_cache_head_budget")
+        return v.value
+
+    def head_runs(self, layer: int, head: int):
+        """[(start, len), ...] of the valid-slot runs of one head's unit (host arithmetic only)."""
+        st, ln = (C.c_int32 * 3)(), (C.c_int32 * 3)()
+        _check(lib.ssd_cache_head_runs(self._h, layer, head, st, ln), "ssd_cache_head_runs")
+        return [(st[k], ln[k]) for k in range(3) if ln[k] > 0]
+
+    def spatial_slot(self, layer: int, head: int, position: int) -> int:
+        v = C.c_int32(0)
+        _check(lib.ssd_cache_spatial_slot(self._h, layer, head, position, C.byref(v)), "ssd_cache_spatial_slot")
         return v.value
 
     def layer_window(self, layer: int) -> int:

@@ -422,6 +422,41 @@ int ssd_cache_head_budget(const ssd_cache *cache, int layer, int head, int32_t *
     return SSD_OK;
 }
 
+int ssd_cache_head_runs(const ssd_cache *cache, int layer, int head, int32_t start[3], int32_t len[3]) {
+    clear_error();
+    int rc = check_layers(cache, layer, layer + 1);
+    if (rc != SSD_OK) return rc;
+    if (head < 0 || head >= cache->cfg.n_heads) return fail(SSD_ERR_INVALID_ARG, "head=%d outside 0..%d", head, cache->cfg.n_heads - 1);
+    if (!start || !len) return fail(SSD_ERR_INVALID_ARG, "output pointer is NULL");
+    const ssd_config &cf = cache->cfg;
+    const LayerState &st = cache->st[layer];
+    const size_t i = (size_t)layer * cf.n_heads + head;
+    Segs s;
+    if (cache->head_type[i] == SSD_SEMANTIC) {
+        s = semantic_segs(cache, layer, st);
+        if (per_head(cache)) s.len[0] = st.m < cache->head_budget[i] ? st.m : cache->head_budget[i];
+    } else {
+        const int W = per_head(cache) ? cache->head_budget[i] : cache->Wl[layer];
+        s = ring_segs(cf.n_init_sink, W, cf.stage_cap, cf.spatial_row_buffer != 0, st.n, st.nc);
+    }
+    for (int k = 0; k < 3; ++k) { start[k] = s.start[k]; len[k] = s.len[k]; }
+    return SSD_OK;
+}
+
+int ssd_cache_spatial_slot(const ssd_cache *cache, int layer, int head, int position, int32_t *slot) {
+    clear_error();
+    int rc = check_layers(cache, layer, layer + 1);
+    if (rc != SSD_OK) return rc;
+    const ssd_config &cf = cache->cfg;
+    if (head < 0 || head >= cf.n_heads) return fail(SSD_ERR_INVALID_ARG, "head=%d outside 0..%d", head, cf.n_heads - 1);
+    const size_t i = (size_t)layer * cf.n_heads + head;
+    if (cache->head_type[i] != SSD_SPATIAL) return fail(SSD_ERR_INVALID_ARG, "head %d of layer %d is not a spatial head", head, layer);
+    if (position < 0 || !slot) return fail(SSD_ERR_INVALID_ARG, "bad position or output pointer");
+    const int W = per_head(cache) ? cache->head_budget[i] : cache->Wl[layer];
+    *slot = ring_slot(cf.n_init_sink, W + (cf.spatial_row_buffer ? cf.stage_cap : 0), position);
+    return SSD_OK;
+}
+
 int ssd_cache_export_slots(const ssd_cache *cache) {
     if (!cache) return 0;
     int slots = 0;

@@ -355,6 +355,57 @@ def test_cfg_mix_rejects_bad_arguments_before_any_launch():
         assert ssd.ssd_last_error() != ""
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_slot_arithmetic_holds_the_oracles_retained_sets(seed):
+    """The valid-slot runs and ring slots the kernels compute (the same host/device functions) against the oracle's
+    position sets, step by step, without a GPU: every retained position of a spatial head has its own slot inside
+    the runs and nothing else is in them; a semantic head's runs have as many slots as it retains tokens."""
+    r = np.random.default_rng(300 + seed)
+    L, B, H, d = 2, 2, int(r.integers(2, 7)), 64
+    S, R = int(r.integers(0, 4)), int(r.integers(0, 3))
+    cadence = int(r.integers(1, 7))
+    C_ = R + cadence + int(r.integers(0, 2))
+    alg2 = bool(r.integers(0, 2))
+    ht = (r.random((L, H)) < 0.5).astype(np.uint8)
+    per_head = bool(r.integers(0, 2))
+    hb = r.integers(1, 12, (L, H)).astype(np.int32)
+    W, M = int(r.integers(1, 12)), int(r.integers(1, 12))
+    cfg = make_config(L, B, H, d, "bf16", W, S, M, R, C_, 0.0, int(alg2))
+    c = ssd.Cache(cfg, ht, device=None, head_budget=hb if per_head else None)
+    units = [[oracle.Unit(bool(ht[l, h]), int(hb[l, h]) if per_head else W, S, int(hb[l, h]) if per_head else M, R, C_,
+                          buffered_spatial=alg2) for h in range(H)] for l in range(L)]
+    for step in range(45):
+        comp = (step + 1) % cadence == 0
+        ssd.ssd_append_token(c, 0, L, FAKE, FAKE)
+        for l in range(L):
+            for h in range(H):
+                u = units[l][h]
+                assert u.append() == 0
+                runs = c.head_runs(l, h)
+                slots = [s for (a, n) in runs for s in range(a, a + n)]
+                assert len(slots) == len(set(slots))
+                kept = u.retained()
+                if ht[l, h] == 0:
+                    assert sorted(c.spatial_slot(l, h, int(p)) for p in kept) == sorted(slots), (l, h, step)
+                    if alg2:    # the runs of Algorithm 2's ring follow the positions, oldest first
+                        by_slot = {c.spatial_slot(l, h, int(p)): int(p) for p in kept}
+                        ring = [by_slot[s] for s in slots if s >= S]
+                        assert ring == sorted(ring)
+                else:
+                    assert len(slots) == len(kept), (l, h, step)
+        if comp:
+            ssd.ssd_compress_kv(c, 0, L)
+            for row in units:
+                for u in row:
+                    u.compress()
+    with pytest.raises(ssd.SsdError):
+        c.head_runs(0, H)
+    sem = [(l, h) for l in range(L) for h in range(H) if ht[l, h] == 1]
+    if sem:
+        with pytest.raises(ssd.SsdError):
+            c.spatial_slot(sem[0][0], sem[0][1], 0)
+
+
 def test_rotary_step_rejects_bad_arguments_and_keeps_the_counters():
     L, B, H, d = 2, 2, 4, 64
     c = ssd.Cache(make_config(L, B, H, d, "bf16", 8, 1, 4, 1, 3), _ht(L, H), device=None)

@@ -141,8 +141,10 @@ int ssd_cache_layer_budget(const ssd_cache *cache, int layer, int32_t *window, i
  * W_h (spatial) or M_h (semantic); head h uses a ring of W_h slots, or the
  * first M_h heavy slots, of its unit, and the row buffer of every semantic
  * head of the layer starts at slot max_h M_h.  So memory is that of the
- * largest head, while the rows a step reads are each head's own.  Every call
- * then takes one launch per layer.  Everything else is unchanged; the host
+ * largest head, while the rows a step reads are each head's own.  A layer
+ * whose heads differ takes a launch of its own in every call (a layer whose
+ * heads of each type agree is handled like one of ssd_cache_init_layered).
+ * Everything else is unchanged; the host
  * counter m of ssd_cache_layer_state is the layer's largest (a head has
  * min(m, M_h) heavy slots in use).
  */

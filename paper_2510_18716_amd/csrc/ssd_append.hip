@@ -82,7 +82,7 @@ extern "C" int ssd_append_token(ssd_cache *cache, int layer_begin, int layer_end
             a.pos = st.n;
             a.slot_sp = spatial_slot(cache, lb, st.n);
             a.slot_se = cache->Ml[lb] + (st.base + st.c) % cf.stage_cap;
-            a.heads = per_head(cache) ? 1 : 0;
+            a.heads = heads_differ(cache, lb) ? 1 : 0;
             fill_head_table(cache, lb, &a.ht);
             const long long threads = (long long)a.n_units * 2 * a.lpr;
             const unsigned blocks = (unsigned)((threads + 255) / 256);

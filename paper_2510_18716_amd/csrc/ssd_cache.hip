@@ -228,19 +228,19 @@ static bool same_geom(const ssd_cache *c, int a, int b) { return c->Wl[a] == c->
 
 int same_state_run(const ssd_cache *c, int lb, int le) {
     int l = lb + 1;
-    if (per_head(c)) return l;
+    if (heads_differ(c, lb)) return l;
     // layers with and without semantic heads never share a launch: only the former have a row buffer
     const bool buf = has_buffer(c, lb), has_se = c->ldesc[lb].n_se > 0;
     while (l < le && l - lb < LMAX && c->st[l] == c->st[lb] && same_geom(c, l, lb) && has_buffer(c, l) == buf &&
-           (c->ldesc[l].n_se > 0) == has_se)
+           (c->ldesc[l].n_se > 0) == has_se && !heads_differ(c, l))
         ++l;
     return l;
 }
 
 int same_geom_run(const ssd_cache *c, int lb, int le) {
     int l = lb + 1;
-    if (per_head(c)) return l;
-    while (l < le && l - lb < LMAX && same_geom(c, l, lb)) ++l;
+    if (heads_differ(c, lb)) return l;
+    while (l < le && l - lb < LMAX && same_geom(c, l, lb) && !heads_differ(c, l)) ++l;
     return l;
 }
 
@@ -331,6 +331,12 @@ int ssd_cache_init_heads(const ssd_config *cfg, const uint8_t *head_type, const 
     const size_t n = (size_t)cfg->n_layers * cfg->n_heads;
     (*out)->head_budget.resize(n);
     for (size_t i = 0; i < n; ++i) (*out)->head_budget[i] = (uint16_t)head_budget[i];
+    (*out)->heads_differ.assign(cfg->n_layers, 0);
+    for (int l = 0; l < cfg->n_layers; ++l)
+        for (int h = 0; h < cfg->n_heads; ++h) {
+            const size_t i = (size_t)l * cfg->n_heads + h;
+            if (head_budget[i] != (head_type[i] == SSD_SEMANTIC ? Ml[l] : Wl[l])) (*out)->heads_differ[l] = 1;
+        }
     return SSD_OK;
 }
 
@@ -483,7 +489,7 @@ int ssd_cache_export(ssd_cache *cache, int layer, int32_t *pos, int32_t *count, 
     HeadTable ht;
     fill_head_table(cache, layer, &ht);
     hipLaunchKernelGGL(export_kernel, dim3(units), dim3(64), 0, s, make_geom(cache, layer), cache->ldesc[layer], st, se, ref,
-                       ssd_cache_export_slots(cache), ht, per_head(cache) ? 1 : 0, pos, count, score);
+                       ssd_cache_export_slots(cache), ht, heads_differ(cache, layer) ? 1 : 0, pos, count, score);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "export launch");
     return SSD_OK;

@@ -157,7 +157,7 @@ int launch_compress_inplace(const ssd_cache *cache, int lb, int le, const LayerS
     a.base = st.base;
     a.R = cf.recent;
     a.lpr = cf.head_dim * cache->esize / 16;
-    a.heads = per_head(cache) ? 1 : 0;
+    a.heads = heads_differ(cache, lb) ? 1 : 0;
     fill_head_table(cache, lb, &a.ht);
     const int n_cand = st.m + n_old;
     const unsigned units = (unsigned)((le - lb) * cf.n_seqs * cf.n_heads);
@@ -205,7 +205,7 @@ extern "C" int ssd_compress_kv(ssd_cache *cache, int layer_begin, int layer_end,
                 a.n_src = n_src;
                 a.R = cf.recent;
                 a.lpr = lpr;
-                a.heads = per_head(cache) ? 1 : 0;
+                a.heads = heads_differ(cache, lb) ? 1 : 0;
                 fill_head_table(cache, lb, &a.ht);
                 const size_t lds = sizeof(unsigned long long) * (size_t)n_cand + sizeof(int) * (size_t)cache->Ml[lb] + (size_t)n_cand + 16;
                 hipLaunchKernelGGL((compress_dense_kernel<256>), dim3((unsigned)((le - lb) * BH)), dim3(256), lds, s, a);

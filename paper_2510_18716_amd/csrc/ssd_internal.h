@@ -121,6 +121,7 @@ struct ssd_cache {
     std::vector<int32_t> Wl, Ml;              // [L] window and budget of each layer (cfg.window / cfg.budget unless given per layer);
                                               //     with budgets per head: the largest of the layer, which sizes its units
     std::vector<uint16_t> head_budget;        // [L*H] W_h of a spatial head, M_h of a semantic head; empty unless given per head
+    std::vector<uint8_t> heads_differ;        // [L] 1 where the heads of one type do not all share one budget (empty unless given per head)
     std::vector<ssd::LayerState> st;          // [L]
     char *dev;
     size_t bytes;
@@ -149,8 +150,11 @@ int spatial_slot(const ssd_cache *c, int l, int p);
 void apply_compress_counters(ssd_cache *c, int l);
 // does layer l keep a row buffer (semantic heads, or spatial heads under Algorithm 2)
 bool has_buffer(const ssd_cache *c, int l);
-// budgets per head?  (then every launch covers one layer and carries that layer's HeadTable)
+// budgets given per head?
 static inline bool per_head(const ssd_cache *c) { return !c->head_budget.empty(); }
+// ... and do they differ inside layer l?  (then a launch covers that one layer and carries its HeadTable; a layer
+// whose heads agree is an ordinary layer with that window and budget)
+static inline bool heads_differ(const ssd_cache *c, int l) { return per_head(c) && c->heads_differ[l] != 0; }
 void fill_head_table(const ssd_cache *c, int l, HeadTable *out);
 // end of the run of layers starting at lb that share layer lb's state, window and budget, at most LMAX long
 // (one layer when budgets are per head)

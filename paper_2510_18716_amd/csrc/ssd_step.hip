@@ -669,7 +669,7 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.lpr = a.g.row_bytes / 16;
             a.n_att = at.n; a.nc = before.nc; a.row_buffer = cf.spatial_row_buffer;
             a.rope_layout = rope.layout; a.rope_cos = rope.cos; a.rope_sin = rope.sin;
-            if (per_head(cache)) fill_head_order(cache, lb, before, at, fused, &full.ho);
+            if (heads_differ(cache, lb)) fill_head_order(cache, lb, before, at, fused, &full.ho);
             else full.ho = HeadOrder{};                  // never read then; keeps the argument bytes defined
             a.probe = g_probe % 1000000;
             int mth = 1;
@@ -680,11 +680,11 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.sem_first = a.se.total + (fused ? 1 : 0) >= a.sp.total + (fused ? 1 : 0) ? 1 : 0;
             hipError_t e;
             if (cf.dtype == SSD_BF16)
-                e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, per_head(cache), cache->Ml[lb], s)
-                                       : launch_step<bf16_t, 64>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, per_head(cache), cache->Ml[lb], s);
+                e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, heads_differ(cache, lb), cache->Ml[lb], s)
+                                       : launch_step<bf16_t, 64>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, heads_differ(cache, lb), cache->Ml[lb], s);
             else
-                e = cf.head_dim == 128 ? launch_step<float, 128>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, per_head(cache), cache->Ml[lb], s)
-                                       : launch_step<float, 64>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, per_head(cache), cache->Ml[lb], s);
+                e = cf.head_dim == 128 ? launch_step<float, 128>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, heads_differ(cache, lb), cache->Ml[lb], s)
+                                       : launch_step<float, 64>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, heads_differ(cache, lb), cache->Ml[lb], s);
             if (e != hipSuccess) return hip_fail(e, what);
             if (do_compress && !in_kernel) {
                 const int rc = launch_compress_inplace(cache, lb, le, at, s);

@@ -152,6 +152,9 @@ def test_window_and_budget_per_head(fused):
     _full_compare(wl.replace(name="per-head-calls"), lpc=1, fused=fused)
     _full_compare(wl.replace(name="per-head-alg2", alg2=True, R=0, C=5, cadence=5), fused=fused)
     _full_compare(wl.replace(name="per-head-f32-d64", dtype="f32", d=64, S=2, R=2, C=9, cadence=6), fused=fused)
+    # layers whose heads agree (handled like per-layer budgets, two of them sharing a launch) around one whose heads differ
+    mixed = ((7, 7, 7, 5, 5, 5), (5, 5, 5, 7, 7, 7), (9, 4, 7, 5, 2, 5), (5, 5, 5, 7, 7, 7))   # W = 7, M = 5 where uniform
+    _full_compare(wl.replace(name="per-head-mixed-layers", L=4, spatial_frac=0.5, head_budget=mixed), fused=fused)
     # long row buffer: many evictions per compression, the general selection path with each head's own M_h
     _full_compare(wl.replace(name="per-head-long-buffer", R=3, C=40, cadence=33), fused=fused)
     r = np.random.default_rng(5)

@@ -14,6 +14,8 @@ Prints ONE JSON line:
                    timed with HIP events on the launch stream, against the 8 TB/s HBM peak
   all_layers_one_launch   the same steps with all layers handed to the library in one call (possible only
                    because the synthetic queries of all layers exist up front: an upper bound)
+  stream_ceiling   a plain read of as many units of as many bytes per launch, no arithmetic, without and with the
+                   least a step must store: what the memory system allows a launch of this shape
   dense_baseline   the same steps through the full-cache decode kernel
   cpu_baseline     the CPU oracle timed on a sample of (layer, sequence, head) units
 """
@@ -140,6 +142,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-microbatch", action="store_true")
+    ap.add_argument("--no-ceiling", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--no-all-layers", action="store_true")
     ap.add_argument("--tune", type=str, default="", help="ch,wpb[,probe] launch-shape knobs of the attention kernel")
@@ -433,6 +436,39 @@ def main():
             "note": "same step, the sequences split into two caches of %d whose per-layer launches go to two streams: the start and "
                     "the tail of one half's launch overlap the other's; each half keeps its layer order" % Bm}
         del caches
+
+    # ---- what the memory system allows a launch of this shape: a plain read of as many units of as many bytes,
+    #      one launch per layer, without and with the least a decode step must store (two 256-byte rows per unit)
+    if not args.no_ceiling:
+        n_units = wl.B * wl.H
+        n_, m_, c_, _ = cache.layer_state(0)
+        rows_u = max(2, int(round((algorithmic_bytes_attend(wl, ht, range(1), (n_, m_, c_)) / n_units) / (2 * row_bytes(wl)))))
+        unit_b = rows_u * 2 * row_bytes(wl)
+        unit_b = (unit_b + 511) // 512 * 512
+        layers_c = min(wl.L, max(1, (6 << 30) // (n_units * unit_b)))              # distinct memory per launch, at most 6 GiB
+        buf = torch.zeros(layers_c * n_units * unit_b, dtype=torch.uint8, device=dev)
+        sink = torch.zeros(64, dtype=torch.uint8, device=dev)
+        stream = torch.cuda.current_stream().cuda_stream
+        ceil = {}
+        for key, rows_w in (("read_only", 0), ("read_and_two_row_writes", 2)):
+            def one_pass():
+                for l in range(layers_c):
+                    rc = ssd.lib.ssd_bench_stream(buf.data_ptr() + l * n_units * unit_b, unit_b, n_units, rows_w, sink.data_ptr(), stream)
+                    assert rc == 0, ssd.ssd_last_error()
+            one_pass()
+            torch.cuda.synchronize()
+            reps = 10
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                one_pass()
+            torch.cuda.synchronize()
+            us = (time.perf_counter() - t0) / (reps * layers_c) * 1e6
+            moved = n_units * (unit_b + 256 * rows_w)
+            ceil[key] = {"us_per_launch": us, "GBps": moved / 1e3 / us, "frac_of_hbm_peak": moved / 1e3 / us / HBM_PEAK_GBS}
+        result["stream_ceiling"] = dict(ceil, units_per_launch=n_units, bytes_per_unit=unit_b, launches_timed=layers_c,
+                                        kind="ssd_bench_stream: every unit read once by one wavefront, no arithmetic; the second line "
+                                             "also stores one 256-byte row into each plane of every unit (a new token's K and V)")
+        del buf
 
     # ---- prompt scoring (accumulated causal scores of the n0 prompt tokens), one launch per layer ------------
     if not args.no_prefill:

@@ -379,6 +379,21 @@ int ssd_dense_decode_attn(const void *q, const void *K, const void *V, void *out
 int ssd_tune_attend(int ch, int wpb, int probe);
 int ssd_tune_dense(int splits);
 
+/*
+ * Benchmark aid, not part of the method: move what a decode launch moves with
+ * none of its arithmetic.  n_units units of unit_bytes each (contiguous in
+ * buf, a multiple of 512 bytes: two planes of 256-byte rows) are each read
+ * once by one wavefront, four units per workgroup; with rows_written = 2 every
+ * wavefront then stores one 256-byte row into each plane of its unit -- the
+ * least a decode step must write per head (the new token's K and V rows).
+ * Timing it at a launch's shape tells what the memory system allows a kernel
+ * of that shape, with and without the writes.
+ *   buf  : dev, n_units * unit_bytes bytes, 16-byte aligned; overwritten in part when rows_written = 2
+ *   sink : dev, at least 16 bytes (never written in practice)
+ */
+int ssd_bench_stream(void *buf, size_t unit_bytes, long long n_units, int rows_written,
+                     void *sink, void *stream);
+
 /* Text of the calling thread's most recent error ("" if none). Never NULL. */
 const char *ssd_last_error(void);
 

@@ -429,6 +429,19 @@ def test_rotary_step_rejects_bad_arguments_and_keeps_the_counters():
         assert [c.layer_state(l) for l in range(L)] == [c2.layer_state(l) for l in range(L)]
 
 
+def test_stream_benchmark_rejects_bad_arguments_before_any_launch():
+    ok = dict(buf=FAKE, unit_bytes=66 * 512, n_units=4096, rows=2, sink=FAKE)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return ssd.lib.ssd_bench_stream(a["buf"], a["unit_bytes"], a["n_units"], a["rows"], a["sink"], None)
+
+    for bad in (dict(buf=None), dict(sink=None), dict(buf=FAKE + 8), dict(unit_bytes=0), dict(unit_bytes=512), dict(unit_bytes=1000),
+                dict(n_units=0), dict(rows=1), dict(rows=3)):
+        assert call(**bad) == ssd.SSD_ERR_INVALID_ARG, bad
+        assert ssd.ssd_last_error() != ""
+
+
 def test_package_without_its_library_fails_loudly(tmp_path):
     """No CPU or PyTorch fallback: a copy of the package without the built library, on a machine where it
     cannot be built either, must refuse to import."""

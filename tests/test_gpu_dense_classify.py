@@ -166,3 +166,22 @@ def test_dense_source_without_scores_keeps_lowest_positions():
     assert sorted(int(x) for x in pos[0, 0] if x >= 0) == [0, 26, 27, 28, 29]
     assert cnt[0].tolist() == [5, 8] and (sc == 0).all()
     assert cache.layer_state(0) == (30, 6, 2, 0)
+
+
+def test_stream_benchmark_reads_everything_and_writes_only_its_two_rows():
+    # the measurement aid behind bench.py's "stream_ceiling": it must touch what it says and nothing else
+    n_units, rows = 37, 5                                   # a ragged last workgroup
+    unit_b = rows * 2 * 256
+    buf = torch.randint(0, 255, (n_units + 1, unit_b), dtype=torch.uint8, device="cuda")     # one guard unit behind
+    before = buf.clone()
+    sink = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    assert ssd.lib.ssd_bench_stream(buf.data_ptr(), unit_b, n_units, 0, sink.data_ptr(), stream) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(buf, before) and int(sink.sum()) == 0
+    assert ssd.lib.ssd_bench_stream(buf.data_ptr(), unit_b, n_units, 2, sink.data_ptr(), stream) == 0
+    torch.cuda.synchronize()
+    changed = (buf != before).view(n_units + 1, 2, rows, 256).any(dim=3)      # [unit, plane, row]
+    assert not changed[n_units].any()                       # nothing behind the last unit
+    assert not changed[:, :, 1:].any()                      # only row 0 of each plane
+    assert changed[:n_units, :, 0].float().mean() > 0.9     # and that one is written (a random row rarely stays equal)

@@ -237,3 +237,14 @@ def test_rope_float_form_stays_within_rounding_of_the_definition():
         b = oracle.rope(x, cos_t[577], sin_t[577], layout, single=True)
         assert np.abs(a - b).max() <= 2 ** -22 * np.abs(x).max()      # one product's rounding, at most
         assert (a != b).mean() < 0.5                                   # and mostly the very same float
+
+
+def test_rope_tables_are_the_standard_angles():
+    cos_t, sin_t = workload.rope_tables(9, 8, base=10000.0)
+    assert cos_t.shape == sin_t.shape == (9, 4)
+    np.testing.assert_array_equal(cos_t[0], 1.0)
+    np.testing.assert_array_equal(sin_t[0], 0.0)
+    np.testing.assert_allclose(cos_t ** 2 + sin_t ** 2, 1.0, atol=1e-6)
+    # pair i turns by position * base^(-2i/d): pair 0 by one radian per position, the last pair slowest
+    np.testing.assert_allclose(np.arctan2(sin_t[1], cos_t[1]), [1.0, 0.1, 0.01, 0.001], rtol=1e-5)
+    np.testing.assert_allclose(np.arctan2(sin_t[3, 1:], cos_t[3, 1:]), [0.3, 0.03, 0.003], rtol=1e-5)

@@ -445,7 +445,10 @@ def main():
         rows_u = max(2, int(round((algorithmic_bytes_attend(wl, ht, range(1), (n_, m_, c_)) / n_units) / (2 * row_bytes(wl)))))
         unit_b = rows_u * 2 * row_bytes(wl)
         unit_b = (unit_b + 511) // 512 * 512
-        layers_c = min(wl.L, max(1, (6 << 30) // (n_units * unit_b)))              # distinct memory per launch, at most 6 GiB
+        per_launch = n_units * unit_b
+        # distinct memory per launch: as many regions as layers, more if that is needed to exceed the memory-side
+        # cache several times over (1.5 GB), at most 6 GiB in all
+        layers_c = max(1, min(max(wl.L, -(-1500000000 // per_launch)), (6 << 30) // per_launch))
         buf = torch.zeros(layers_c * n_units * unit_b, dtype=torch.uint8, device=dev)
         sink = torch.zeros(64, dtype=torch.uint8, device=dev)
         stream = torch.cuda.current_stream().cuda_stream

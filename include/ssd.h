@@ -154,20 +154,6 @@ int ssd_cache_init_heads(const ssd_config *cfg, const uint8_t *head_type, const 
 /* W_h (spatial head) or M_h (semantic head) of one head, whichever init call made the cache. */
 int ssd_cache_head_budget(const ssd_cache *cache, int layer, int head, int32_t *value);
 
-/*
- * Test hooks for the slot arithmetic (host only, nothing is enqueued): the same
- * functions the kernels evaluate.
- *   ssd_cache_head_runs    : the up to three runs of consecutive valid slots of
- *                            one head's unit at the layer's current counters,
- *                            in the order the attention streams them
- *                            (start[k], len[k]; unused runs have len 0)
- *   ssd_cache_spatial_slot : slot that holds `position` in a spatial head's
- *                            unit (sink slot, else ring slot S + (p-S) mod ring
- *                            size); SSD_ERR_INVALID_ARG for a semantic head
- */
-int ssd_cache_head_runs(const ssd_cache *cache, int layer, int head, int32_t start[3], int32_t len[3]);
-int ssd_cache_spatial_slot(const ssd_cache *cache, int layer, int head, int position, int32_t *slot);
-
 /* Free the descriptor (not dev_mem).  NULL is allowed. */
 void ssd_cache_free(ssd_cache *cache);
 
@@ -182,13 +168,6 @@ int ssd_cache_layer_state(const ssd_cache *cache, int layer, int32_t out4[4]);
 
 /* Token count of the layer at its last compression (the start of a spatial head's row buffer). */
 int ssd_cache_layer_window(const ssd_cache *cache, int layer, int32_t *n_at_last_compress);
-
-/*
- * Test hook: with enable == 0 every later call on this cache does all of its
- * checking and counter updates but enqueues nothing (for exercising the host
- * logic on a machine without a GPU).  Default: enabled.
- */
-int ssd_cache_set_launch(ssd_cache *cache, int enable);
 
 /*
  * Head classification by attention sparsity (Sec. 3.3, "Spatial Sparsity
@@ -249,7 +228,11 @@ int ssd_decode_attn(ssd_cache *cache, int layer_begin, int layer_end,
  * segment (the prefill branch of Algorithm 2).
  *   K_src, V_src : dev [layer_end - layer_begin, B, H, n_src, d], cache dtype
  *   score_src    : dev float [layer_end - layer_begin, B, H, n_src] accumulated
- *                  scores of those tokens, or NULL for all zero
+ *                  scores of those tokens, or NULL for all zero.  Every value
+ *                  must be finite and >= 0 (sums of probabilities are): the
+ *                  selection orders scores by their bit patterns, which is the
+ *                  numerical order for such values only; the library does not
+ *                  check this
  *   n_src        : 1 .. 4096 tokens
  * Spatial heads take positions {0..S-1} and the last W; semantic heads take
  * the top-M of positions 0..n_src-R-1 and put the R newest into the row
@@ -308,6 +291,41 @@ int ssd_decode_step(ssd_cache *cache, int layer_begin, int layer_end, const void
                     int accumulate_scores, int compress, void *stream);
 
 /*
+ * The same step with the batch dealt to several streams, so that the launches
+ * of different parts of the batch overlap: while one part's launch ramps up
+ * or drains, another part's is streaming.  Sequences are independent of each
+ * other (Sec. 3.1: each prompt is decoded on its own; the two sequences of a
+ * prompt meet only in Eq. 1, after the last layer), so a caller that runs its
+ * model on parts of the batch in turn (micro-batches) keeps every part's
+ * layers in order on that part's stream and never has to make the parts meet
+ * between layers.  Results are those of ssd_decode_step, bit for bit.
+ *   streams   : host array of n_streams distinct hipStream_t, all of the
+ *               default priority; n_streams in 1..SSD_MAX_SPLIT
+ *   Part i = sequences [i * P, min(B, (i + 1) * P)), P = B / n_streams rounded
+ *   up to an even number (a prompt's two sequences stay together); its work is
+ *   enqueued on streams[i] only, and the rows of q, k_new, v_new it reads and
+ *   of out it writes are ordered with respect to that stream only.
+ *   sync      : SSD_SPLIT_FORK  -- before anything is enqueued, streams[1..]
+ *               are made to wait for what streams[0] holds so far;
+ *               SSD_SPLIT_JOIN  -- afterwards streams[0] is made to wait for
+ *               what the other streams hold.  A caller with one stream of its
+ *               own forks at a token's first layer and joins at its last.
+ *               Both use events the cache keeps (made on first use, timing
+ *               disabled); nothing waits on the host, nothing is allocated on
+ *               the device.
+ * The host counters advance once per call (all parts move together), so a
+ * cache must not be used through this call and through the one-stream calls
+ * in between a fork and its join.  Errors as ssd_decode_step, plus
+ * SSD_ERR_INVALID_ARG for a bad stream list or sync value.
+ */
+enum { SSD_MAX_SPLIT = 4 };
+enum { SSD_SPLIT_FORK = 1, SSD_SPLIT_JOIN = 2 };
+int ssd_decode_step_split(ssd_cache *cache, int layer_begin, int layer_end, const void *q,
+                          const void *k_new, const void *v_new, void *out,
+                          int accumulate_scores, int compress,
+                          void *const *streams, int n_streams, int sync);
+
+/*
  * The same step with rotary position embedding (Su et al., "RoFormer") applied
  * to q and k_new on the way in, so that the rows the projections produce need
  * no launch of their own before this one.  The paper does not describe the
@@ -330,6 +348,8 @@ int ssd_decode_step_rope(ssd_cache *cache, int layer_begin, int layer_end, const
                          const void *k_new, const void *v_new, void *out, int accumulate_scores,
                          int compress, const float *cos, const float *sin, int rope_layout,
                          void *stream);
+
+/* ---- exports for tests and benchmarks (not steps of the method) ------------ */
 
 /*
  * Test / benchmark export of one layer's index table.
@@ -360,39 +380,6 @@ int ssd_dense_decode_attn(const void *q, const void *K, const void *V, void *out
                           float softmax_scale, float *far, float *tot, int mass_stride,
                           int vis_start, int w, void *workspace, size_t workspace_bytes,
                           void *stream);
-
-/*
- * Launch-shape knobs for benchmark sweeps and tests.  Process-wide, not
- * thread-safe, no effect on results; (0, 0, 0) / 0 restore the defaults, which
- * the library otherwise picks from the launch size.
- *   ssd_tune_attend : ch = wave-wide loads of K (and of V) per chunk (0, 1, 2,
- *                     4), wpb = units per workgroup (0, 1, 2, 4; or 12 / 14:
- *                     one unit per workgroup shared by 2 / 4 wavefronts, with
- *                     ch = 2 or 4) of the
- *                     attention / fused-step kernel; probe = 0, or 1000000 /
- *                     2000000 to force the fused step's new rows to be stored
- *                     at the start / after the end of the row stream (other
- *                     values select measurement variants in probe builds only)
- *   ssd_tune_dense  : number of row splits of the full-cache kernel (0..64)
- * Return SSD_ERR_INVALID_ARG for values outside these sets.
- */
-int ssd_tune_attend(int ch, int wpb, int probe);
-int ssd_tune_dense(int splits);
-
-/*
- * Benchmark aid, not part of the method: move what a decode launch moves with
- * none of its arithmetic.  n_units units of unit_bytes each (contiguous in
- * buf, a multiple of 512 bytes: two planes of 256-byte rows) are each read
- * once by one wavefront, four units per workgroup; with rows_written = 2 every
- * wavefront then stores one 256-byte row into each plane of its unit -- the
- * least a decode step must write per head (the new token's K and V rows).
- * Timing it at a launch's shape tells what the memory system allows a kernel
- * of that shape, with and without the writes.
- *   buf  : dev, n_units * unit_bytes bytes, 16-byte aligned; overwritten in part when rows_written = 2
- *   sink : dev, at least 16 bytes (never written in practice)
- */
-int ssd_bench_stream(void *buf, size_t unit_bytes, long long n_units, int rows_written,
-                     void *sink, void *stream);
 
 /* Text of the calling thread's most recent error ("" if none). Never NULL. */
 const char *ssd_last_error(void);

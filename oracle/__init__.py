@@ -59,7 +59,7 @@ _lib.ssd_oracle_prefill_scores.argtypes = [_f32p, _f32p, C.c_int, C.c_int, C.c_d
 _lib.ssd_oracle_prefill_scores.restype = None
 _lib.ssd_oracle_cfg_mix.argtypes = [_f32p, C.c_int, C.c_int, C.c_double, _f32p]
 _lib.ssd_oracle_cfg_mix.restype = None
-_lib.ssd_oracle_rope.argtypes = [_f32p, C.c_int, _f32p, _f32p, C.c_int, C.c_int, _f32p]
+_lib.ssd_oracle_rope.argtypes = [_f32p, C.c_int, _f32p, _f32p, C.c_int, _f32p]
 _lib.ssd_oracle_rope.restype = None
 _lib.ssd_oracle_top_m.argtypes = [_f32p, _i32p, C.c_int, C.c_int, _i32p, C.POINTER(C.c_double)]
 _lib.ssd_oracle_top_m.restype = C.c_int
@@ -166,10 +166,9 @@ def cfg_mix(p, gamma):
 ROPE_HALF, ROPE_INTERLEAVED = 1, 2
 
 
-def rope(x, cos, sin, layout, single=False):
+def rope(x, cos, sin, layout):
     """O7.  Rotary position embedding of rows x [..., d] at one position (cos, sin: [d/2]) -> float32 [..., d].
-    layout ROPE_HALF pairs element i with i + d/2, ROPE_INTERLEAVED pairs 2i with 2i+1.  `single`: float
-    arithmetic in the order the kernel states (for results that are rounded to bfloat16 next)."""
+    layout ROPE_HALF pairs element i with i + d/2, ROPE_INTERLEAVED pairs 2i with 2i+1.  The definition, in double."""
     x = _f32(x)
     d = x.shape[-1]
     cos, sin = _f32(cos), _f32(sin)
@@ -177,7 +176,7 @@ def rope(x, cos, sin, layout, single=False):
     rows = np.ascontiguousarray(x.reshape(-1, d))
     out = np.zeros_like(rows)
     for i in range(rows.shape[0]):
-        _lib.ssd_oracle_rope(rows[i], d, cos, sin, int(layout), int(bool(single)), out[i])
+        _lib.ssd_oracle_rope(rows[i], d, cos, sin, int(layout), out[i])
     return out.reshape(x.shape)
 
 

@@ -252,29 +252,17 @@ void ssd_oracle_cfg_mix(const float *p, int n_prompts, int V, double gamma, floa
  * rotated in its plane,
  *     a' = a cos_i - b sin_i,   b' = b cos_i + a sin_i.
  * layout 1: pair i is (x[i], x[i + d/2]); layout 2: pair i is (x[2i], x[2i+1]).
- *
- * single == 0: the definition, in double.
- * single != 0: the same two expressions in float, each as one product and
- *   one fused multiply-add (t = b*sin; a' = fma(a, cos, -t)), the precision
- *   and order the GPU kernel states for itself.  Used where the result is
- *   rounded to bfloat16 next: that rounding is a quantisation, and both sides
- *   must take it from the same float.  A test pins this form to the double one.
+ * Computed in double, returned as float.
  */
-void ssd_oracle_rope(const float *x, int d, const float *cosv, const float *sinv, int layout, int single, float *out)
+void ssd_oracle_rope(const float *x, int d, const float *cosv, const float *sinv, int layout, float *out)
 {
     int i;
     for (i = 0; i < d / 2; ++i) {
         const int ia = layout == 1 ? i : 2 * i;
         const int ib = layout == 1 ? i + d / 2 : 2 * i + 1;
-        if (single) {
-            const float ta = x[ib] * sinv[i], tb = x[ia] * sinv[i];
-            out[ia] = fmaf(x[ia], cosv[i], -ta);
-            out[ib] = fmaf(x[ib], cosv[i], tb);
-        } else {
-            const double a = x[ia], b = x[ib], c = cosv[i], s = sinv[i];
-            out[ia] = (float)(a * c - b * s);
-            out[ib] = (float)(b * c + a * s);
-        }
+        const double a = x[ia], b = x[ib], c = cosv[i], s = sinv[i];
+        out[ia] = (float)(a * c - b * s);
+        out[ib] = (float)(b * c + a * s);
     }
 }
 

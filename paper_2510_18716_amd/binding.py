@@ -1,4 +1,4 @@
-"""ctypes binding of include/ssd.h.  Same names, same argument order; tensors are passed as
+"""ctypes binding of include/ssd.h and include/ssd_hooks.h.  Same names, same argument order; tensors are passed as
 `data_ptr()` and the stream as the raw hipStream_t of torch's current stream."""
 from __future__ import annotations
 
@@ -100,10 +100,13 @@ lib.ssd_last_error.argtypes = []
 lib.ssd_last_error.restype = C.c_char_p
 lib.ssd_version.argtypes = []
 lib.ssd_version.restype = C.c_int
-lib.ssd_tune_attend.argtypes = [C.c_int] * 3
-lib.ssd_tune_attend.restype = C.c_int
-lib.ssd_tune_dense.argtypes = [C.c_int]
-lib.ssd_tune_dense.restype = C.c_int
+lib.ssd_cache_set_launch_shape.argtypes = [_vp, C.c_int, C.c_int, C.c_int]
+lib.ssd_cache_set_launch_shape.restype = C.c_int
+lib.ssd_dense_decode_attn_splits.argtypes = [_vp, _vp, _vp, _vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                             C.c_float, _vp, _vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, C.c_size_t, _vp]
+lib.ssd_dense_decode_attn_splits.restype = C.c_int
+lib.ssd_decode_step_split.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp, _vp, C.c_int, C.c_int, C.POINTER(_vp), C.c_int, C.c_int]
+lib.ssd_decode_step_split.restype = C.c_int
 
 
 class SsdError(RuntimeError):
@@ -248,6 +251,10 @@ class Cache:
     def reset(self):
         _check(lib.ssd_cache_reset(self._h), "ssd_cache_reset")
 
+    def set_launch_shape(self, ch: int = 0, wpb: int = 0, new_rows: int = 0):
+        """Test / sweep hook: override the attention launch shape of this cache ((0, 0, 0) = the library's choice)."""
+        _check(lib.ssd_cache_set_launch_shape(self._h, ch, wpb, new_rows), "ssd_cache_set_launch_shape")
+
     def layer_state(self, layer: int):
         out = (C.c_int32 * 4)()
         _check(lib.ssd_cache_layer_state(self._h, layer, C.byref(out)), "ssd_cache_layer_state")
@@ -313,6 +320,24 @@ def ssd_decode_step(cache: Cache, layer_begin: int, layer_end: int, q, k_new, v_
                                int(bool(accumulate_scores)), int(bool(compress)), _stream(stream)), "ssd_decode_step")
 
 
+SSD_MAX_SPLIT = 4
+SSD_SPLIT_FORK, SSD_SPLIT_JOIN = 1, 2
+
+
+def stream_array(streams):
+    """ctypes array of raw hipStream_t for ssd_decode_step_split (torch streams or raw handles)."""
+    raw = [(s if isinstance(s, int) else s.cuda_stream) for s in streams]
+    return (_vp * len(raw))(*raw)
+
+
+def ssd_decode_step_split(cache: Cache, layer_begin: int, layer_end: int, q, k_new, v_new, out, streams, sync: int = 0,
+                          accumulate_scores: bool = True, compress: bool = True) -> None:
+    arr = streams if isinstance(streams, C.Array) else stream_array(streams)
+    _check(lib.ssd_decode_step_split(cache.handle, layer_begin, layer_end, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                     int(bool(accumulate_scores)), int(bool(compress)), arr, len(arr), int(sync)),
+           "ssd_decode_step_split")
+
+
 SSD_ROPE_HALF, SSD_ROPE_INTERLEAVED = 1, 2
 
 
@@ -349,8 +374,15 @@ def ssd_dense_workspace_bytes(B: int, H: int, d: int, n: int) -> int:
 
 def ssd_dense_decode_attn(q, K, V, out, B: int, H: int, d: int, dtype, n_cap: int, n: int, softmax_scale: float = 0.0,
                           far=None, tot=None, mass_stride: int = 1, vis_start: int = 0, w: int = 32, workspace=None,
-                          stream=None) -> None:
+                          stream=None, splits: Optional[int] = None) -> None:
+    """splits=None: ssd_dense_decode_attn; an integer: the test hook ssd_dense_decode_attn_splits with that many row splits."""
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib.ssd_dense_decode_attn(_ptr(q), _ptr(K), _ptr(V), _ptr(out), B, H, d, _dtype_code(dtype), n_cap, n,
-                                     float(softmax_scale), _ptr(far), _ptr(tot), mass_stride, vis_start, w,
-                                     _ptr(workspace), ws_bytes, _stream(stream)), "ssd_dense_decode_attn")
+    if splits is None:
+        _check(lib.ssd_dense_decode_attn(_ptr(q), _ptr(K), _ptr(V), _ptr(out), B, H, d, _dtype_code(dtype), n_cap, n,
+                                         float(softmax_scale), _ptr(far), _ptr(tot), mass_stride, vis_start, w,
+                                         _ptr(workspace), ws_bytes, _stream(stream)), "ssd_dense_decode_attn")
+    else:
+        _check(lib.ssd_dense_decode_attn_splits(_ptr(q), _ptr(K), _ptr(V), _ptr(out), B, H, d, _dtype_code(dtype), n_cap, n,
+                                                float(softmax_scale), _ptr(far), _ptr(tot), mass_stride, vis_start, w,
+                                                int(splits), _ptr(workspace), ws_bytes, _stream(stream)),
+               "ssd_dense_decode_attn_splits")

@@ -156,6 +156,22 @@ int check_layers(const ssd_cache *c, int lb, int le) {
     return SSD_OK;
 }
 
+int ensure_events(ssd_cache *c) {
+    if (c->have_events) return SSD_OK;
+    hipError_t e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
+    if (e != hipSuccess) return hip_fail(e, "event creation");
+    for (int i = 1; i < SSD_MAX_SPLIT; ++i) {
+        e = hipEventCreateWithFlags(&c->ev_join[i], hipEventDisableTiming);
+        if (e != hipSuccess) {
+            (void)hipEventDestroy(c->ev_fork);
+            for (int j = 1; j < i; ++j) (void)hipEventDestroy(c->ev_join[j]);
+            return hip_fail(e, "event creation");
+        }
+    }
+    c->have_events = true;
+    return SSD_OK;
+}
+
 Geom make_geom(const ssd_cache *c, int l) {
     Geom g;
     g.base = c->dev;
@@ -367,12 +383,20 @@ int ssd_cache_init_layered(const ssd_config *cfg, const uint8_t *head_type, cons
     c->dev = static_cast<char *>(dev_mem);
     c->bytes = bytes;
     c->launch_enabled = true;
+    c->shape = LaunchShape{0, 0, 0};
+    c->have_events = false;
     c->st.assign(cfg->n_layers, LayerState{0, 0, 0, 0, 0});
     *out = c;
     return SSD_OK;
 }
 
-void ssd_cache_free(ssd_cache *cache) { delete cache; }
+void ssd_cache_free(ssd_cache *cache) {
+    if (cache && cache->have_events) {
+        (void)hipEventDestroy(cache->ev_fork);
+        for (int i = 1; i < SSD_MAX_SPLIT; ++i) (void)hipEventDestroy(cache->ev_join[i]);
+    }
+    delete cache;
+}
 
 int ssd_cache_reset(ssd_cache *cache) {
     clear_error();

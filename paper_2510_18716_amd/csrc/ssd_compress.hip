@@ -15,6 +15,8 @@ struct CompressArgs {
     int R;
     int lpr;           // 16-byte fragments per row
     int heads;         // budgets per head
+    int seq_off;       // the launch covers sequences [seq_off, seq_off + n_seq)
+    int n_seq;
     HeadTable ht;
 };
 
@@ -22,11 +24,11 @@ struct CompressArgs {
 template <int THREADS>
 __global__ __launch_bounds__(THREADS) void compress_inplace_kernel(CompressArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
-    const int BH = a.g.B * a.g.H;
+    const int BH = a.n_seq * a.g.H;
     const int unit = blockIdx.x;
     const int lrel = unit / BH;
     const int rem = unit % BH;
-    const UnitRef u = unit_ref(a.g, a.lm.layer[lrel], rem / a.g.H, rem % a.g.H);
+    const UnitRef u = unit_ref(a.g, a.lm.layer[lrel], a.seq_off + rem / a.g.H, rem % a.g.H);
     if (!u.sem) return;                       // uniform for the whole workgroup
     const int Mh = a.heads ? a.ht.v[rem % a.g.H] : a.g.M;     // this head's budget
     const int m = a.m < Mh ? a.m : Mh;        // heavy slots this head has in use
@@ -145,8 +147,9 @@ __global__ __launch_bounds__(THREADS) void compress_dense_kernel(DenseSrcArgs a)
     }
 }
 
-// In-place compression of layers [lb, le), which all hold the state `st` (st.c - R > 0).
-int launch_compress_inplace(const ssd_cache *cache, int lb, int le, const LayerState &st, hipStream_t s) {
+// In-place compression of sequences [seq_off, seq_off + n_seq) of layers [lb, le), which all hold the state `st`
+// (st.c - R > 0).
+int launch_compress_inplace(const ssd_cache *cache, int lb, int le, const LayerState &st, int seq_off, int n_seq, hipStream_t s) {
     const ssd_config &cf = cache->cfg;
     const int n_old = st.c - cf.recent;
     CompressArgs a;
@@ -158,9 +161,11 @@ int launch_compress_inplace(const ssd_cache *cache, int lb, int le, const LayerS
     a.R = cf.recent;
     a.lpr = cf.head_dim * cache->esize / 16;
     a.heads = heads_differ(cache, lb) ? 1 : 0;
+    a.seq_off = seq_off;
+    a.n_seq = n_seq;
     fill_head_table(cache, lb, &a.ht);
     const int n_cand = st.m + n_old;
-    const unsigned units = (unsigned)((le - lb) * cf.n_seqs * cf.n_heads);
+    const unsigned units = (unsigned)((le - lb) * n_seq * cf.n_heads);
     const size_t lds = select_lds_bytes(cache->Ml[lb], n_cand, n_old);
     if (n_cand <= 192)
         hipLaunchKernelGGL((compress_inplace_kernel<64>), dim3(units), dim3(64), lds, s, a);
@@ -232,7 +237,7 @@ extern "C" int ssd_compress_kv(ssd_cache *cache, int layer_begin, int layer_end,
         // kernels run only where semantic heads have candidates; the counters (and the spatial window of
         // Algorithm 2) move in every layer of the range
         if (n_old > 0 && cache->ldesc[lb].n_se > 0 && cache->launch_enabled) {
-            rc = launch_compress_inplace(cache, lb, le, st, s);
+            rc = launch_compress_inplace(cache, lb, le, st, 0, cf.n_seqs, s);
             if (rc != SSD_OK) return rc;
         }
         for (int l = lb; l < le; ++l) apply_compress_counters(cache, l);

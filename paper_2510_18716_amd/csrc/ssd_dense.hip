@@ -54,7 +54,7 @@ __global__ __launch_bounds__(WPB * 64) void dense_kernel(DenseArgs a) {
     Softmax<VEC> sm;
     sm.init();
     if (r_begin < r_end)
-        stream_rows<T, D, CH, false, true, true, NoHook, false>(Kb, Vb, a.row_bytes, sg, r_begin, r_end, 0, 1, q, a.qscale, sm, nullptr, a.vis_start, a.far_last);
+        stream_rows<T, D, CH, false, true, NoHook, false>(Kb, Vb, a.row_bytes, sg, r_begin, r_end, 0, 1, q, a.qscale, sm, nullptr, a.vis_start, a.far_last);
     merge_groups<VEC, LPR, true>(sm);
     if (a.splits == 1) {
         const float inv_l = sm.l > 0.f ? 1.0f / sm.l : 0.f;
@@ -103,10 +103,7 @@ __global__ __launch_bounds__(D) void dense_merge_kernel(DenseArgs a) {
     }
 }
 
-static int g_dense_splits = 0;    // 0 = choose from the shape
-
 static int pick_splits(int units, int n) {
-    if (g_dense_splits > 0) return g_dense_splits;
     // aim for >= 8192 waves (8 per SIMD on 256 CUs) but keep at least 128 rows per wave
     int s = (8192 + units - 1) / units;
     const int max_s = n / 128 > 1 ? n / 128 : 1;
@@ -134,21 +131,10 @@ static hipError_t launch_dense(const DenseArgs &a, hipStream_t s) {
 
 using namespace ssd;
 
-extern "C" int ssd_tune_dense(int splits) {
-    if (splits < 0 || splits > 64) return SSD_ERR_INVALID_ARG;
-    g_dense_splits = splits;
-    return SSD_OK;
-}
-
-extern "C" size_t ssd_dense_workspace_bytes(int B, int H, int d, int n) {
-    if (B < 1 || H < 1 || d < 1 || n < 1) return 0;
-    // room for the largest split count the library ever picks
-    return (size_t)B * H * 64 * (size_t)(4 + d) * sizeof(float);
-}
-
-extern "C" int ssd_dense_decode_attn(const void *q, const void *K, const void *V, void *out, int B, int H, int d, int dtype,
-                                     int n_cap, int n, float softmax_scale, float *far, float *tot, int mass_stride,
-                                     int vis_start, int w, void *workspace, size_t workspace_bytes, void *stream) {
+// splits == 0: chosen from the shape
+static int dense_run(const void *q, const void *K, const void *V, void *out, int B, int H, int d, int dtype, int n_cap, int n,
+                     float softmax_scale, float *far, float *tot, int mass_stride, int vis_start, int w, int splits,
+                     void *workspace, size_t workspace_bytes, void *stream) {
     clear_error();
     if (!q || !K || !V || !out) return fail(SSD_ERR_INVALID_ARG, "q, K, V or out is NULL");
     if (!aligned(q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 16)) return fail(SSD_ERR_INVALID_ARG, "q, K, V, out must be 16-byte aligned");
@@ -159,6 +145,7 @@ extern "C" int ssd_dense_decode_attn(const void *q, const void *K, const void *V
     if ((far == nullptr) != (tot == nullptr)) return fail(SSD_ERR_INVALID_ARG, "far and tot must both be given or both be NULL");
     if (far && (mass_stride < 1 || vis_start < 0 || w < 0)) return fail(SSD_ERR_INVALID_ARG, "bad mass_stride, vis_start or w");
     if (!(softmax_scale >= 0.f)) return fail(SSD_ERR_INVALID_ARG, "softmax_scale must be >= 0");
+    if (splits < 0 || splits > 64) return fail(SSD_ERR_INVALID_ARG, "splits=%d outside 0..64", splits);
     DenseArgs a;
     a.q = static_cast<const char *>(q);
     a.K = static_cast<const char *>(K);
@@ -170,7 +157,7 @@ extern "C" int ssd_dense_decode_attn(const void *q, const void *K, const void *V
     a.n_cap = n_cap;
     a.n = n;
     a.row_bytes = d * (dtype == SSD_F32 ? 4 : 2);
-    a.splits = pick_splits(a.n_units, n);
+    a.splits = splits > 0 ? splits : pick_splits(a.n_units, n);
     a.rows_per_split = (n + a.splits - 1) / a.splits;
     a.mass_stride = mass_stride;
     a.vis_start = far ? vis_start : 0;
@@ -188,4 +175,25 @@ extern "C" int ssd_dense_decode_attn(const void *q, const void *K, const void *V
     else e = d == 128 ? launch_dense<float, 128>(a, s) : launch_dense<float, 64>(a, s);
     if (e != hipSuccess) return hip_fail(e, "dense attention launch");
     return SSD_OK;
+}
+
+extern "C" size_t ssd_dense_workspace_bytes(int B, int H, int d, int n) {
+    if (B < 1 || H < 1 || d < 1 || n < 1) return 0;
+    // room for the largest split count the library ever picks
+    return (size_t)B * H * 64 * (size_t)(4 + d) * sizeof(float);
+}
+
+extern "C" int ssd_dense_decode_attn(const void *q, const void *K, const void *V, void *out, int B, int H, int d, int dtype,
+                                     int n_cap, int n, float softmax_scale, float *far, float *tot, int mass_stride,
+                                     int vis_start, int w, void *workspace, size_t workspace_bytes, void *stream) {
+    return dense_run(q, K, V, out, B, H, d, dtype, n_cap, n, softmax_scale, far, tot, mass_stride, vis_start, w, 0,
+                     workspace, workspace_bytes, stream);
+}
+
+extern "C" int ssd_dense_decode_attn_splits(const void *q, const void *K, const void *V, void *out, int B, int H, int d, int dtype,
+                                            int n_cap, int n, float softmax_scale, float *far, float *tot, int mass_stride,
+                                            int vis_start, int w, int splits, void *workspace, size_t workspace_bytes,
+                                            void *stream) {
+    return dense_run(q, K, V, out, B, H, d, dtype, n_cap, n, softmax_scale, far, tot, mass_stride, vis_start, w, splits,
+                     workspace, workspace_bytes, stream);
 }

@@ -204,13 +204,13 @@ struct NoHook { __device__ __forceinline__ void operator()() const {} };
 // PAD: every chunk issues its full 2 * CH loads and consumes them all (see `load` and `compute`); this is what
 // launches of few rounds want.  Without it loads and arithmetic past the end are skipped, which is slightly
 // better when many rounds of waves hide each other's waits anyway (the full-cache kernel).
-template <typename T, int D, int CH, bool ZBUF, bool MASS, bool PF = true, typename Hook = NoHook, bool PAD = true>
+template <typename T, int D, int CH, bool ZBUF, bool MASS, typename Hook = NoHook, bool PAD = true>
 static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, const char *__restrict__ Vb,
                                                   int row_bytes, const Segs &sg, int row_begin, int row_end,
                                                   int first_iter, int iter_stride,
                                                   const typename Elem<T>::Q &q, float qscale,
                                                   Softmax<Elem<T>::VEC> &sm, float *zbuf, int vis_start, int far_last,
-                                                  int g_probe = 0, Hook after_first_issue = Hook()) {
+                                                  Hook after_first_issue = Hook()) {
     constexpr int VEC = Elem<T>::VEC;
     constexpr int LPR = D / VEC;
     constexpr int RPW = 64 / LPR;
@@ -236,14 +236,6 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
         }
     };
     auto compute = [&](int it0, const uint4 (&kr)[CH], const uint4 (&vr)[CH]) {
-#ifdef SSD_PROBE
-        if (g_probe == 1 || g_probe == 11) {      // probe: loads only, trivial arithmetic
-#pragma unroll
-            for (int i = 0; i < CH; ++i) sm.acc[0] += __uint_as_float(kr[i].x ^ kr[i].y ^ kr[i].z ^ kr[i].w ^ vr[i].x ^ vr[i].y ^ vr[i].z ^ vr[i].w);
-            sm.l = 1.f;
-            return;
-        }
-#endif
         float z[CH];
         float mx = NEG_BIG;
 #pragma unroll
@@ -287,17 +279,6 @@ static __device__ __forceinline__ void stream_rows(const char *__restrict__ Kb, 
 
     int it = first_iter;
     if (it >= n_iter) { after_first_issue(); return; }
-    if (!PF) {                  // one buffer: issue a chunk, wait, compute
-        uint4 k1[CH], v1[CH];
-#pragma unroll
-        for (int i = 0; i < CH; ++i) { k1[i] = v1[i] = make_uint4(0, 0, 0, 0); }
-        for (bool first = true; it < n_iter; it += chunk_iters, first = false) {
-            load(it, k1, v1);
-            if (first) after_first_issue();
-            compute(it, k1, v1);
-        }
-        return;
-    }
     uint4 ka[CH], va[CH], kb[CH], vb[CH];
 #pragma unroll
     for (int i = 0; i < CH; ++i) { ka[i] = va[i] = kb[i] = vb[i] = make_uint4(0, 0, 0, 0); }

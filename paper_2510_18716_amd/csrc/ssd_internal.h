@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "ssd.h"
+#include "ssd_hooks.h"
 
 namespace ssd {
 
@@ -110,6 +111,13 @@ __host__ __device__ inline Segs ring_segs_fused(int S, int W, int C, bool row_bu
     return s;
 }
 
+// Override of the attention / step launch shape, kept per cache (0 = the library's choice by launch size).
+struct LaunchShape {
+    int ch;        // wave-wide loads of K (and of V) per chunk: 1, 2, 4
+    int wpb;       // units per workgroup: 1, 2, 4; 12 / 14: one unit per workgroup shared by 2 / 4 waves
+    int new_rows;  // fused step: 1 = store the new token's rows at the start of the row stream, 2 = after it
+};
+
 }  // namespace ssd
 
 struct ssd_cache {
@@ -126,6 +134,9 @@ struct ssd_cache {
     char *dev;
     size_t bytes;
     bool launch_enabled;
+    ssd::LaunchShape shape;                   // test / sweep override of the attention launch shape (all 0: chosen by launch size)
+    hipEvent_t ev_fork, ev_join[SSD_MAX_SPLIT];   // ssd_decode_step_split: made on first use, timing disabled
+    bool have_events;
 };
 
 namespace ssd {
@@ -137,6 +148,7 @@ void clear_error();
 
 // host helpers implemented in ssd_cache.hip
 int check_layers(const ssd_cache *c, int lb, int le);
+int ensure_events(ssd_cache *c);                                               // events of ssd_decode_step_split
 Geom make_geom(const ssd_cache *c, int l);                                     // geometry of layer l
 void fill_launch_meta(const ssd_cache *c, int lb, int le, LaunchMeta *out);   // le - lb <= LMAX
 Segs spatial_segs(const ssd_cache *c, int l, const LayerState &st);
@@ -163,7 +175,7 @@ int same_state_run(const ssd_cache *c, int lb, int le);
 int same_geom_run(const ssd_cache *c, int lb, int le);
 
 // implemented in ssd_compress.hip
-int launch_compress_inplace(const ssd_cache *cache, int lb, int le, const LayerState &st, hipStream_t s);
+int launch_compress_inplace(const ssd_cache *cache, int lb, int le, const LayerState &st, int seq_off, int n_seq, hipStream_t s);
 
 static inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 

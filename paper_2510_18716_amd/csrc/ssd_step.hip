@@ -17,18 +17,6 @@
 // arguments; heads dispatched longest first), ROPE (the fused step rotates q and the new k by the token's
 // position on the way in) and SPLIT (several waves share a unit: for launches of few, long units).  The plain
 // kernel pays for none of them.
-//
-// Measurement probes.  A build with -DSSD_PROBE keeps variants of the kernel that leave work out, selected
-// by the third argument of ssd_tune_attend (decimal fields; 0 = the real kernel):
-//   p % 100         1 or 11: loads only, no arithmetic; 2, 3, >= 10: no K/V stream at all
-//   p % 10          3..6: return before the output store / after it / after the score update / after the
-//                   selection (what each part of the tail costs)
-//   (p / 100) % 100 bit set of store classes to skip: 1 new token's rows, 2 output, 4 scores and positions,
-//                   8 promoted row; 16 = write all stores through at system scope
-//   p / 10000 % 100 pad the workgroup's LDS to that many KB (caps the workgroups per CU)
-//   p / 1000000     1 / 2: force the new token's rows to be stored at the start / after the end of the
-//                   stream (this field also works in ordinary builds)
-// The results of these variants are wrong on purpose; only their timings are used.
 #include <algorithm>
 
 #include "ssd_select.h"
@@ -52,8 +40,8 @@ struct StepHot {
     int lpr;
     int zcap;            // floats of LDS per wave for the logits of a semantic unit
     int wave_lds;        // bytes of LDS per wave (logits + selection scratch)
-    int probe;           // SSD_PROBE builds only
     int sem_first;       // semantic units have more rows than spatial ones: dispatch them first
+    int seq_off;         // first sequence of this launch (a launch may cover a part of the batch only)
     int late_new_store;  // fused append: store the new token's rows after the stream instead of at its start
     int n_att, nc;       // budgets per head: tokens the attention sees, tokens held at the last compression,
     int row_buffer;      //   and whether spatial heads use the row buffer (a spatial unit derives its own rows)
@@ -119,7 +107,7 @@ static __device__ __forceinline__ void fetch_args(int lrel, StepHot &a, LayerDes
     SSD_P(q, const char *); SSD_P(out, char *); SSD_P(k_new, const char *); SSD_P(v_new, const char *);
     a.qscale = __uint_as_float(SSD_W(offsetof(StepHot, qscale)));
     SSD_I(layer_off); SSD_I(new_slot_sp); SSD_I(new_slot_se); SSD_I(new_pos); SSD_I(accumulate); SSD_I(do_compress);
-    SSD_I(m); SSD_I(c); SSD_I(base); SSD_I(R); SSD_I(lpr); SSD_I(zcap); SSD_I(wave_lds); SSD_I(probe); SSD_I(sem_first);
+    SSD_I(m); SSD_I(c); SSD_I(base); SSD_I(R); SSD_I(lpr); SSD_I(zcap); SSD_I(wave_lds); SSD_I(sem_first); SSD_I(seq_off);
     SSD_I(late_new_store); SSD_I(n_att); SSD_I(nc); SSD_I(row_buffer); SSD_I(rope_layout);
     SSD_P(rope_cos, const float *); SSD_P(rope_sin, const float *);
     SSD_I(sp.start[0]); SSD_I(sp.start[1]); SSD_I(sp.start[2]); SSD_I(sp.len[0]); SSD_I(sp.len[1]); SSD_I(sp.len[2]); SSD_I(sp.total);
@@ -200,16 +188,6 @@ static __device__ __forceinline__ uint4 rope_fragment(const uint4 &raw, const fl
 
 // One wave per unit, WPB units (consecutive heads of one sequence and layer) per workgroup;
 // grid = (ceil(H / WPB), B, layers of the launch).  Nothing below needs a workgroup barrier.
-#ifdef SSD_PROBE      // (probe / 100) & bit: the kernel with that class of stores left out (what the write path costs)
-#define SSD_ST16(bit, ptr, val) do { if (!((a.probe / 100 % 100) & (bit))) { if ((a.probe / 100 % 100) & 16) { const uint4 _v = (val); asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" :: "v"((char *)(ptr)), "v"(__builtin_bit_cast(u32x4_t, _v)) : "memory"); } else *reinterpret_cast<uint4 *>(ptr) = (val); } } while (0)
-#define SSD_ST4(bit, ptr, val) do { if (!((a.probe / 100 % 100) & (bit))) { if ((a.probe / 100 % 100) & 16) asm volatile("global_store_dword %0, %1, off sc0 sc1" :: "v"(ptr), "v"(val) : "memory"); else *(ptr) = (val); } } while (0)
-#else
-#define SSD_ST16(bit, ptr, val) (*reinterpret_cast<uint4 *>(ptr) = (val))
-#define SSD_ST4(bit, ptr, val) (*(ptr) = (val))
-#endif
-// store classes: 1 = new token's rows, 2 = output, 4 = running scores and positions, 8 = promoted row;
-// 16 = all stores written through (system scope) instead of left dirty in L2
-
 // HEADS: budgets per head.  The launch covers one layer; a unit takes its head's W_h or M_h from the table
 // in the arguments and derives its own rows and slots from it (the host's are those of the largest head).
 // ROPE: q and the new token's k are rotated by the position's angles on the way in (the rotated k is what the
@@ -217,7 +195,7 @@ static __device__ __forceinline__ uint4 rope_fragment(const uint4 &raw, const fl
 // SPLIT > 1 (with WPB = 1): SPLIT waves share one unit, taking every SPLIT-th wave-load of its rows, and meet
 // once in LDS; wave 0 carries on alone.  For launches of few, long units, which would leave most of the chip's
 // wave slots empty.
-template <typename T, int D, int CH, int WPB, bool FUSED, bool PF = true, bool HEADS = false, bool ROPE = false, int SPLIT = 1>
+template <typename T, int D, int CH, int WPB, bool FUSED, bool HEADS = false, bool ROPE = false, int SPLIT = 1>
 __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {      // read through fetch_args
     constexpr int VEC = Elem<T>::VEC;
     constexpr int LPR = D / VEC;
@@ -249,7 +227,7 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
         const int rank = (blockIdx.z * RANK_GROUPS + blockIdx.x) * WPB + w;
         if (rank >= a.g.H) return;
         fetch_head_order(rank, h, hb);
-        seq = blockIdx.y;
+        seq = a.seq_off + blockIdx.y;
         const uint64_t word = h < 64 ? ld.sem_mask[0] : ld.sem_mask[1];
         const uint64_t below = (1ull << (h & 63)) - 1ull;
         sem_unit = ((word >> (h & 63)) & 1ull) != 0;
@@ -262,7 +240,7 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
         const uint64_t m0 = sem_unit ? ld.sem_mask[0] : ~ld.sem_mask[0];
         const uint64_t m1 = sem_unit ? ld.sem_mask[1] : ~ld.sem_mask[1];
         h = kth_set_bit(m0, m1, local);                   // spatial heads: bits above H are never reached (local < n_sp)
-        seq = blockIdx.y;
+        seq = a.seq_off + blockIdx.y;
     }
     const int rem = seq * a.g.H + h;
     const UnitRef u = unit_ref_local(a.g, ld, seq, sem_unit, local);
@@ -324,8 +302,8 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
         if (FUSED && lane < LPR && part == 0) {
             const int slot = u.sem ? a.new_slot_se : a.new_slot_sp;
             const size_t off = (size_t)slot * (size_t)a.g.row_bytes + (size_t)sub * 16u;
-            SSD_ST16(1, u.K + off, new_k);
-            SSD_ST16(1, u.V + off, new_v);
+            *reinterpret_cast<uint4 *>(u.K + off) = new_k;
+            *reinterpret_cast<uint4 *>(u.V + off) = new_v;
         }
     };
     auto after_first_issue = [&]() {
@@ -347,13 +325,10 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
             }
         }
     };
-#ifdef SSD_PROBE
-    if (a.probe % 100 == 2 || a.probe % 100 == 3 || a.probe % 100 >= 10) { sm.l = 1.f; after_first_issue(); } else
-#endif
     if (want_z)
-        stream_rows<T, D, CH, true, false, PF>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, part, SPLIT, q, a.qscale, sm, zbuf, 0, 0, a.probe, after_first_issue);
+        stream_rows<T, D, CH, true, false>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, part, SPLIT, q, a.qscale, sm, zbuf, 0, 0, after_first_issue);
     else
-        stream_rows<T, D, CH, false, false, PF>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, part, SPLIT, q, a.qscale, sm, nullptr, 0, 0, a.probe, after_first_issue);
+        stream_rows<T, D, CH, false, false>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, part, SPLIT, q, a.qscale, sm, nullptr, 0, 0, after_first_issue);
     if (FUSED && part == 0) {
         // The new token, from the registers it was loaded into, is folded into lane group 0's softmax as
         // one more row (index sg.total).
@@ -402,14 +377,11 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
     }
     const float m_all = sm.m;
     const float inv_l = sm.l > 0.f ? 1.0f / sm.l : 0.f;
-#ifdef SSD_PROBE
-    if (a.probe % 10 == 3) return;
-#endif
     if (lane < LPR) {
         float o[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) o[e] = sm.acc[e] * inv_l;
-        SSD_ST16(2, a.out + qoff, Elem<T>::pack(o));
+        *reinterpret_cast<uint4 *>(a.out + qoff) = Elem<T>::pack(o);
     }
     // Fused append, the new token's rows.  Stores and loads share one in-order counter per wave, and a store is
     // acknowledged much later than a load returns: issued at the start of the stream, these two stores keep
@@ -420,9 +392,6 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
     if (a.late_new_store) store_new();
 
     if (!tail) return;
-#ifdef SSD_PROBE
-    if (a.probe % 10 == 4) return;
-#endif
     lds_sync();                                           // the logits written by the group leaders
     const int M = t_M, C = t_C;
     const int n_old = t_c - t_R;                          // buffered tokens that become candidates
@@ -440,8 +409,8 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
         const int slot = is_new ? t_new_slot_se : seg_slot(sg, r);
         const float p = t_accumulate ? fast_exp2(zbuf[r] - m_all) * inv_l : 0.f;
         const float s = (is_new ? 0.f : s_old) + p;
-        if (t_accumulate || is_new) SSD_ST4(4, &u.score[slot], s);
-        if (is_new) SSD_ST4(4, &u.pos[slot], t_new_pos);
+        if (t_accumulate || is_new) u.score[slot] = s;
+        if (is_new) u.pos[slot] = t_new_pos;
         unsigned long long key = ~0ull;
         if (compress && r < n_cand) {
             key = make_key(s, is_new ? t_new_pos : pos_old);
@@ -462,9 +431,6 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
         score_row(r, is_new ? 0.f : u.score[slot], (is_new || !compress) ? 0 : u.pos[slot]);
     }
     if (!compress) return;
-#ifdef SSD_PROBE
-    if (a.probe % 10 == 5) return;
-#endif
     if (general) {
         lds_sync();
         select_and_move<64, true>(a.g, u, sel, n_cand, t_m, n_old, t_base, t_lpr, lane, t_Mh);
@@ -479,9 +445,6 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
         const unsigned long long hit1 = __ballot(my_key[1] == min_key);
         e_idx = hit0 ? __builtin_ctzll(hit0) : 64 + __builtin_ctzll(hit1);
     }
-#ifdef SSD_PROBE
-    if (a.probe % 10 == 6) return;
-#endif
     const bool ev_heavy = e_idx >= 0 && e_idx < t_m;
     const bool ev_staged = e_idx >= t_m;
     const int n_move = n_old - (ev_staged ? 1 : 0);
@@ -498,7 +461,7 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
         char *plane = kv ? u.V : u.K;
         const int from = M + (t_base + (src_idx(k) - t_m)) % C;
         const uint4 v = *reinterpret_cast<const uint4 *>(plane + (size_t)from * t_row_bytes + (size_t)fs * 16u);
-        SSD_ST16(8, plane + (size_t)dst_slot(k) * t_row_bytes + (size_t)fs * 16u, v);
+        *reinterpret_cast<uint4 *>(plane + (size_t)dst_slot(k) * t_row_bytes + (size_t)fs * 16u) = v;
     }
     // position and score travel with the token: its key sits in the registers of lane (index mod 64)
     for (int k0 = 0; k0 < n_move; k0 += 64) {             // wave-uniform trip count: the shuffles need every lane
@@ -513,15 +476,6 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
         }
     }
 }
-
-struct Tuning {
-    int ch;      // wave-wide loads of K (and of V) per chunk; two chunks are in flight per wave (0 = by launch size)
-    int wpb;     // units (waves) per workgroup (0 = by launch size)
-};
-
-static int g_probe = 0;
-static constexpr Tuning DEFAULT_TUNE = {0, 0};
-static Tuning g_tune = DEFAULT_TUNE;
 
 // Largest candidate count the fused entry point ranks with a single wave; beyond it the stand-alone
 // compression kernel (a whole workgroup per head) runs after the attention.
@@ -552,29 +506,31 @@ static void fill_head_order(const ssd_cache *c, int l, const LayerState &before,
 
 template <typename T, int D, int CH, int SPLIT>
 static void launch_split(const StepArgs &full, dim3 blocks, size_t lds, bool fused, hipStream_t s) {
-    if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, 1, true, true, false, false, SPLIT>), blocks, dim3(SPLIT * 64), lds, s, full);
-    else hipLaunchKernelGGL((step_kernel<T, D, CH, 1, false, true, false, false, SPLIT>), blocks, dim3(SPLIT * 64), lds, s, full);
+    if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, 1, true, false, false, SPLIT>), blocks, dim3(SPLIT * 64), lds, s, full);
+    else hipLaunchKernelGGL((step_kernel<T, D, CH, 1, false, false, false, SPLIT>), blocks, dim3(SPLIT * 64), lds, s, full);
 }
 
-template <typename T, int D, int CH, int WPB, bool PF = true>
+template <typename T, int D, int CH, int WPB>
 static void launch_one(const StepArgs &full, dim3 blocks, size_t lds, bool fused, bool heads, hipStream_t s) {
     const bool rope = full.h.rope_layout != 0;            // fused launches only (checked by the entry point)
     if (heads || rope) {
         // budgets per head, rotary embedding: one variant (four wave-loads per chunk) per workgroup size
-        if constexpr (PF && CH == 4) {
-            if (rope && heads) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, true, true, true>), blocks, dim3(WPB * 64), lds, s, full);
-            else if (rope) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, true, false, true>), blocks, dim3(WPB * 64), lds, s, full);
-            else if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, true, true>), blocks, dim3(WPB * 64), lds, s, full);
-            else hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, false, true, true>), blocks, dim3(WPB * 64), lds, s, full);
+        if constexpr (CH == 4) {
+            if (rope && heads) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, true, true>), blocks, dim3(WPB * 64), lds, s, full);
+            else if (rope) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, false, true>), blocks, dim3(WPB * 64), lds, s, full);
+            else if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, true>), blocks, dim3(WPB * 64), lds, s, full);
+            else hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, false, true>), blocks, dim3(WPB * 64), lds, s, full);
         }
         return;
     }
-    if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true, PF>), blocks, dim3(WPB * 64), lds, s, full);
-    else hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, false, PF>), blocks, dim3(WPB * 64), lds, s, full);
+    if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, true>), blocks, dim3(WPB * 64), lds, s, full);
+    else hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, false>), blocks, dim3(WPB * 64), lds, s, full);
 }
 
+// One launch over sequences [a.seq_off, a.seq_off + B) of the layers in `full`.
 template <typename T, int D>
-static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, int layers, bool fused, bool heads, int M, hipStream_t s) {
+static hipError_t launch_step(StepArgs &full, const LaunchShape &shape, int H, int max_type_heads, int B, int layers, bool fused,
+                              bool heads, int M, hipStream_t s) {
     StepHot &a = full.h;
     const int n_old = a.c - a.R, n_cand = a.m + n_old;
     // Launch shape by the number of units (measured on the 7B- and 1B-shaped workloads).  Up to half of
@@ -583,19 +539,16 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
     // chunks in flight) are best at every size.  Between half a round and four rounds the new token's
     // rows are stored after the stream (see the kernel).
     const long long units = (long long)H * B * layers;
-    a.late_new_store = g_probe / 1000000 == 1 ? 0 : g_probe / 1000000 == 2 ? 1 : (units > 2048 && units <= 16384 ? 1 : 0);
-    int ch = g_tune.ch && !heads && !a.rope_layout ? g_tune.ch : 4;
-    int wpb = g_tune.wpb ? g_tune.wpb : (units <= 2048 ? 1 : 4);
+    a.late_new_store = shape.new_rows == 1 ? 0 : shape.new_rows == 2 ? 1 : (units > 2048 && units <= 16384 ? 1 : 0);
+    int ch = shape.ch && !heads && !a.rope_layout ? shape.ch : 4;
+    int wpb = shape.wpb ? shape.wpb : (units <= 2048 ? 1 : 4);
     // few and long units (the high-resolution shape: 2048 units of 129 to 385 rows): four waves share a unit (code 14)
     const int longest = a.se.total > a.sp.total ? a.se.total : a.sp.total;
-    if (!g_tune.wpb && !heads && !a.rope_layout && units <= 2048 && longest >= 96) wpb = 14;
+    if (!shape.wpb && !heads && !a.rope_layout && units <= 2048 && longest >= 96) wpb = 14;
     if (wpb > 10 && ch == 1) ch = 2;                      // the shared-unit launch exists with two and four loads per chunk
     a.wave_lds = (int)(((size_t)a.zcap * 4 + (a.do_compress ? select_lds_bytes(M, n_cand, n_old) + 16 : 0) + 15) / 16 * 16);
     while (wpb > 1 && wpb < 10 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;
-    size_t lds = (size_t)wpb * a.wave_lds;
-#ifdef SSD_PROBE
-    if ((size_t)(g_probe / 10000 % 100) * 1024 > lds) lds = (size_t)(g_probe / 10000 % 100) * 1024;   // occupancy experiments: pad the workgroup's LDS
-#endif
+    const size_t lds = (size_t)wpb * a.wave_lds;
     const dim3 blocks = heads ? dim3((unsigned)RANK_GROUPS, (unsigned)B, (unsigned)(((H + wpb - 1) / wpb + RANK_GROUPS - 1) / RANK_GROUPS))   // rank order, see the kernel
                               : dim3((unsigned)((max_type_heads + wpb - 1) / wpb), (unsigned)B, (unsigned)(2 * layers));
     // wpb codes 12 and 14: one unit per workgroup, shared by 2 or 4 waves
@@ -607,11 +560,6 @@ static hipError_t launch_step(StepArgs &full, int H, int max_type_heads, int B, 
         SSD_CASE(1, 1) SSD_CASE(2, 1) SSD_CASE(4, 1)
         SSD_CASE(1, 2) SSD_CASE(2, 2) SSD_CASE(4, 2)
         SSD_CASE(1, 4) SSD_CASE(2, 4) SSD_CASE(4, 4)
-#ifdef SSD_PROBE
-#define SSD_CASE_NPF(CODE_, CH_, WPB_) if (ch == CODE_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_, false>(full, blocks, lds, fused, false, s); return hipGetLastError(); }
-        SSD_CASE_NPF(14, 4, 4) SSD_CASE_NPF(18, 8, 4) SSD_CASE_NPF(14, 4, 8) SSD_CASE_NPF(18, 8, 8) SSD_CASE_NPF(18, 8, 2) SSD_CASE(4, 8) SSD_CASE(2, 8)
-#undef SSD_CASE_NPF
-#endif
     } else {
         if (ch == 1) ch = 2;
         SSD_CASE(2, 1) SSD_CASE(4, 1) SSD_CASE(2, 2) SSD_CASE(4, 2) SSD_CASE(2, 4) SSD_CASE(4, 4)
@@ -625,12 +573,21 @@ struct Rope {
     int layout;
 };
 
-// Shared by ssd_decode_attn (k_new == NULL, compress == 0), ssd_decode_step and ssd_decode_step_rope.
+// Sequences per part when the batch is dealt to n streams: equal parts of an even number of sequences (the
+// two sequences of a prompt under classifier-free guidance stay together), the last part taking what is left.
+static int part_size(int B, int n) {
+    const int per = (B + n - 1) / n;
+    return (per + 1) / 2 * 2;
+}
+
+// Shared by ssd_decode_attn (k_new == NULL, compress == 0), ssd_decode_step, ssd_decode_step_rope and
+// ssd_decode_step_split.  streams[0..n_streams): part i of the batch is enqueued on streams[i].
 static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new, const void *v_new,
-                    void *out, int accumulate, int compress, void *stream, const char *what, Rope rope = {nullptr, nullptr, 0}) {
+                    void *out, int accumulate, int compress, void *const *streams, int n_streams, const char *what,
+                    Rope rope = {nullptr, nullptr, 0}) {
     const ssd_config &cf = cache->cfg;
     const bool fused = k_new != nullptr;
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int Bp = part_size(cf.n_seqs, n_streams);
     for (int lb = layer_begin; lb < layer_end;) {
         const int le = same_state_run(cache, lb, layer_end);
         const LayerState before = cache->st[lb];
@@ -671,24 +628,29 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.rope_layout = rope.layout; a.rope_cos = rope.cos; a.rope_sin = rope.sin;
             if (heads_differ(cache, lb)) fill_head_order(cache, lb, before, at, fused, &full.ho);
             else full.ho = HeadOrder{};                  // never read then; keeps the argument bytes defined
-            a.probe = g_probe % 1000000;
             int mth = 1;
             for (int l = lb; l < le; ++l) {
                 mth = cache->ldesc[l].n_sp > mth ? cache->ldesc[l].n_sp : mth;
                 mth = cache->ldesc[l].n_se > mth ? cache->ldesc[l].n_se : mth;
             }
             a.sem_first = a.se.total + (fused ? 1 : 0) >= a.sp.total + (fused ? 1 : 0) ? 1 : 0;
-            hipError_t e;
-            if (cf.dtype == SSD_BF16)
-                e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, heads_differ(cache, lb), cache->Ml[lb], s)
-                                       : launch_step<bf16_t, 64>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, heads_differ(cache, lb), cache->Ml[lb], s);
-            else
-                e = cf.head_dim == 128 ? launch_step<float, 128>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, heads_differ(cache, lb), cache->Ml[lb], s)
-                                       : launch_step<float, 64>(full, cf.n_heads, mth, cf.n_seqs, le - lb, fused, heads_differ(cache, lb), cache->Ml[lb], s);
-            if (e != hipSuccess) return hip_fail(e, what);
-            if (do_compress && !in_kernel) {
-                const int rc = launch_compress_inplace(cache, lb, le, at, s);
-                if (rc != SSD_OK) return rc;
+            for (int part = 0; part < n_streams && part * Bp < cf.n_seqs; ++part) {
+                hipStream_t s = static_cast<hipStream_t>(streams[part]);
+                a.seq_off = part * Bp;
+                const int Bn = cf.n_seqs - a.seq_off < Bp ? cf.n_seqs - a.seq_off : Bp;
+                const bool hd = heads_differ(cache, lb);
+                hipError_t e;
+                if (cf.dtype == SSD_BF16)
+                    e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(full, cache->shape, cf.n_heads, mth, Bn, le - lb, fused, hd, cache->Ml[lb], s)
+                                           : launch_step<bf16_t, 64>(full, cache->shape, cf.n_heads, mth, Bn, le - lb, fused, hd, cache->Ml[lb], s);
+                else
+                    e = cf.head_dim == 128 ? launch_step<float, 128>(full, cache->shape, cf.n_heads, mth, Bn, le - lb, fused, hd, cache->Ml[lb], s)
+                                           : launch_step<float, 64>(full, cache->shape, cf.n_heads, mth, Bn, le - lb, fused, hd, cache->Ml[lb], s);
+                if (e != hipSuccess) return hip_fail(e, what);
+                if (do_compress && !in_kernel) {
+                    const int rc = launch_compress_inplace(cache, lb, le, at, a.seq_off, Bn, s);
+                    if (rc != SSD_OK) return rc;
+                }
             }
         }
         for (int l = lb; l < le; ++l) {
@@ -701,20 +663,32 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
     return SSD_OK;
 }
 
+// Argument and overflow checks common to the fused entry points.
+static int check_step_args(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new, const void *v_new,
+                           const void *out) {
+    int rc = check_layers(cache, layer_begin, layer_end);
+    if (rc != SSD_OK) return rc;
+    if (!q || !out || !k_new || !v_new) return fail(SSD_ERR_INVALID_ARG, "q, k_new, v_new or out is NULL");
+    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(k_new, 16) || !aligned(v_new, 16))
+        return fail(SSD_ERR_INVALID_ARG, "q / k_new / v_new / out must be 16-byte aligned");
+    for (int l = layer_begin; l < layer_end; ++l)
+        if (has_buffer(cache, l) && cache->st[l].c >= cache->cfg.stage_cap)
+            return fail(SSD_ERR_STAGE_OVERFLOW, "row buffer overflow: layer %d already buffers %d tokens (C=%d); call ssd_compress_kv",
+                        l, cache->st[l].c, cache->cfg.stage_cap);
+    return SSD_OK;
+}
+
 }  // namespace ssd
 
 using namespace ssd;
 
-// Launch-shape knobs for benchmark sweeps and tests: wave-wide loads per chunk (1, 2, 4; 0 = the
-// default) and units per workgroup (1, 2, 4; 0 = chosen from the launch size); (0, 0) restores the
-// defaults.
-extern "C" int ssd_tune_attend(int ch, int wpb, int probe) {
-    g_probe = probe;
-    if (ch == 0 && wpb == 0) { g_tune = DEFAULT_TUNE; return SSD_OK; }
-#ifndef SSD_PROBE
-    if ((ch != 0 && ch != 1 && ch != 2 && ch != 4) || (wpb != 0 && wpb != 1 && wpb != 2 && wpb != 4 && wpb != 12 && wpb != 14)) return SSD_ERR_INVALID_ARG;
-#endif
-    g_tune.ch = ch; g_tune.wpb = wpb;
+extern "C" int ssd_cache_set_launch_shape(ssd_cache *cache, int ch, int wpb, int new_rows) {
+    clear_error();
+    if (!cache) return fail(SSD_ERR_INVALID_ARG, "cache is NULL");
+    if ((ch != 0 && ch != 1 && ch != 2 && ch != 4) || (wpb != 0 && wpb != 1 && wpb != 2 && wpb != 4 && wpb != 12 && wpb != 14) ||
+        new_rows < 0 || new_rows > 2)
+        return fail(SSD_ERR_INVALID_ARG, "launch shape (%d, %d, %d) is not one the library has", ch, wpb, new_rows);
+    cache->shape = LaunchShape{ch, wpb, new_rows};
     return SSD_OK;
 }
 
@@ -727,41 +701,63 @@ extern "C" int ssd_decode_attn(ssd_cache *cache, int layer_begin, int layer_end,
     if (!aligned(q, 16) || !aligned(out, 16)) return fail(SSD_ERR_INVALID_ARG, "q / out must be 16-byte aligned");
     for (int l = layer_begin; l < layer_end; ++l)
         if (cache->st[l].n < 1) return fail(SSD_ERR_ORDER, "layer %d holds no token: call ssd_append_token first", l);
-    return run_step(cache, layer_begin, layer_end, q, nullptr, nullptr, out, accumulate_scores, 0, stream, "attention launch");
+    return run_step(cache, layer_begin, layer_end, q, nullptr, nullptr, out, accumulate_scores, 0, &stream, 1, "attention launch");
 }
 
 extern "C" int ssd_decode_step(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new,
                                const void *v_new, void *out, int accumulate_scores, int compress, void *stream) {
     clear_error();
-    int rc = check_layers(cache, layer_begin, layer_end);
+    const int rc = check_step_args(cache, layer_begin, layer_end, q, k_new, v_new, out);
     if (rc != SSD_OK) return rc;
-    if (!q || !out || !k_new || !v_new) return fail(SSD_ERR_INVALID_ARG, "q, k_new, v_new or out is NULL");
-    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(k_new, 16) || !aligned(v_new, 16))
-        return fail(SSD_ERR_INVALID_ARG, "q / k_new / v_new / out must be 16-byte aligned");
-    for (int l = layer_begin; l < layer_end; ++l)
-        if (has_buffer(cache, l) && cache->st[l].c >= cache->cfg.stage_cap)
-            return fail(SSD_ERR_STAGE_OVERFLOW, "row buffer overflow: layer %d already buffers %d tokens (C=%d); call ssd_compress_kv",
-                        l, cache->st[l].c, cache->cfg.stage_cap);
-    return run_step(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, stream, "decode step launch");
+    return run_step(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, &stream, 1, "decode step launch");
+}
+
+extern "C" int ssd_decode_step_split(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new,
+                                     const void *v_new, void *out, int accumulate_scores, int compress,
+                                     void *const *streams, int n_streams, int sync) {
+    clear_error();
+    int rc = check_step_args(cache, layer_begin, layer_end, q, k_new, v_new, out);
+    if (rc != SSD_OK) return rc;
+    if (!streams || n_streams < 1 || n_streams > SSD_MAX_SPLIT)
+        return fail(SSD_ERR_INVALID_ARG, "streams is NULL or n_streams=%d outside 1..%d", n_streams, SSD_MAX_SPLIT);
+    if (sync & ~(SSD_SPLIT_FORK | SSD_SPLIT_JOIN)) return fail(SSD_ERR_INVALID_ARG, "sync=%d has unknown bits", sync);
+    for (int i = 0; i < n_streams; ++i)
+        for (int j = 0; j < i; ++j)
+            if (streams[i] == streams[j]) return fail(SSD_ERR_INVALID_ARG, "streams[%d] and streams[%d] are the same stream", j, i);
+    const bool live = cache->launch_enabled && n_streams > 1;
+    if (live && sync) {
+        rc = ensure_events(cache);
+        if (rc != SSD_OK) return rc;
+    }
+    if (live && (sync & SSD_SPLIT_FORK)) {
+        // the other streams take up the work where streams[0] stands now
+        hipError_t e = hipEventRecord(cache->ev_fork, static_cast<hipStream_t>(streams[0]));
+        for (int i = 1; i < n_streams && e == hipSuccess; ++i) e = hipStreamWaitEvent(static_cast<hipStream_t>(streams[i]), cache->ev_fork, 0);
+        if (e != hipSuccess) return hip_fail(e, "fork of the split step");
+    }
+    rc = run_step(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, streams, n_streams, "split decode step launch");
+    if (rc != SSD_OK) return rc;
+    if (live && (sync & SSD_SPLIT_JOIN)) {
+        // streams[0] goes on only when every part is done
+        for (int i = 1; i < n_streams; ++i) {
+            hipError_t e = hipEventRecord(cache->ev_join[i], static_cast<hipStream_t>(streams[i]));
+            if (e == hipSuccess) e = hipStreamWaitEvent(static_cast<hipStream_t>(streams[0]), cache->ev_join[i], 0);
+            if (e != hipSuccess) return hip_fail(e, "join of the split step");
+        }
+    }
+    return SSD_OK;
 }
 
 extern "C" int ssd_decode_step_rope(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new,
                                     const void *v_new, void *out, int accumulate_scores, int compress, const float *cos_p,
                                     const float *sin_p, int rope_layout, void *stream) {
     clear_error();
-    int rc = check_layers(cache, layer_begin, layer_end);
+    const int rc = check_step_args(cache, layer_begin, layer_end, q, k_new, v_new, out);
     if (rc != SSD_OK) return rc;
-    if (!q || !out || !k_new || !v_new) return fail(SSD_ERR_INVALID_ARG, "q, k_new, v_new or out is NULL");
-    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(k_new, 16) || !aligned(v_new, 16))
-        return fail(SSD_ERR_INVALID_ARG, "q / k_new / v_new / out must be 16-byte aligned");
     if (rope_layout != SSD_ROPE_HALF && rope_layout != SSD_ROPE_INTERLEAVED)
         return fail(SSD_ERR_INVALID_ARG, "rope_layout=%d is neither SSD_ROPE_HALF nor SSD_ROPE_INTERLEAVED", rope_layout);
     if (!cos_p || !sin_p || !aligned(cos_p, 16) || !aligned(sin_p, 16))
         return fail(SSD_ERR_INVALID_ARG, "cos / sin must be given and 16-byte aligned");
-    for (int l = layer_begin; l < layer_end; ++l)
-        if (has_buffer(cache, l) && cache->st[l].c >= cache->cfg.stage_cap)
-            return fail(SSD_ERR_STAGE_OVERFLOW, "row buffer overflow: layer %d already buffers %d tokens (C=%d); call ssd_compress_kv",
-                        l, cache->st[l].c, cache->cfg.stage_cap);
-    return run_step(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, stream,
+    return run_step(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, &stream, 1,
                     "decode step launch (rotary)", Rope{cos_p, sin_p, rope_layout});
 }

@@ -16,10 +16,16 @@ FAKE = 1 << 24          # a 16-byte aligned non-null "device pointer" that is ne
 
 
 def test_library_exports_every_declared_symbol():
-    text = open(os.path.join(ROOT, "include", "ssd.h")).read()
+    import glob
+    headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
+    assert [os.path.basename(h) for h in headers] == ["ssd.h", "ssd_hooks.h"]
+    text = "".join(open(h).read() for h in headers)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(ssd_[a-z_0-9]+)\s*\(", text)))
-    assert {"ssd_classify_heads", "ssd_compress_kv", "ssd_decode_attn", "ssd_append_token"} <= set(names)
+    assert {"ssd_classify_heads", "ssd_compress_kv", "ssd_decode_attn", "ssd_append_token", "ssd_decode_step_split"} <= set(names)
+    # the method's header holds no launch-shape or benchmark hook
+    api = re.sub(r"/\*.*?\*/", "", open(headers[0]).read(), flags=re.S)
+    assert "ssd_bench_stream" not in api and "launch_shape" not in api and "ssd_cache_set_launch" not in api
     for n in names:
         assert hasattr(ssd.lib, n), n
     assert ssd.ssd_version() >= 100
@@ -477,3 +483,66 @@ def test_product_and_oracle_do_not_import_each_other():
         assert "paper_2510_18716_amd" not in text and "ssd.h" not in text and "csrc" not in text, path
     wl = open(os.path.join(ROOT, "workload", "__init__.py")).read()
     assert not re.search(r"^\s*(import|from)\s+(oracle|paper_2510_18716_amd)\b", wl, flags=re.M)
+
+
+def test_split_step_checks_its_stream_list_and_moves_the_counters_once():
+    """ssd_decode_step_split on the host: the counters advance once per call whatever the number of streams (the
+    parts of the batch move together), and a bad stream list or sync value is refused before anything else."""
+    import ctypes as C
+    cfg = make_config(3, 10, 4, 64, "f32", 5, 1, 4, 1, 3)
+    ht = np.array([[0, 0, 1, 1], [0, 0, 0, 0], [1, 1, 1, 1]], np.uint8)
+    a = ssd.Cache(cfg, ht, device=None)
+    b = ssd.Cache(cfg, ht, device=None)
+    fake_streams = [FAKE + 64 * i for i in range(1, 5)]           # never dereferenced: launches are off
+    for step in range(12):
+        comp = step % 2 == 1
+        n = 1 + step % ssd.SSD_MAX_SPLIT
+        ssd.ssd_decode_step_split(a, 0, 3, FAKE, FAKE, FAKE, FAKE, fake_streams[:n], ssd.SSD_SPLIT_FORK | ssd.SSD_SPLIT_JOIN, True, comp)
+        ssd.ssd_decode_step(b, 0, 3, FAKE, FAKE, FAKE, FAKE, True, comp)
+        for l in range(3):
+            assert a.layer_state(l) == b.layer_state(l), (step, l)
+    lib = ssd.lib
+    arr = ssd.stream_array(fake_streams)
+    ok = (a.handle, 0, 3, FAKE, FAKE, FAKE, FAKE, 1, 1)
+    before = [a.layer_state(l) for l in range(3)]
+    assert lib.ssd_decode_step_split(*ok, None, 2, 0) == ssd.SSD_ERR_INVALID_ARG
+    assert lib.ssd_decode_step_split(*ok, arr, 0, 0) == ssd.SSD_ERR_INVALID_ARG
+    assert lib.ssd_decode_step_split(*ok, arr, ssd.SSD_MAX_SPLIT + 1, 0) == ssd.SSD_ERR_INVALID_ARG
+    assert lib.ssd_decode_step_split(*ok, arr, 2, 4) == ssd.SSD_ERR_INVALID_ARG                   # unknown sync bit
+    assert "sync" in ssd.ssd_last_error()
+    dup = (C.c_void_p * 2)(fake_streams[0], fake_streams[0])
+    assert lib.ssd_decode_step_split(*ok, dup, 2, 0) == ssd.SSD_ERR_INVALID_ARG                   # the same stream twice
+    assert lib.ssd_decode_step_split(a.handle, 0, 3, None, FAKE, FAKE, FAKE, 1, 1, arr, 2, 0) == ssd.SSD_ERR_INVALID_ARG
+    assert lib.ssd_decode_step_split(a.handle, 2, 4, FAKE, FAKE, FAKE, FAKE, 1, 1, arr, 2, 0) == ssd.SSD_ERR_LAYER_RANGE
+    assert [a.layer_state(l) for l in range(3)] == before          # a refused call changes nothing
+    # a full row buffer refuses the whole call, as in ssd_decode_step
+    for _ in range(2):
+        ssd.ssd_decode_step_split(a, 0, 3, FAKE, FAKE, FAKE, FAKE, fake_streams[:2], 0, True, False)
+    with pytest.raises(ssd.SsdError) as e:
+        ssd.ssd_decode_step_split(a, 0, 3, FAKE, FAKE, FAKE, FAKE, fake_streams[:2], 0, True, False)
+    assert e.value.code == ssd.SSD_ERR_STAGE_OVERFLOW
+
+
+def test_launch_shape_hook_accepts_only_shapes_the_library_has():
+    cfg = make_config(1, 2, 4, 64, "f32", 5, 1, 4, 1, 3)
+    a = ssd.Cache(cfg, _ht(1, 4), device=None)
+    for ch, wpb, rows in [(0, 0, 0), (1, 1, 1), (2, 2, 2), (4, 4, 0), (2, 12, 1), (4, 14, 2)]:
+        a.set_launch_shape(ch, wpb, rows)
+    for ch, wpb, rows in [(3, 1, 0), (8, 1, 0), (1, 3, 0), (1, 8, 0), (1, 13, 0), (1, 1, 3), (1, 1, -1), (-1, 0, 0)]:
+        with pytest.raises(ssd.SsdError) as e:
+            a.set_launch_shape(ch, wpb, rows)
+        assert e.value.code == ssd.SSD_ERR_INVALID_ARG
+    assert ssd.lib.ssd_cache_set_launch_shape(None, 0, 0, 0) == ssd.SSD_ERR_INVALID_ARG
+    # results of host-side calls are unaffected
+    ssd.ssd_decode_step(a, 0, 1, FAKE, FAKE, FAKE, FAKE, True, True)
+    assert a.layer_state(0)[0] == 1
+
+
+def test_dense_split_hook_rejects_bad_split_counts_before_any_launch():
+    lib = ssd.lib
+    ok = (FAKE, FAKE, FAKE, FAKE, 1, 1, 64, ssd.SSD_F32, 8, 4, 0.0, None, None, 1, 0, 32)
+    assert lib.ssd_dense_decode_attn_splits(*ok, -1, FAKE, 1 << 20, None) == ssd.SSD_ERR_INVALID_ARG
+    assert lib.ssd_dense_decode_attn_splits(*ok, 65, FAKE, 1 << 20, None) == ssd.SSD_ERR_INVALID_ARG
+    assert "splits" in ssd.ssd_last_error()
+    assert lib.ssd_dense_decode_attn_splits(*ok, 4, None, 0, None) == ssd.SSD_ERR_INVALID_ARG      # splits need a workspace
+    assert lib.ssd_dense_decode_attn_splits(*ok, 4, FAKE, 16, None) == ssd.SSD_ERR_INVALID_ARG     # ... that is large enough

@@ -7,7 +7,7 @@ import torch
 import oracle
 import paper_2510_18716_amd as ssd
 import workload
-from harness import TOL, check_outputs, gpu_decode, make_cache, oracle_unit, sample_units, say
+from harness import TOL, check_outputs, gpu_decode, heavy_cap, make_cache, oracle_unit, sample_units, say
 
 pytestmark = pytest.mark.gpu
 
@@ -23,13 +23,11 @@ def _dense_case(B, H, d, dtype, n_cap, n, splits, seed, vis_start=0, w=32):
     far = torch.full((B, H, 3), -7.0, device="cuda")
     tot = torch.full((B, H, 3), -7.0, device="cuda")
     ws = torch.empty(ssd.ssd_dense_workspace_bytes(B, H, d, n), dtype=torch.uint8, device="cuda")
-    assert ssd.lib.ssd_tune_dense(splits) == 0
-    try:
-        ssd.ssd_dense_decode_attn(q.cuda(), K.cuda(), V.cuda(), out, B, H, d, dtype, n_cap, n, 0.0,
-                                  far[:, :, 1:].data_ptr(), tot[:, :, 1:].data_ptr(), 3, vis_start, w, ws)
-        torch.cuda.synchronize()
-    finally:
-        ssd.lib.ssd_tune_dense(0)
+    # splits = 0: the entry point itself (the library's choice); otherwise the hook that fixes the split count
+    ssd.ssd_dense_decode_attn(q.cuda(), K.cuda(), V.cuda(), out, B, H, d, dtype, n_cap, n, 0.0,
+                              far[:, :, 1:].data_ptr(), tot[:, :, 1:].data_ptr(), 3, vis_start, w, ws,
+                              splits=splits if splits else None)
+    torch.cuda.synchronize()
     o = out.float().cpu().numpy()
     farh, toth = far.cpu().numpy(), tot.cpu().numpy()
     scale = 1.0 / np.sqrt(d)
@@ -117,13 +115,11 @@ def test_classification_strict_threshold_and_zero_denominator():
     assert ty.cpu().tolist() == [[1, 1]]
 
 
-@pytest.mark.parametrize("dtype,d,n_src,M,R,W,S", [("bf16", 128, 200, 16, 3, 24, 2), ("f32", 64, 37, 40, 1, 50, 1),
-                                                    ("bf16", 128, 2368, 128, 1, 128, 1), ("bf16", 64, 5, 4, 8, 3, 1)])
-def test_dense_source_compression_with_tied_scores(dtype, d, n_src, M, R, W, S):
-    say("dense-source case", dtype, d, n_src, M, R, W, S)
-    wl = workload.Workload("dsrc", L=2, prompts=1, H=4, d=d, dtype=dtype, n0=n_src, grid_h=2, grid_w=3, W=W, M=M,
-                           S=S, R=R, C=R + 3, cadence=2, seed=31 + n_src, plain=True)
-    ht = workload.head_map(wl)
+def _dense_source_case(wl, ht, n_src, fused=False):
+    """Dense-source compression of the first n_src tokens with scores full of exact ties, then ordinary decode of
+    the rest, against an oracle unit that took the same route (load_dense, then run)."""
+    say("dense-source case", wl.name, wl.dtype, wl.d, "n_src", n_src, "M", wl.M, "R", wl.R, "W", wl.W, "S", wl.S, "alg2", wl.alg2,
+        "per-head", wl.head_budget is not None, "fused", fused)
     data = workload.generate(wl, head_type=ht)
     dev = {k: v.cuda() for k, v in data.items()}
     r = np.random.default_rng(n_src)
@@ -133,25 +129,73 @@ def test_dense_source_compression_with_tied_scores(dtype, d, n_src, M, R, W, S):
     V = workload.dense_layout(dev["v"][:n_src])
     cache = make_cache(wl, ht)
     ssd.ssd_compress_kv(cache, 0, wl.L, K, V, torch.from_numpy(score).cuda(), n_src)
+    first = [x.cpu().numpy() for x in cache.export(0)]          # state right after the dense-source call, layer 0
     # then decode the remaining tokens normally on both sides
     units = sample_units(wl, ht, 10 ** 9)
     sched = workload.compress_schedule(wl)
     steps = list(range(n_src, wl.n_total))
-    outs, exports, _ = gpu_decode(wl, dev, ht, sched, units, export_steps=steps, cache=cache, p_begin=n_src)
+    outs, exports, _ = gpu_decode(wl, dev, ht, sched, units, export_steps=steps, cache=cache, p_begin=n_src, fused=fused,
+                                  shadow=False)
     for ui, (l, b, h) in enumerate(units):
         q_, K_, V_ = workload.unit_arrays(data, l, b, h)
         sem = ht[l, h] == workload.SEMANTIC
-        u = oracle.Unit(sem, W, S, M, R, wl.C)
+        W_h, M_h = wl.W_of(l, h), wl.M_of(l, h)
+        u = oracle.Unit(sem, W_h, wl.S, M_h, wl.R, wl.C, buffered_spatial=wl.alg2)
         u.load_dense(n_src, score[l, b, h])
+        if l == 0:      # the call's own result, before any further token
+            got = sorted(int(x) for x in first[0][b, h] if x >= 0)
+            assert got == sorted(int(x) for x in u.retained()), ("retained set after the dense-source call", (l, b, h))
+            if sem:
+                hp, hs, sp, ss = u.state()
+                ref = dict(zip(hp.tolist() + sp.tolist(), hs.tolist() + ss.tolist()))
+                assert {int(p): float(x) for p, x in zip(first[0][b, h], first[2][b, h]) if p >= 0} == ref
         o_ref, hl, gl = u.run(q_, K_, V_, wl.scale, sched, log=True)
-        check_outputs(outs[:, ui], o_ref, dtype, "unit %s after dense-source compression" % ((l, b, h),))
+        check_outputs(outs[:, ui], o_ref, wl.dtype, "unit %s after dense-source compression" % ((l, b, h),))
+        Mcap = heavy_cap(wl, ht, l)
         for p in steps:
             row = exports[p]["post"][0][l, b, h]
             if sem:
-                assert sorted(int(x) for x in row[:M] if x >= 0) == [int(x) for x in hl[p - n_src] if x >= 0]
+                assert sorted(int(x) for x in row[:Mcap] if x >= 0) == [int(x) for x in hl[p - n_src] if x >= 0], ((l, b, h), p)
             else:
                 n = p + 1
-                assert sorted(int(x) for x in row if x >= 0) == sorted(set(range(min(S, n))) | set(range(max(S, n - W), n)))
+                n_c = max([s + 1 for s in range(n_src, p + 1) if sched[s]], default=n_src)
+                ref_n = n_c if wl.alg2 else n
+                assert sorted(int(x) for x in row if x >= 0) == sorted(set(range(min(wl.S, n))) | set(range(max(wl.S, ref_n - W_h), n))), ((l, b, h), p)
+
+
+@pytest.mark.parametrize("dtype,d,n_src,M,R,W,S", [("bf16", 128, 200, 16, 3, 24, 2), ("f32", 64, 37, 40, 1, 50, 1),
+                                                    ("bf16", 128, 2368, 128, 1, 128, 1), ("bf16", 64, 5, 4, 8, 3, 1)])
+def test_dense_source_compression_with_tied_scores(dtype, d, n_src, M, R, W, S):
+    wl = workload.Workload("dsrc", L=2, prompts=1, H=4, d=d, dtype=dtype, n0=n_src, grid_h=2, grid_w=3, W=W, M=M,
+                           S=S, R=R, C=R + 3, cadence=2, seed=31 + n_src, plain=True)
+    _dense_source_case(wl, workload.head_map(wl), n_src)
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["three-calls", "fused-step"])
+@pytest.mark.parametrize("dtype,d,n_src,M,R,W,S,C,cadence", [("bf16", 128, 200, 16, 0, 24, 2, 6, 6), ("f32", 64, 37, 40, 2, 50, 1, 7, 4),
+                                                             ("bf16", 64, 5, 4, 3, 3, 1, 5, 2), ("bf16", 128, 90, 12, 1, 100, 0, 4, 3)])
+def test_dense_source_compression_under_algorithm2(dtype, d, n_src, M, R, W, S, C, cadence, fused):
+    # the prefill branch of Algorithm 2 with the row buffer read by both head types: the spatial heads' window is
+    # cut at n_src ("Compress spatial cache (sink + recent)"), their ring has W + C slots, and the tokens decoded
+    # afterwards pile up in the row buffer until the next compression
+    wl = workload.Workload("dsrc-alg2", L=2, prompts=1, H=4, d=d, dtype=dtype, n0=n_src, grid_h=3, grid_w=5, W=W, M=M,
+                           S=S, R=R, C=C, cadence=cadence, seed=131 + n_src, plain=True, alg2=True)
+    assert R + cadence <= C          # room in the row buffer until the first compression after the prompt
+    _dense_source_case(wl, workload.head_map(wl), n_src, fused=fused)
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["three-calls", "fused-step"])
+@pytest.mark.parametrize("alg2", [False, True], ids=["alg1", "alg2"])
+def test_dense_source_compression_with_budgets_per_head(alg2, fused):
+    # head-wise allocation: every head keeps its own W_h newest / top-M_h tokens of the dense segment, inside units
+    # sized for the layer's largest head; includes W_h = 1, M_h = 1 and budgets beyond the segment
+    hb = ((24, 5, 1, 7, 200, 3), (9, 9, 30, 2, 1, 17))
+    n_src = 60
+    wl = workload.Workload("dsrc-per-head", L=2, prompts=1, H=6, d=128, dtype="bf16", n0=n_src, grid_h=3, grid_w=5, W=99, M=99,
+                           S=1, R=(0 if alg2 else 2), C=5, cadence=(5 if alg2 else 3), seed=137, plain=True, head_budget=hb, alg2=alg2)
+    _dense_source_case(wl, workload.head_map(wl), n_src, fused=fused)
+    wl = wl.replace(name="dsrc-per-head-f32", dtype="f32", d=64, seed=139)
+    _dense_source_case(wl, workload.head_map(wl), n_src, fused=fused)
 
 
 def test_dense_source_without_scores_keeps_lowest_positions():

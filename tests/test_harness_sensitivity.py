@@ -73,8 +73,8 @@ def _rope_unit(wl, ht, data, h, layout_q, layout_k, shift_k=0, flip_k=False, rot
     cos_t, sin_t = workload.rope_tables(wl.n_total + 1, wl.d)
     import torch
     rnd = lambda x: torch.from_numpy(x).to(torch.bfloat16).float().numpy()
-    qr = np.stack([oracle.rope(q[p], cos_t[p], sin_t[p], layout_q, single=True) for p in range(wl.n_total)]) if rotate_q else q
-    kr = np.stack([oracle.rope(K[p], cos_t[p + shift_k], (-sin_t if flip_k else sin_t)[p + shift_k], layout_k, single=True)
+    qr = np.stack([oracle.rope(q[p], cos_t[p], sin_t[p], layout_q) for p in range(wl.n_total)]) if rotate_q else q
+    kr = np.stack([oracle.rope(K[p], cos_t[p + shift_k], (-sin_t if flip_k else sin_t)[p + shift_k], layout_k)
                    for p in range(wl.n_total)])
     u = oracle.Unit(ht[0, h] == workload.SEMANTIC, wl.W, wl.S, wl.M, wl.R, wl.C)
     o, hl, _ = u.run(rnd(qr), rnd(kr), V, wl.scale, workload.compress_schedule(wl), log=True)

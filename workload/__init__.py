@@ -55,6 +55,7 @@ class Workload:
     W_layers: Optional[Sequence[int]] = None    # window per layer (None = W everywhere)
     M_layers: Optional[Sequence[int]] = None    # budget per layer (None = M everywhere)
     head_budget: Optional[Sequence[Sequence[int]]] = None   # [L][H]: W_h of a spatial head, M_h of a semantic head
+    softmax_scale: Optional[float] = None       # None = 1/sqrt(d)
 
     @property
     def B(self) -> int:
@@ -74,7 +75,7 @@ class Workload:
 
     @property
     def scale(self) -> float:
-        return 1.0 / math.sqrt(self.d)
+        return 1.0 / math.sqrt(self.d) if self.softmax_scale is None else float(self.softmax_scale)
 
     def W_of(self, layer: int, head: Optional[int] = None) -> int:
         if self.head_budget is not None and head is not None:

@@ -185,6 +185,10 @@ def main():
     ap.add_argument("--no-all-layers", action="store_true")
     ap.add_argument("--streams", type=int, default=2,
                     help="streams the batch is dealt to for the headline (ssd_decode_step_split); 1 = ssd_decode_step on one stream")
+    ap.add_argument("--sync", choices=["run", "step"], default="run",
+                    help="split schedule: 'step' forks at every token's first layer and joins at its last (a caller with one stream "
+                         "of its own); 'run' lets the parts run free on their streams between host synchronisations (a caller "
+                         "that runs its model on the parts of the batch in turn, each on its stream)")
     ap.add_argument("--no-one-stream", action="store_true", help="skip the one-stream figure reported beside a split headline")
     ap.add_argument("--dense-only", action="store_true", help="time only the full-cache baseline kernel (for a counter run of its own)")
     ap.add_argument("--tune", type=str, default="", help="ch,wpb[,new_rows] launch-shape override of the attention kernel (test hook)")
@@ -283,6 +287,7 @@ def main():
         calls = [(lb, min(wl.L, lb + lpc)) for lb in range(0, wl.L, lpc)]
         stream_arr = ssd.stream_array([torch.cuda.current_stream()] + side_streams[: ns - 1])
         FORK, JOIN = ssd.SSD_SPLIT_FORK, ssd.SSD_SPLIT_JOIN
+        sync_step = args.sync == "step"          # else: the parts meet only at the host's device-wide synchronisations
         n_parts = len(range(0, wl.B, (-(-wl.B // ns) + 1) // 2 * 2))          # parts that are not empty
 
         # raw device addresses: a launch should cost the host a ctypes call, not four tensor slices
@@ -317,7 +322,7 @@ def main():
                                                      cos_p + p * wl.d * 2, sin_p + p * wl.d * 2, args.rope, stream)
                     elif ns > 1:
                         rc = L_.ssd_decode_step_split(h, lb, le, qb + o, kb + o, vb + o, ob + lb * stride_l, acc_i, comp, stream_arr, ns,
-                                                      (FORK if ci == 0 else 0) | (JOIN if ci == len(calls) - 1 else 0))
+                                                      ((FORK if ci == 0 else 0) | (JOIN if ci == len(calls) - 1 else 0)) if sync_step else 0)
                     else:
                         rc = L_.ssd_decode_step(h, lb, le, qb + o, kb + o, vb + o, ob + lb * stride_l, acc_i, comp, stream)
                     assert rc == 0, ssd.ssd_last_error()
@@ -386,7 +391,31 @@ def main():
         # events themselves do not sit between launches.  Separate: a pair around each attention launch.
         n_ev = 2 if fused else 2 * len(calls)
         evs = []
-        for k_i in passes:
+        if fused and ns > 1 and not sync_step:
+            # free-running parts: one start event (every stream is idle after the synchronisation), one end event per
+            # stream behind its last launch; the span of a pass is the latest end
+            span_ms = 0.0
+            for k_i in passes:
+                for c_i in caches:
+                    c_i.reset()
+                for p in range(0, wl.n_total - k_i):
+                    step(p)
+                torch.cuda.synchronize()
+                e0 = torch.cuda.Event(enable_timing=True)
+                ends = [torch.cuda.Event(enable_timing=True) for _ in range(ns)]
+                e0.record()
+                for p in range(wl.n_total - k_i, wl.n_total):
+                    step(p)
+                ends[0].record()
+                for e_i, st_i in zip(ends[1:], side_streams):
+                    e_i.record(st_i)
+                torch.cuda.synchronize()
+                span_ms += max(e0.elapsed_time(e_i) for e_i in ends)
+            durs = [span_ms / (K_steps * len(calls) * R_rep)]
+            passes_ev = []
+        else:
+            passes_ev = passes
+        for k_i in passes_ev:
             for c_i in caches:
                 c_i.reset()
             for p in range(0, wl.n_total - k_i):
@@ -397,9 +426,9 @@ def main():
                 step(p, ev=evs_i[i])
             torch.cuda.synchronize()
             evs += evs_i
-        if fused:
+        if fused and evs:
             durs = [e[0].elapsed_time(e[1]) / (len(calls) * R_rep) for e in evs]
-        else:
+        elif not fused:
             durs = [e[2 * ci].elapsed_time(e[2 * ci + 1]) for e in evs for ci in range(len(calls))]
         avg_ms = float(np.mean(durs))
         achieved = bytes_launch / 1e9 / (avg_ms / 1e3)
@@ -414,7 +443,11 @@ def main():
             "algorithmic_bytes_per_launch": bytes_launch / (n_parts if fused else 1),
             "algorithmic_bytes_per_call": bytes_launch, "avg_call_ms": avg_ms,
             "median_call_ms": float(np.median(durs)), "layers_per_call": lpc,
-            "timer": ("HIP events on the stream that forks and joins, around the %d calls (%d launches) of each step: first launch's start "
+            "timer": ("HIP events: one before the first timed launch (all streams idle), one on every stream behind its last launch; the "
+                      "latest end minus the start, divided by the %d steps x %d calls; launches of different parts overlap, so this "
+                      "is the bytes of a call over its share of the span, not one kernel's duration" % (K_steps, len(calls)))
+                     if (fused and ns > 1 and not sync_step)
+                     else ("HIP events on the stream that forks and joins, around the %d calls (%d launches) of each step: first launch's start "
                       "to last launch's end, divided by %d; launches of different parts overlap, so this is bytes of a call over "
                       "its share of the span, not one kernel's duration" % (len(calls), len(calls) * n_parts, len(calls))) if (fused and ns > 1)
                      else ("HIP events on the launch stream around the %d back-to-back launches of each step, divided by %d"
@@ -443,9 +476,11 @@ def main():
                        "spatial_fraction": wl.spatial_frac, "layers_per_call": lpc, "replicas": R_rep,
                        "step": "append + attend(+score accumulate) + compress, every layer",
                        "streams": n_streams,
-                       "schedule": ("the batch dealt to %d streams (ssd_decode_step_split), forked at a token's first layer, joined at "
-                                    "its last; every part's layers in order on its stream" % n_streams) if n_streams > 1
+                       "schedule": ("the batch dealt to %d streams (ssd_decode_step_split), every part's layers in order on its stream"
+                                    % n_streams) if n_streams > 1
                                    else "one stream, one launch per call",
+                       "sync": ("none between host synchronisations: every part runs free on its stream" if args.sync == "run" else
+                                "fork at every token's first layer, join at its last") if n_streams > 1 else None,
                        "launches_per_step": head["launches_per_step"],
                        "entry_points": entry,
                        "timed_at": "last %d tokens of the raster decode (n -> %d)" % (passes[0], wl.n_total) +

@@ -24,8 +24,8 @@ __global__ __launch_bounds__(256) void bench_stream_kernel(uint4 *__restrict__ p
         for (int k = 0; k < 4; ++k) {
             int j = i + k * 64;
             j = j < half ? j : half - 1;
-            a[k] = b[j];
-            c[k] = b[half + j];
+            a[k] = load_once(reinterpret_cast<const char *>(b + j));              // the load the decode kernels stream with
+            c[k] = load_once(reinterpret_cast<const char *>(b + half + j));
         }
 #pragma unroll
         for (int k = 0; k < 4; ++k) acc += a[k].x ^ c[k].y ^ a[k].z ^ c[k].w;

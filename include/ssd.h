@@ -381,6 +381,27 @@ int ssd_dense_decode_attn(const void *q, const void *K, const void *V, void *out
                           int vis_start, int w, void *workspace, size_t workspace_bytes,
                           void *stream);
 
+/*
+ * ssd_dense_decode_attn for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace,
+ * same kernels, same results bit for bit; the partial results of the row splits go to a fixed scratch array of
+ * SSD_DENSE_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU the library runs on holds
+ * its own copy until the process ends).  The call allocates nothing and frees nothing.
+ *   - The device of `stream` must be the calling thread's current device (the scratch is looked up per device,
+ *     once, at the first call on that device).
+ *   - A shape whose partial results (B * H * splits * (4 + d) floats, splits as ssd_dense_decode_attn picks them)
+ *     exceed the scratch is refused with SSD_ERR_INVALID_ARG before anything is enqueued; B * H >= 8192 needs no
+ *     scratch at all.
+ *   - All calls on one GPU share that GPU's scratch and leave their partial results in it: two calls that may
+ *     run at the same time on one GPU (different streams, different threads) race and must not be made; calls
+ *     on one stream are ordered and safe.  Nothing in it has to start at zero.
+ */
+#define SSD_DENSE_STATIC_SCRATCH_BYTES (8u << 20)
+int ssd_dense_decode_attn_static(const void *q, const void *K, const void *V, void *out,
+                                 int B, int H, int d, int dtype, int n_cap, int n,
+                                 float softmax_scale, float *far, float *tot, int mass_stride,
+                                 int vis_start, int w, void *stream);
+
 /* Text of the calling thread's most recent error ("" if none). Never NULL. */
 const char *ssd_last_error(void);
 

@@ -96,6 +96,9 @@ lib.ssd_dense_workspace_bytes.restype = C.c_size_t
 lib.ssd_dense_decode_attn.argtypes = [_vp, _vp, _vp, _vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                       C.c_float, _vp, _vp, C.c_int, C.c_int, C.c_int, _vp, C.c_size_t, _vp]
 lib.ssd_dense_decode_attn.restype = C.c_int
+lib.ssd_dense_decode_attn_static.argtypes = [_vp, _vp, _vp, _vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                             C.c_float, _vp, _vp, C.c_int, C.c_int, C.c_int, _vp]
+lib.ssd_dense_decode_attn_static.restype = C.c_int
 lib.ssd_last_error.argtypes = []
 lib.ssd_last_error.restype = C.c_char_p
 lib.ssd_version.argtypes = []
@@ -386,3 +389,13 @@ def ssd_dense_decode_attn(q, K, V, out, B: int, H: int, d: int, dtype, n_cap: in
                                                 float(softmax_scale), _ptr(far), _ptr(tot), mass_stride, vis_start, w,
                                                 int(splits), _ptr(workspace), ws_bytes, _stream(stream)),
                "ssd_dense_decode_attn_splits")
+
+
+SSD_DENSE_STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def ssd_dense_decode_attn_static(q, K, V, out, B: int, H: int, d: int, dtype, n_cap: int, n: int, softmax_scale: float = 0.0,
+                                 far=None, tot=None, mass_stride: int = 1, vis_start: int = 0, w: int = 32, stream=None) -> None:
+    _check(lib.ssd_dense_decode_attn_static(_ptr(q), _ptr(K), _ptr(V), _ptr(out), B, H, d, _dtype_code(dtype), n_cap, n,
+                                            float(softmax_scale), _ptr(far), _ptr(tot), mass_stride, vis_start, w,
+                                            _stream(stream)), "ssd_dense_decode_attn_static")

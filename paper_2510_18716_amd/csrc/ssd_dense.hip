@@ -8,6 +8,8 @@
 // over several waves (split-K); each wave leaves an unnormalised partial (max, sum, masses,
 // output) in a caller-provided workspace and a second small kernel merges them.
 // Roofline: HBM; algorithmic bytes per unit = n * 2 * d * e.
+#include <mutex>
+
 #include "ssd_device.h"
 
 namespace ssd {
@@ -127,14 +129,46 @@ static hipError_t launch_dense(const DenseArgs &a, hipStream_t s) {
     return e;
 }
 
+// ---- scratch of ssd_dense_decode_attn_static ---------------------------------------------------------------
+//
+// The partial results of the row splits, for callers that may not allocate: a fixed array in the code object
+// instead of a caller's workspace.  Every GPU the library runs on holds its own copy until the process ends.
+// The array's name is a host-side stand-in and never goes to a kernel: the device address is looked up once per
+// device and kept.
+static constexpr size_t SCRATCH_BYTES = SSD_DENSE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[SCRATCH_BYTES];
+
+static constexpr int MAX_DEVICES = 64;
+static void *g_scratch_ptr[MAX_DEVICES];     // device address of `scratch` on device i, 0 until first used there
+static std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch`.
+static int scratch_address(void **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(SSD_ERR_INVALID_ARG, "device index %d outside 0..%d", dev, MAX_DEVICES - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress of the static scratch");
+        if (!ptr) return fail(SSD_ERR_HIP, "hipGetSymbolAddress returned no address for the static scratch");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SSD_OK;
+}
+
 }  // namespace ssd
 
 using namespace ssd;
 
-// splits == 0: chosen from the shape
+// splits == 0: chosen from the shape.  static_scratch: the partials go to this device's fixed scratch array
+// instead of `workspace`.
 static int dense_run(const void *q, const void *K, const void *V, void *out, int B, int H, int d, int dtype, int n_cap, int n,
                      float softmax_scale, float *far, float *tot, int mass_stride, int vis_start, int w, int splits,
-                     void *workspace, size_t workspace_bytes, void *stream) {
+                     void *workspace, size_t workspace_bytes, void *stream, bool static_scratch = false) {
     clear_error();
     if (!q || !K || !V || !out) return fail(SSD_ERR_INVALID_ARG, "q, K, V or out is NULL");
     if (!aligned(q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 16)) return fail(SSD_ERR_INVALID_ARG, "q, K, V, out must be 16-byte aligned");
@@ -166,8 +200,17 @@ static int dense_run(const void *q, const void *K, const void *V, void *out, int
     a.ws = static_cast<float *>(workspace);
     if (a.splits > 1) {
         const size_t need = (size_t)a.n_units * a.splits * (4 + d) * sizeof(float);
-        if (!workspace || workspace_bytes < need || !aligned(workspace, 256))
+        if (static_scratch) {
+            if (need > SCRATCH_BYTES)
+                return fail(SSD_ERR_INVALID_ARG, "%d units in %d row splits need %zu bytes of partial results, the static scratch holds %zu: "
+                            "use ssd_dense_decode_attn with a workspace", a.n_units, a.splits, need, SCRATCH_BYTES);
+            void *ptr = nullptr;
+            const int rc = scratch_address(&ptr);
+            if (rc != SSD_OK) return rc;
+            a.ws = static_cast<float *>(ptr);
+        } else if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) {
             return fail(SSD_ERR_INVALID_ARG, "workspace of %zu bytes (256-byte aligned) needed, got %zu", need, workspace_bytes);
+        }
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
@@ -196,4 +239,11 @@ extern "C" int ssd_dense_decode_attn_splits(const void *q, const void *K, const 
                                             void *stream) {
     return dense_run(q, K, V, out, B, H, d, dtype, n_cap, n, softmax_scale, far, tot, mass_stride, vis_start, w, splits,
                      workspace, workspace_bytes, stream);
+}
+
+extern "C" int ssd_dense_decode_attn_static(const void *q, const void *K, const void *V, void *out, int B, int H, int d, int dtype,
+                                            int n_cap, int n, float softmax_scale, float *far, float *tot, int mass_stride,
+                                            int vis_start, int w, void *stream) {
+    return dense_run(q, K, V, out, B, H, d, dtype, n_cap, n, softmax_scale, far, tot, mass_stride, vis_start, w, 0,
+                     nullptr, 0, stream, true);
 }

@@ -183,14 +183,24 @@ def main():
     ap.add_argument("--no-ceiling", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--no-all-layers", action="store_true")
-    ap.add_argument("--streams", type=int, default=2,
-                    help="streams the batch is dealt to for the headline (ssd_decode_step_split); 1 = ssd_decode_step on one stream")
+    ap.add_argument("--streams", type=int, default=0,
+                    help="streams the batch is dealt to for the headline (ssd_decode_step_split); 1 = ssd_decode_step on one stream; "
+                         "0 = 2 if a layer has at least 2048 (sequence, head) units, else 1 (smaller launches are bound by their fixed "
+                         "cost, and splitting them only adds launches)")
     ap.add_argument("--sync", choices=["run", "step"], default="run",
                     help="split schedule: 'step' forks at every token's first layer and joins at its last (a caller with one stream "
                          "of its own); 'run' lets the parts run free on their streams between host synchronisations (a caller "
                          "that runs its model on the parts of the batch in turn, each on its stream)")
+    ap.add_argument("--input-layers", type=int, default=0,
+                    help="generate the per-token inputs (q, k_new, v_new) for this many layers only and let layer l read those of layer "
+                         "l mod this (0 = every layer its own).  For configurations whose inputs for all layers and all tokens would not fit "
+                         "beside the cache (the large batch: 240 GB); the cache itself stays that of all layers")
     ap.add_argument("--no-one-stream", action="store_true", help="skip the one-stream figure reported beside a split headline")
-    ap.add_argument("--dense-only", action="store_true", help="time only the full-cache baseline kernel (for a counter run of its own)")
+    ap.add_argument("--only", choices=["dense", "prefill", "ceiling"], default="",
+                    help="run one of the side legs alone, without the decode measurement (for a profiler run of its own)")
+    ap.add_argument("--counter-reference", action="store_true",
+                    help="start with two launches of a plain copy kernel of exactly 1 GiB (ssd_bench_copy): the known traffic against "
+                         "which the profiler's FETCH_SIZE / WRITE_SIZE readings of the same run are scaled")
     ap.add_argument("--tune", type=str, default="", help="ch,wpb[,new_rows] launch-shape override of the attention kernel (test hook)")
     ap.add_argument("--separate", action="store_true",
                     help="three launches per layer (append, attend, compress) instead of the fused ssd_decode_step")
@@ -256,10 +266,13 @@ def main():
     assert max_k >= 1, "the workload is too short to time a step in steady state"
     passes = [max_k] * (K_steps // max_k) + ([K_steps % max_k] if K_steps % max_k else [])
     fused = not args.separate
-    n_streams = max(1, min(args.streams, ssd.SSD_MAX_SPLIT)) if fused and not args.rope else 1
+    want_streams = args.streams if args.streams > 0 else (2 if wl.B * wl.H >= 2048 else 1)
+    n_streams = max(1, min(want_streams, ssd.SSD_MAX_SPLIT)) if fused and not args.rope else 1
 
     t0 = time.time()
-    data = workload.generate(wl, device=dev, head_type=ht)
+    Ld = wl.L if not args.input_layers else min(wl.L, args.input_layers)       # layers that have inputs of their own
+    assert Ld == wl.L or (Ld % 2 == 0 and args.no_dense), "--input-layers: an even number (the head map alternates), and no dense leg"
+    data = workload.generate(wl, device=dev, head_type=ht, layers=range(Ld))
     torch.cuda.synchronize()
     t_gen = time.time() - t0
     sched = workload.compress_schedule(wl)
@@ -292,7 +305,7 @@ def main():
 
         # raw device addresses: a launch should cost the host a ctypes call, not four tensor slices
         stride_l = wl.B * wl.H * wl.d * (2 if wl.dtype == "bf16" else 4)
-        stride_p = wl.L * stride_l
+        stride_p = Ld * stride_l
         qb, kb, vb, ob = data["q"].data_ptr(), data["k"].data_ptr(), data["v"].data_ptr(), out.data_ptr()
         stream = torch.cuda.current_stream().cuda_stream
         L_ = ssd.lib
@@ -311,7 +324,7 @@ def main():
 
         def step_one(h, p, comp, ev, acct):
             for ci, (lb, le) in enumerate(calls):
-                o = p * stride_p + lb * stride_l
+                o = p * stride_p + (lb % Ld) * stride_l
                 if fused:
                     if acct is not None:            # what this launch has to move, from the live counters
                         n_, m_, c_, _ = cache.layer_state(lb)
@@ -455,11 +468,19 @@ def main():
         return res
 
     lpc = max(1, min(wl.L, args.layers_per_call))
-    if args.dense_only:
+    if args.counter_reference:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            assert ssd.lib.ssd_bench_copy(dst.data_ptr(), src.data_ptr(), 1 << 30, torch.cuda.current_stream().cuda_stream) == 0
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:4096], src[:4096]) and bool((dst[-4096:] == 1).all())
+        del src, dst
+    if args.only:
         head = None
-        result = {"metric": "visual tokens/sec per GPU (dense full-cache decode attn, all layers)", "config": {"workload": wl.name, "layers": wl.L}}
-        args.no_all_layers = args.no_ceiling = args.no_prefill = args.no_cpu = args.no_one_stream = True
-        args.no_dense = False
+        result = {"metric": "side leg '%s' alone" % args.only, "config": {"workload": wl.name, "layers": wl.L}}
+        args.no_all_layers = args.no_one_stream = args.no_cpu = True
+        args.no_dense, args.no_prefill, args.no_ceiling = args.only != "dense", args.only != "prefill", args.only != "ceiling"
     else:
         head = measure(lpc, with_events=not args.no_roofline, ns=n_streams)
     if head is not None:
@@ -473,7 +494,7 @@ def main():
             "config": {"workload": wl.name, "layers": wl.L, "prompts": wl.prompts, "sequences": wl.B, "heads": wl.H,
                        "head_dim": wl.d, "prompt_tokens": wl.n0, "visual_tokens": wl.N, "window": wl.W, "budget": wl.M,
                        "init_sink": wl.S, "recent": wl.R, "stage_cap": wl.C, "cadence": wl.cadence,
-                       "spatial_fraction": wl.spatial_frac, "layers_per_call": lpc, "replicas": R_rep,
+                       "spatial_fraction": wl.spatial_frac, "layers_per_call": lpc, "replicas": R_rep, "layers_with_own_inputs": Ld,
                        "step": "append + attend(+score accumulate) + compress, every layer",
                        "streams": n_streams,
                        "schedule": ("the batch dealt to %d streams (ssd_decode_step_split), every part's layers in order on its stream"
@@ -503,7 +524,7 @@ def main():
         if "roofline" in one:
             result["one_stream"]["roofline"] = one["roofline"]
 
-    if head is not None and not args.no_all_layers and lpc != wl.L:
+    if head is not None and not args.no_all_layers and lpc != wl.L and Ld == wl.L:
         alt = measure(wl.L, with_events=not args.no_roofline, ns=1)
         result["all_layers_one_launch"] = {
             "value": alt["value"], "unit": "tokens/s", "ms_per_step": alt["ms_per_step"],
@@ -518,6 +539,8 @@ def main():
     if not args.no_ceiling:
         n_units = wl.B * wl.H
         n_, m_, c_, _ = cache.layer_state(0)
+        if head is None:                                 # no decode has run: the counters a finished decode leaves behind
+            n_, m_, c_ = wl.n_total, min(wl.M, wl.n_total), wl.R
         rows_u = max(2, int(round((algorithmic_bytes_attend(wl, ht, range(1), (n_, m_, c_)) / n_units) / (2 * row_bytes(wl)))))
         unit_b = rows_u * 2 * row_bytes(wl)
         unit_b = (unit_b + 511) // 512 * 512
@@ -552,14 +575,14 @@ def main():
     # ---- prompt scoring (accumulated causal scores of the n0 prompt tokens), one launch per layer ------------
     if not args.no_prefill:
         n0 = wl.n0
-        Qp = [workload.dense_layout(data["q"][:n0, l:l + 1])[0].contiguous() for l in range(wl.L)]
-        Kp = [workload.dense_layout(data["k"][:n0, l:l + 1])[0].contiguous() for l in range(wl.L)]
+        Qp = [workload.dense_layout(data["q"][:n0, l:l + 1])[0].contiguous() for l in range(Ld)]
+        Kp = [workload.dense_layout(data["k"][:n0, l:l + 1])[0].contiguous() for l in range(Ld)]
         sc = torch.empty((wl.B, wl.H, n0), device=dev)
         units = wl.B * wl.H
 
         def prefill_pass():
             for l in range(wl.L):
-                ssd.ssd_prefill_scores(Qp[l], Kp[l], units, n0, wl.d, wl.dtype, sc)
+                ssd.ssd_prefill_scores(Qp[l % Ld], Kp[l % Ld], units, n0, wl.d, wl.dtype, sc)
         prefill_pass()
         torch.cuda.synchronize()
         reps = 5
@@ -607,7 +630,7 @@ def main():
         # whole raster decode through the dense kernel (its cost grows with n)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for p in range(n - reps if args.dense_only else wl.n0, n):        # a counter run of the dense kernel alone stays short
+        for p in range(n - reps if (args.only == "dense") else wl.n0, n):        # a counter run of the dense kernel alone stays short
             dense_step(p)
         torch.cuda.synchronize()
         dense_whole = time.perf_counter() - t0
@@ -633,7 +656,7 @@ def main():
         pairs = sorted(set((int(rng.integers(wl.L)), int(rng.integers(wl.B))) for _ in range(n_pairs)))
         host = {}
         for (l, b) in pairs:
-            host[(l, b)] = tuple(np.ascontiguousarray(data[x][:, l, b].float().cpu().numpy().transpose(1, 0, 2)) for x in "qkv")
+            host[(l, b)] = tuple(np.ascontiguousarray(data[x][:, l % Ld, b].float().cpu().numpy().transpose(1, 0, 2)) for x in "qkv")
         units = [(l, b, h) for (l, b) in pairs for h in range(wl.H)]
 
         def run_unit(i):

@@ -73,6 +73,13 @@ int ssd_dense_decode_attn_splits(const void *q, const void *K, const void *V, vo
 int ssd_bench_stream(void *buf, size_t unit_bytes, long long n_units, int rows_written,
                      void *sink, void *stream);
 
+/*
+ * Copy `bytes` (a multiple of 16) from src to dst with a plain kernel: a launch whose HBM reads and writes are
+ * known exactly, for scaling the profiler's byte counters (FETCH_SIZE, WRITE_SIZE) in the run that reads them.
+ *   dst, src : dev, 16-byte aligned, not overlapping
+ */
+int ssd_bench_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

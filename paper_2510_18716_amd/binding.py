@@ -81,6 +81,8 @@ lib.ssd_decode_step_rope.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp, _vp, 
 lib.ssd_decode_step_rope.restype = C.c_int
 lib.ssd_bench_stream.argtypes = [_vp, C.c_size_t, C.c_longlong, C.c_int, _vp, _vp]
 lib.ssd_bench_stream.restype = C.c_int
+lib.ssd_bench_copy.argtypes = [_vp, _vp, C.c_size_t, _vp]
+lib.ssd_bench_copy.restype = C.c_int
 lib.ssd_compress_kv.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp, C.c_int, _vp]
 lib.ssd_compress_kv.restype = C.c_int
 lib.ssd_prefill_scores.argtypes = [_vp, _vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, _vp, _vp]

@@ -38,9 +38,29 @@ __global__ __launch_bounds__(256) void bench_stream_kernel(uint4 *__restrict__ p
     if (ROWS_OUT == 0 && acc == 0x12345678u && lane == 0) sink[0] = row;   // keeps the loads alive
 }
 
+// Plain copy, 16 bytes per lane, grid-stride: a kernel whose HBM reads and writes are known exactly, against
+// which the profiler's byte counters are scaled.
+__global__ __launch_bounds__(256) void bench_copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, long long n_u4) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n_u4; i += (long long)gridDim.x * 256) dst[i] = src[i];
+}
+
 }  // namespace ssd
 
 using namespace ssd;
+
+extern "C" int ssd_bench_copy(void *dst, const void *src, size_t bytes, void *stream) {
+    clear_error();
+    if (!dst || !src || !aligned(dst, 16) || !aligned(src, 16)) return fail(SSD_ERR_INVALID_ARG, "dst and src must be given, 16-byte aligned");
+    if (bytes < 16 || bytes % 16 != 0) return fail(SSD_ERR_INVALID_ARG, "bytes must be a positive multiple of 16");
+    const long long n_u4 = (long long)(bytes / 16);
+    const long long want = (n_u4 + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 65536 ? want : 65536);
+    hipLaunchKernelGGL(bench_copy_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), static_cast<uint4 *>(dst),
+                       static_cast<const uint4 *>(src), n_u4);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "copy benchmark launch");
+    return SSD_OK;
+}
 
 extern "C" int ssd_bench_stream(void *buf, size_t unit_bytes, long long n_units, int rows_written, void *sink, void *stream) {
     clear_error();

@@ -9,6 +9,7 @@
 // output) in a caller-provided workspace and a second small kernel merges them.
 // Roofline: HBM; algorithmic bytes per unit = n * 2 * d * e.
 #include <mutex>
+#include <type_traits>
 
 #include "ssd_device.h"
 
@@ -33,6 +34,10 @@ struct DenseArgs {
     int far_last;       // last row index that counts as "far": n - 1 - w
     float qscale;
 };
+
+// passed to the kernels by value: plain data, 7 pointers and 10 four-byte fields, no padding
+static_assert(sizeof(DenseArgs) == 96 && alignof(DenseArgs) == 8 && std::is_trivially_copyable<DenseArgs>::value,
+              "DenseArgs is copied into the kernel-argument segment as it is");
 
 template <typename T, int D, int CH, int WPB>
 __global__ __launch_bounds__(WPB * 64) void dense_kernel(DenseArgs a) {

@@ -549,7 +549,8 @@ _SEEDS = range(*(int(x) for x in os.environ.get("SSD_RANDOM_SEEDS", "0:64").spli
 @pytest.mark.parametrize("seed", _SEEDS)
 def test_random_small_configurations(seed):
     """Seeded random shapes and policies (both dtypes and head dims, Algorithm 1 and 2, any cadence the row
-    buffer allows, budgets per layer or per head and the rotary step now and then), every unit compared at every step, fused and unfused."""
+    buffer allows, budgets per layer or per head, the rotary step or the split step now and then), every unit compared at
+    every step, fused and unfused."""
     r = np.random.default_rng(1000 + seed)
     d = int(r.choice([64, 128]))
     dtype = str(r.choice(["bf16", "f32"]))
@@ -570,8 +571,9 @@ def test_random_small_configurations(seed):
     if r.random() < 0.35:         # budgets per head instead (drawn last: the other cases keep their draws)
         wl = wl.replace(W_layers=None, M_layers=None, head_budget=tuple(tuple(int(x) for x in r.integers(1, 40, H)) for _ in range(L)))
     rope = int(r.choice([0, 0, ssd.SSD_ROPE_HALF, ssd.SSD_ROPE_INTERLEAVED]))    # the fused leg, now and then with rotary embedding
+    split = 0 if rope else int(r.choice([0, 0, 2, 3]))                           # ... or dealt to several streams (drawn last)
     _full_compare(wl, lpc=lpc, fused=False)
-    _full_compare(wl, lpc=lpc, fused=True, rope=rope)
+    _full_compare(wl, lpc=lpc, fused=True, rope=rope, split=split)
 
 
 @pytest.mark.parametrize("seed", range(12))

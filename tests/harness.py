@@ -32,6 +32,15 @@ from paper_2510_18716_amd.binding import make_config
 
 GAP_MARGIN = 1e-4
 
+# The rotary step in bf16.  The kernel rotates k in fp32 (one product, one fused multiply-add) and rounds to bf16; the oracle
+# rotates in double and rounds to bf16.  Where the exact value lies within 2^-24 (relative) of a bf16 rounding boundary --
+# about 3 elements in 10^5 -- the two stored keys differ by one bf16 ulp, 2^-8 of the element.  The logit of that row then
+# differs by scale * |q_i| * |k_i| * 2^-8, at most 0.125 * 3 * 3 * 2^-8 = 4.4e-3 for entries within three standard deviations
+# (d = 64; 3.1e-3 at d = 128), and so does the row's probability, relatively, at every step it is attended, hence its
+# accumulated score.  Scores and near-tie margins of such runs are therefore compared at 5e-3; outputs keep the bf16
+# tolerance, index sets stay exact outside the margin, and the own-score check applies unchanged.
+ROPE_BF16_MARGIN = 5e-3
+
 # |gpu - ref| <= atol + rtol |ref|.
 #   bf16: the target stated for the bf16 path (the output is rounded to bf16: half an ulp at |o| < 8 is 1.6e-2).
 #   f32 : the error model of the kernel's arithmetic.  Logits: d <= 128 products accumulated in fp32,
@@ -235,7 +244,7 @@ def spatial_positions(wl: workload.Workload, n: int, n_c: Optional[int] = None, 
     return sorted(set(range(min(wl.S, n))) | set(range(max(wl.S, ref - wl.W_of(layer, head)), n)))
 
 
-def compare_unit_sets(wl, ht, unit, layer_index, exports, heavy_log, gap_log, schedule, p_begin: int = 0):
+def compare_unit_sets(wl, ht, unit, layer_index, exports, heavy_log, gap_log, schedule, p_begin: int = 0, margin: float = GAP_MARGIN):
     """Exact comparison of the exported index tables of one unit with the oracle's log (row p - p_begin = step
     p) at every exported step.  Returns None, or -- for a heavy set that differs because of a permitted near-tie
     -- the pair (s, p): s the compression step whose oracle margin excuses it, p the exported step at which the
@@ -258,7 +267,7 @@ def compare_unit_sets(wl, ht, unit, layer_index, exports, heavy_log, gap_log, sc
         heavy_ref = [int(x) for x in heavy_log[p - p_begin] if x >= 0]
         if heavy_gpu != heavy_ref:
             # allowed only if a cut since the last agreeing export was a near-tie in the oracle
-            near = [s for s in range(agreed + 1, p + 1) if schedule[s] and 0 <= gap_log[s - p_begin] <= GAP_MARGIN]
+            near = [s for s in range(agreed + 1, p + 1) if schedule[s] and 0 <= gap_log[s - p_begin] <= margin]
             assert near, ("heavy set differs above the tie margin", unit, p, heavy_gpu, heavy_ref)
             return near[0], p
         agreed = p

@@ -448,6 +448,14 @@ def test_stream_benchmark_rejects_bad_arguments_before_any_launch():
         assert ssd.ssd_last_error() != ""
 
 
+def test_copy_benchmark_rejects_bad_arguments_before_any_launch():
+    lib = ssd.lib
+    for dst, src, nbytes in [(None, FAKE, 1024), (FAKE, None, 1024), (FAKE + 8, FAKE, 1024), (FAKE, FAKE + 4, 1024), (FAKE, FAKE, 0),
+                             (FAKE, FAKE, 1000)]:
+        assert lib.ssd_bench_copy(dst, src, nbytes, None) == ssd.SSD_ERR_INVALID_ARG, (dst, src, nbytes)
+        assert ssd.ssd_last_error() != ""
+
+
 def test_package_without_its_library_fails_loudly(tmp_path):
     """No CPU or PyTorch fallback: a copy of the package without the built library, on a machine where it
     cannot be built either, must refuse to import."""

@@ -229,3 +229,14 @@ def test_stream_benchmark_reads_everything_and_writes_only_its_two_rows():
     assert not changed[n_units].any()                       # nothing behind the last unit
     assert not changed[:, :, 1:].any()                      # only row 0 of each plane
     assert changed[:n_units, :, 0].float().mean() > 0.9     # and that one is written (a random row rarely stays equal)
+
+
+def test_copy_benchmark_copies_exactly_what_it_says():
+    # the kernel whose known traffic scales the profiler's byte counters: dst = src over `bytes`, nothing beyond
+    n = (1 << 20) + 16 * 37                                  # not a multiple of the workgroup's stride
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.full((n + 256,), 7, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    assert ssd.lib.ssd_bench_copy(dst.data_ptr(), src.data_ptr(), n, stream) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n], src) and bool((dst[n:] == 7).all())

@@ -301,7 +301,7 @@ def main():
         stream_arr = ssd.stream_array([torch.cuda.current_stream()] + side_streams[: ns - 1])
         FORK, JOIN = ssd.SSD_SPLIT_FORK, ssd.SSD_SPLIT_JOIN
         sync_step = args.sync == "step"          # else: the parts meet only at the host's device-wide synchronisations
-        n_parts = len(range(0, wl.B, (-(-wl.B // ns) + 1) // 2 * 2))          # parts that are not empty
+        n_parts = cache.split_plan(lpc, ns)[1]                                  # launches per call: the library's cut of the batch
 
         # raw device addresses: a launch should cost the host a ctypes call, not four tensor slices
         stride_l = wl.B * wl.H * wl.d * (2 if wl.dtype == "bf16" else 4)

@@ -301,10 +301,14 @@ int ssd_decode_step(ssd_cache *cache, int layer_begin, int layer_end, const void
  * between layers.  Results are those of ssd_decode_step, bit for bit.
  *   streams   : host array of n_streams distinct hipStream_t, all of the
  *               default priority; n_streams in 1..SSD_MAX_SPLIT
- *   Part i = sequences [i * P, min(B, (i + 1) * P)), P = B / n_streams rounded
- *   up to an even number (a prompt's two sequences stay together); its work is
- *   enqueued on streams[i] only, and the rows of q, k_new, v_new it reads and
- *   of out it writes are ordered with respect to that stream only.
+ *   The batch is cut into n_parts consecutive parts of P sequences (P even: a prompt's two sequences stay
+ *   together; the last part takes what is left), part i = sequences [i * P, min(B, (i + 1) * P)).  Part i's work
+ *   is enqueued on streams[i mod n_streams] only, and the rows of q, k_new, v_new it reads and of out it writes
+ *   are ordered with respect to that stream only.  The library picks P: one part per stream, or more (at most
+ *   four per stream) when a part would otherwise exceed about 4096 (sequence, head, layer) units per launch --
+ *   launches of about one resident round of wavefronts write their dirty lines back in one burst at their end,
+ *   larger ones spill them into the read stream.  ssd_decode_step_split_plan returns P and n_parts for a call
+ *   that covers layers_per_call layers (they depend on the cache's shape, that number and n_streams only).
  *   sync      : SSD_SPLIT_FORK  -- before anything is enqueued, streams[1..]
  *               are made to wait for what streams[0] holds so far;
  *               SSD_SPLIT_JOIN  -- afterwards streams[0] is made to wait for
@@ -324,6 +328,8 @@ int ssd_decode_step_split(ssd_cache *cache, int layer_begin, int layer_end, cons
                           const void *k_new, const void *v_new, void *out,
                           int accumulate_scores, int compress,
                           void *const *streams, int n_streams, int sync);
+int ssd_decode_step_split_plan(const ssd_cache *cache, int layers_per_call, int n_streams,
+                               int32_t *part_seqs, int32_t *n_parts);   /* either output may be NULL */
 
 /*
  * The same step with rotary position embedding (Su et al., "RoFormer") applied

@@ -112,6 +112,8 @@ lib.ssd_dense_decode_attn_splits.argtypes = [_vp, _vp, _vp, _vp, C.c_int, C.c_in
 lib.ssd_dense_decode_attn_splits.restype = C.c_int
 lib.ssd_decode_step_split.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp, _vp, C.c_int, C.c_int, C.POINTER(_vp), C.c_int, C.c_int]
 lib.ssd_decode_step_split.restype = C.c_int
+lib.ssd_decode_step_split_plan.argtypes = [_vp, C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+lib.ssd_decode_step_split_plan.restype = C.c_int
 
 
 class SsdError(RuntimeError):
@@ -259,6 +261,12 @@ class Cache:
     def set_launch_shape(self, ch: int = 0, wpb: int = 0, new_rows: int = 0):
         """Test / sweep hook: override the attention launch shape of this cache ((0, 0, 0) = the library's choice)."""
         _check(lib.ssd_cache_set_launch_shape(self._h, ch, wpb, new_rows), "ssd_cache_set_launch_shape")
+
+    def split_plan(self, layers_per_call: int, n_streams: int):
+        """(sequences per part, number of parts) of ssd_decode_step_split for a call over that many layers."""
+        p, n = C.c_int32(0), C.c_int32(0)
+        _check(lib.ssd_decode_step_split_plan(self._h, layers_per_call, n_streams, C.byref(p), C.byref(n)), "ssd_decode_step_split_plan")
+        return p.value, n.value
 
     def layer_state(self, layer: int):
         out = (C.c_int32 * 4)()

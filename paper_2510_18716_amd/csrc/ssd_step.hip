@@ -573,21 +573,45 @@ struct Rope {
     int layout;
 };
 
-// Sequences per part when the batch is dealt to n streams: equal parts of an even number of sequences (the
-// two sequences of a prompt under classifier-free guidance stay together), the last part taking what is left.
-static int part_size(int B, int n) {
-    const int per = (B + n - 1) / n;
-    return (per + 1) / 2 * 2;
+// How a split call cuts the batch: consecutive parts of `seqs` sequences (an even number: the two sequences of a
+// prompt under classifier-free guidance stay together; the last part takes what is left), part i going to stream
+// i mod n_streams.  At least one part per stream; more when a part's launch would exceed about one resident
+// round of waves (4096 units over the layers of the call): launches of that size keep their dirty lines in L2
+// until they end and write them back in one burst, larger ones spill them into the read stream all along
+// (large batch, 512 sequences on two streams: 2.996 ms per step with 2 parts, 2.804 with 4, 2.796 with 8).  Small
+// launches pay their fixed cost instead (7B shape, 128 sequences: 0.720 / 0.860 / 1.188 ms with 2 / 4 / 8 parts),
+// so never more than four parts per stream.
+struct SplitPlan {
+    int seqs;      // sequences per part
+    int parts;
+};
+static constexpr int SPLIT_UNITS_PER_LAUNCH = 4096;
+static SplitPlan split_plan(int B, int H, int layers, int n_streams) {
+    auto even = [](int x) { return (x + 1) / 2 * 2; };
+    int seqs = even((B + n_streams - 1) / n_streams);                      // one part per stream
+    const long long per_seq = (long long)H * layers;
+    int fit = (int)(SPLIT_UNITS_PER_LAUNCH / per_seq) / 2 * 2;             // sequences whose units fill one resident round
+    if (fit < 2) fit = 2;
+    if (n_streams > 1 && fit < seqs) seqs = fit;
+    const int floor_seqs = even((B + 4 * n_streams - 1) / (4 * n_streams));  // at most four parts per stream
+    if (seqs < floor_seqs) seqs = floor_seqs;
+    SplitPlan p;
+    p.seqs = seqs;
+    p.parts = (B + seqs - 1) / seqs;
+    return p;
 }
 
 // Shared by ssd_decode_attn (k_new == NULL, compress == 0), ssd_decode_step, ssd_decode_step_rope and
-// ssd_decode_step_split.  streams[0..n_streams): part i of the batch is enqueued on streams[i].
+// ssd_decode_step_split.  streams[0..n_streams): part i of the batch is enqueued on streams[i mod n_streams].
 static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new, const void *v_new,
                     void *out, int accumulate, int compress, void *const *streams, int n_streams, const char *what,
                     Rope rope = {nullptr, nullptr, 0}) {
     const ssd_config &cf = cache->cfg;
     const bool fused = k_new != nullptr;
-    const int Bp = part_size(cf.n_seqs, n_streams);
+    // one plan per call, from the layers the call covers (its launches may cover fewer: runs of layers in one state)
+    const int span = layer_end - layer_begin;
+    const SplitPlan plan = split_plan(cf.n_seqs, cf.n_heads, span < LMAX ? span : LMAX, n_streams);
+    const int Bp = plan.seqs;
     for (int lb = layer_begin; lb < layer_end;) {
         const int le = same_state_run(cache, lb, layer_end);
         const LayerState before = cache->st[lb];
@@ -634,8 +658,8 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
                 mth = cache->ldesc[l].n_se > mth ? cache->ldesc[l].n_se : mth;
             }
             a.sem_first = a.se.total + (fused ? 1 : 0) >= a.sp.total + (fused ? 1 : 0) ? 1 : 0;
-            for (int part = 0; part < n_streams && part * Bp < cf.n_seqs; ++part) {
-                hipStream_t s = static_cast<hipStream_t>(streams[part]);
+            for (int part = 0; part < plan.parts; ++part) {
+                hipStream_t s = static_cast<hipStream_t>(streams[part % n_streams]);
                 a.seq_off = part * Bp;
                 const int Bn = cf.n_seqs - a.seq_off < Bp ? cf.n_seqs - a.seq_off : Bp;
                 const bool hd = heads_differ(cache, lb);
@@ -745,6 +769,19 @@ extern "C" int ssd_decode_step_split(ssd_cache *cache, int layer_begin, int laye
             if (e != hipSuccess) return hip_fail(e, "join of the split step");
         }
     }
+    return SSD_OK;
+}
+
+extern "C" int ssd_decode_step_split_plan(const ssd_cache *cache, int layers_per_call, int n_streams, int32_t *part_seqs,
+                                          int32_t *n_parts) {
+    clear_error();
+    if (!cache) return fail(SSD_ERR_INVALID_ARG, "cache is NULL");
+    if (layers_per_call < 1 || layers_per_call > cache->cfg.n_layers)
+        return fail(SSD_ERR_INVALID_ARG, "layers_per_call=%d outside 1..%d", layers_per_call, cache->cfg.n_layers);
+    if (n_streams < 1 || n_streams > SSD_MAX_SPLIT) return fail(SSD_ERR_INVALID_ARG, "n_streams=%d outside 1..%d", n_streams, SSD_MAX_SPLIT);
+    const SplitPlan p = split_plan(cache->cfg.n_seqs, cache->cfg.n_heads, layers_per_call < LMAX ? layers_per_call : LMAX, n_streams);
+    if (part_seqs) *part_seqs = p.seqs;
+    if (n_parts) *n_parts = p.parts;
     return SSD_OK;
 }
 

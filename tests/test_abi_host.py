@@ -531,6 +531,31 @@ def test_split_step_checks_its_stream_list_and_moves_the_counters_once():
     assert e.value.code == ssd.SSD_ERR_STAGE_OVERFLOW
 
 
+def test_split_plan_keeps_prompt_pairs_together_and_launches_near_one_resident_round():
+    def plan(B, H, L, layers, n):
+        c = ssd.Cache(make_config(L, B, H, 128, "bf16", 8, 1, 8, 1, 2), _ht(L, H), device=None)
+        return c.split_plan(layers, n)
+    assert plan(128, 32, 30, 1, 1) == (128, 1)                # one stream: one part
+    assert plan(128, 32, 30, 1, 2) == (64, 2)                 # 7B shape: 2048 units per launch, one part per stream
+    assert plan(128, 32, 30, 1, 4) == (32, 4)
+    assert plan(512, 32, 30, 1, 2) == (128, 4)                # large batch: 4096 units per launch, two parts per stream
+    assert plan(512, 32, 30, 1, 1) == (512, 1)
+    assert plan(512, 32, 30, 30, 2) == (64, 8)                # many layers per call: never more than four parts per stream
+    assert plan(32, 16, 24, 1, 2) == (16, 2)
+    assert plan(10, 4, 2, 1, 3) == (4, 3)                     # 4 + 4 + 2
+    assert plan(10, 4, 2, 1, 4) == (4, 3)                     # fewer parts than streams when pairs run out
+    assert plan(3, 4, 2, 1, 2) == (2, 2)
+    for B, H, L, layers, n in [(2, 1, 1, 1, 4), (65534, 2, 1, 1, 3), (100, 128, 3, 3, 2), (6, 128, 40, 32, 4)]:
+        P, parts = plan(B, H, L, layers, n)
+        assert P % 2 == 0 and P >= 2 and (parts - 1) * P < B <= parts * P and parts <= 4 * n
+    c = ssd.Cache(make_config(2, 4, 4, 64, "f32", 5, 1, 4, 1, 3), _ht(2, 4), device=None)
+    import ctypes as C
+    for layers, n in [(0, 1), (3, 1), (1, 0), (1, ssd.SSD_MAX_SPLIT + 1)]:
+        assert ssd.lib.ssd_decode_step_split_plan(c.handle, layers, n, None, None) == ssd.SSD_ERR_INVALID_ARG
+    assert ssd.lib.ssd_decode_step_split_plan(None, 1, 1, None, None) == ssd.SSD_ERR_INVALID_ARG
+    assert ssd.lib.ssd_decode_step_split_plan(c.handle, 1, 2, None, None) == ssd.SSD_OK
+
+
 def test_launch_shape_hook_accepts_only_shapes_the_library_has():
     cfg = make_config(1, 2, 4, 64, "f32", 5, 1, 4, 1, 3)
     a = ssd.Cache(cfg, _ht(1, 4), device=None)

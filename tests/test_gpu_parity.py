@@ -437,11 +437,16 @@ def test_split_step_on_several_streams_equals_the_one_stream_step(n_streams):
              workload.config(2).replace(name="cfg2-split-uneven", L=2, prompts=5, grid_h=4),
              workload.Workload("split-long-buffer", L=2, prompts=3, H=4, d=64, dtype="f32", n0=6, grid_h=40, grid_w=40, W=30,
                                M=900, S=1, R=4, C=400, cadence=390, seed=61, plain=True),
+             # 40 sequences x 128 heads x 3 layers per call: more parts than streams (4 parts of 10 sequences on 2 streams)
+             workload.Workload("split-many-parts", L=3, prompts=20, H=128, d=64, dtype="bf16", n0=3, grid_h=4, grid_w=5, W=7, M=5,
+                               S=1, R=1, C=3, cadence=2, seed=67, plain=True),
              workload.Workload("split-per-head-alg2", L=2, prompts=3, H=6, d=128, dtype="bf16", n0=7, grid_h=6, grid_w=10, W=99,
                                M=99, S=1, R=0, C=5, cadence=5, seed=63, plain=True, alg2=True,
                                head_budget=((24, 5, 1, 7, 40, 3), (9, 9, 30, 2, 1, 17)))]
     for wl in cases:
         say("split case", wl.name, "B", wl.B, "streams", n_streams)
+        if wl.name == "split-many-parts" and n_streams == 2:
+            assert make_cache(wl, workload.head_map(wl)).split_plan(wl.L, 2) == (10, 4)
         ht = workload.head_map(wl)
         data = workload.generate(wl, device="cuda", head_type=ht)
         sched = workload.compress_schedule(wl)

@@ -483,8 +483,8 @@ def test_config3_launch_shape_plain_inputs_sampled_units():
     _full_compare(wl.replace(name="cfg3-plain-split"), lpc=1, k_units=64, export_every=128, device_gen=True, fused=True, split=2)
 
 
-@pytest.mark.parametrize("frac,W,M", [(0.25, 32, 128), (0.5, 64, 64), (0.75, 128, 32)])
-def test_config5_large_batch_online_classification_then_decode(frac, W, M):
+@pytest.mark.parametrize("frac,W,M,split", [(0.25, 32, 128, 0), (0.5, 64, 64, 2), (0.75, 128, 32, 2)])
+def test_config5_large_batch_online_classification_then_decode(frac, W, M, split):
     """Large-batch shape (B = 512, 32 heads) with the head types found online: a dense profiling run on a
     16-sequence sub-batch feeds ssd_classify_heads, the resulting table drives the compressed decode of the
     whole batch.  Two layers keep the test short; a per-layer launch has the full configuration's shape."""
@@ -529,7 +529,10 @@ def test_config5_large_batch_online_classification_then_decode(frac, W, M):
     schedule = workload.compress_schedule(wl)
     units = sample_units(wl, ht, 40, seed=2)
     steps = sorted(set(range(0, wl.n_total, 160)) | {wl.n_total - 1})
-    outs, exports, _ = gpu_decode(wl, data, ht, schedule, units, layers_per_call=1, export_steps=steps, fused=True)
+    # split = 2: the launch configuration bench.py times on this shape (four parts of 128 sequences on two streams)
+    outs, exports, cache = gpu_decode(wl, data, ht, schedule, units, layers_per_call=1, export_steps=steps, fused=True, split=split)
+    if split:
+        assert cache.split_plan(1, split) == (128, 4)
     layers = sorted(set(l for (l, _, _) in units))
     worst, near_ties, t3 = 0.0, 0, 0
     for ui, unit in enumerate(units):

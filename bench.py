@@ -267,7 +267,7 @@ def main():
     passes = [max_k] * (K_steps // max_k) + ([K_steps % max_k] if K_steps % max_k else [])
     fused = not args.separate
     want_streams = args.streams if args.streams > 0 else (2 if wl.B * wl.H >= 2048 else 1)
-    n_streams = max(1, min(want_streams, ssd.SSD_MAX_SPLIT)) if fused and not args.rope else 1
+    n_streams = max(1, min(want_streams, ssd.SSD_MAX_SPLIT)) if fused else 1
 
     t0 = time.time()
     Ld = wl.L if not args.input_layers else min(wl.L, args.input_layers)       # layers that have inputs of their own
@@ -330,7 +330,11 @@ def main():
                         n_, m_, c_, _ = cache.layer_state(lb)
                         acct.append(algorithmic_bytes_attend(wl, ht, range(lb, le), (n_ + 1, m_, c_ + 1)) +
                                     algorithmic_bytes_append(wl, ht, range(lb, le)))
-                    if args.rope:
+                    if args.rope and ns > 1:
+                        rc = L_.ssd_decode_step_split_rope(h, lb, le, qb + o, kb + o, vb + o, ob + lb * stride_l, acc_i, comp,
+                                                           cos_p + p * wl.d * 2, sin_p + p * wl.d * 2, args.rope, stream_arr, ns,
+                                                           ((FORK if ci == 0 else 0) | (JOIN if ci == len(calls) - 1 else 0)) if sync_step else 0)
+                    elif args.rope:
                         rc = L_.ssd_decode_step_rope(h, lb, le, qb + o, kb + o, vb + o, ob + lb * stride_l, acc_i, comp,
                                                      cos_p + p * wl.d * 2, sin_p + p * wl.d * 2, args.rope, stream)
                     elif ns > 1:
@@ -445,7 +449,8 @@ def main():
             durs = [e[2 * ci].elapsed_time(e[2 * ci + 1]) for e in evs for ci in range(len(calls))]
         avg_ms = float(np.mean(durs))
         achieved = bytes_launch / 1e9 / (avg_ms / 1e3)
-        entry = ("ssd_decode_step_rope" if args.rope else "ssd_decode_step_split" if ns > 1 else "ssd_decode_step") if fused else "ssd_decode_attn"
+        entry = (("ssd_decode_step_split_rope" if ns > 1 else "ssd_decode_step_rope") if args.rope else
+                 "ssd_decode_step_split" if ns > 1 else "ssd_decode_step") if fused else "ssd_decode_attn"
         traffic = measured_traffic(wl.name, entry, ns, lpc)
         res["roofline"] = {
             "bound": "hbm",
@@ -484,7 +489,8 @@ def main():
     else:
         head = measure(lpc, with_events=not args.no_roofline, ns=n_streams)
     if head is not None:
-        entry = ("ssd_decode_step_rope" if args.rope else "ssd_decode_step_split" if n_streams > 1 else "ssd_decode_step") if fused \
+        entry = (("ssd_decode_step_split_rope" if n_streams > 1 else "ssd_decode_step_rope") if args.rope else
+                 "ssd_decode_step_split" if n_streams > 1 else "ssd_decode_step") if fused \
             else "ssd_append_token, ssd_decode_attn, ssd_compress_kv"
         result = {
             "metric": "visual tokens/sec per GPU (compressed decode attn, all layers)",
@@ -519,7 +525,8 @@ def main():
     if head is not None and n_streams > 1 and not args.no_one_stream:
         one = measure(lpc, with_events=not args.no_roofline, ns=1)
         result["one_stream"] = {"value": one["value"], "unit": "tokens/s", "ms_per_step": one["ms_per_step"],
-                                "launches_per_step": one["launches_per_step"], "entry_points": "ssd_decode_step",
+                                "launches_per_step": one["launches_per_step"],
+                                "entry_points": "ssd_decode_step_rope" if args.rope else "ssd_decode_step",
                                 "whole_step_GBps": one["algorithmic_GB_per_step"] / (one["ms_per_step"] / 1e3)}
         if "roofline" in one:
             result["one_stream"]["roofline"] = one["roofline"]

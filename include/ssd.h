@@ -354,6 +354,11 @@ int ssd_decode_step_rope(ssd_cache *cache, int layer_begin, int layer_end, const
                          const void *k_new, const void *v_new, void *out, int accumulate_scores,
                          int compress, const float *cos, const float *sin, int rope_layout,
                          void *stream);
+/* ssd_decode_step_rope with the batch dealt to several streams: the stream arguments of ssd_decode_step_split. */
+int ssd_decode_step_split_rope(ssd_cache *cache, int layer_begin, int layer_end, const void *q,
+                               const void *k_new, const void *v_new, void *out, int accumulate_scores,
+                               int compress, const float *cos, const float *sin, int rope_layout,
+                               void *const *streams, int n_streams, int sync);
 
 /* ---- exports for tests and benchmarks (not steps of the method) ------------ */
 

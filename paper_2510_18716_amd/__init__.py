@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     Cache, SsdConfig, SsdError, lib, lib_path,
     ssd_append_token, ssd_cache_bytes, ssd_cfg_mix, ssd_classify_heads, ssd_compress_kv, ssd_decode_attn, ssd_decode_step,
     SSD_ROPE_HALF, SSD_ROPE_INTERLEAVED, ssd_decode_step_rope,
-    SSD_MAX_SPLIT, SSD_SPLIT_FORK, SSD_SPLIT_JOIN, ssd_decode_step_split, stream_array,
+    SSD_MAX_SPLIT, SSD_SPLIT_FORK, SSD_SPLIT_JOIN, ssd_decode_step_split, ssd_decode_step_split_rope, stream_array,
     ssd_dense_decode_attn, ssd_dense_decode_attn_static, SSD_DENSE_STATIC_SCRATCH_BYTES, ssd_dense_workspace_bytes, ssd_last_error, ssd_prefill_scores, ssd_version,
 )

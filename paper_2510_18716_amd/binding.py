@@ -112,6 +112,9 @@ lib.ssd_dense_decode_attn_splits.argtypes = [_vp, _vp, _vp, _vp, C.c_int, C.c_in
 lib.ssd_dense_decode_attn_splits.restype = C.c_int
 lib.ssd_decode_step_split.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp, _vp, C.c_int, C.c_int, C.POINTER(_vp), C.c_int, C.c_int]
 lib.ssd_decode_step_split.restype = C.c_int
+lib.ssd_decode_step_split_rope.argtypes = [_vp, C.c_int, C.c_int, _vp, _vp, _vp, _vp, C.c_int, C.c_int, _vp, _vp, C.c_int,
+                                           C.POINTER(_vp), C.c_int, C.c_int]
+lib.ssd_decode_step_split_rope.restype = C.c_int
 lib.ssd_decode_step_split_plan.argtypes = [_vp, C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
 lib.ssd_decode_step_split_plan.restype = C.c_int
 
@@ -352,6 +355,14 @@ def ssd_decode_step_split(cache: Cache, layer_begin: int, layer_end: int, q, k_n
 
 
 SSD_ROPE_HALF, SSD_ROPE_INTERLEAVED = 1, 2
+
+
+def ssd_decode_step_split_rope(cache: Cache, layer_begin: int, layer_end: int, q, k_new, v_new, out, cos, sin, rope_layout: int,
+                               streams, sync: int = 0, accumulate_scores: bool = True, compress: bool = True) -> None:
+    arr = streams if isinstance(streams, C.Array) else stream_array(streams)
+    _check(lib.ssd_decode_step_split_rope(cache.handle, layer_begin, layer_end, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                          int(bool(accumulate_scores)), int(bool(compress)), _ptr(cos), _ptr(sin), int(rope_layout),
+                                          arr, len(arr), int(sync)), "ssd_decode_step_split_rope")
 
 
 def ssd_decode_step_rope(cache: Cache, layer_begin: int, layer_end: int, q, k_new, v_new, out, cos, sin, rope_layout: int,

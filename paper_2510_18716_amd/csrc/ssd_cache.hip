@@ -521,6 +521,6 @@ int ssd_cache_export(ssd_cache *cache, int layer, int32_t *pos, int32_t *count, 
 
 const char *ssd_last_error(void) { return g_err; }
 
-int ssd_version(void) { return 100; }
+int ssd_version(void) { return 200; }
 
 }  // extern "C"

@@ -736,12 +736,9 @@ extern "C" int ssd_decode_step(ssd_cache *cache, int layer_begin, int layer_end,
     return run_step(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, &stream, 1, "decode step launch");
 }
 
-extern "C" int ssd_decode_step_split(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new,
-                                     const void *v_new, void *out, int accumulate_scores, int compress,
-                                     void *const *streams, int n_streams, int sync) {
-    clear_error();
-    int rc = check_step_args(cache, layer_begin, layer_end, q, k_new, v_new, out);
-    if (rc != SSD_OK) return rc;
+// Common body of the split entry points: stream list and sync checks, fork, the launches, join.
+static int run_split(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new, const void *v_new, void *out,
+                     int accumulate_scores, int compress, void *const *streams, int n_streams, int sync, const char *what, Rope rope) {
     if (!streams || n_streams < 1 || n_streams > SSD_MAX_SPLIT)
         return fail(SSD_ERR_INVALID_ARG, "streams is NULL or n_streams=%d outside 1..%d", n_streams, SSD_MAX_SPLIT);
     if (sync & ~(SSD_SPLIT_FORK | SSD_SPLIT_JOIN)) return fail(SSD_ERR_INVALID_ARG, "sync=%d has unknown bits", sync);
@@ -750,7 +747,7 @@ extern "C" int ssd_decode_step_split(ssd_cache *cache, int layer_begin, int laye
             if (streams[i] == streams[j]) return fail(SSD_ERR_INVALID_ARG, "streams[%d] and streams[%d] are the same stream", j, i);
     const bool live = cache->launch_enabled && n_streams > 1;
     if (live && sync) {
-        rc = ensure_events(cache);
+        const int rc = ensure_events(cache);
         if (rc != SSD_OK) return rc;
     }
     if (live && (sync & SSD_SPLIT_FORK)) {
@@ -759,7 +756,7 @@ extern "C" int ssd_decode_step_split(ssd_cache *cache, int layer_begin, int laye
         for (int i = 1; i < n_streams && e == hipSuccess; ++i) e = hipStreamWaitEvent(static_cast<hipStream_t>(streams[i]), cache->ev_fork, 0);
         if (e != hipSuccess) return hip_fail(e, "fork of the split step");
     }
-    rc = run_step(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, streams, n_streams, "split decode step launch");
+    const int rc = run_step(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, streams, n_streams, what, rope);
     if (rc != SSD_OK) return rc;
     if (live && (sync & SSD_SPLIT_JOIN)) {
         // streams[0] goes on only when every part is done
@@ -770,6 +767,36 @@ extern "C" int ssd_decode_step_split(ssd_cache *cache, int layer_begin, int laye
         }
     }
     return SSD_OK;
+}
+
+static int check_rope_args(const float *cos_p, const float *sin_p, int rope_layout) {
+    if (rope_layout != SSD_ROPE_HALF && rope_layout != SSD_ROPE_INTERLEAVED)
+        return fail(SSD_ERR_INVALID_ARG, "rope_layout=%d is neither SSD_ROPE_HALF nor SSD_ROPE_INTERLEAVED", rope_layout);
+    if (!cos_p || !sin_p || !aligned(cos_p, 16) || !aligned(sin_p, 16))
+        return fail(SSD_ERR_INVALID_ARG, "cos / sin must be given and 16-byte aligned");
+    return SSD_OK;
+}
+
+extern "C" int ssd_decode_step_split(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new,
+                                     const void *v_new, void *out, int accumulate_scores, int compress,
+                                     void *const *streams, int n_streams, int sync) {
+    clear_error();
+    const int rc = check_step_args(cache, layer_begin, layer_end, q, k_new, v_new, out);
+    if (rc != SSD_OK) return rc;
+    return run_split(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, streams, n_streams, sync,
+                     "split decode step launch", Rope{nullptr, nullptr, 0});
+}
+
+extern "C" int ssd_decode_step_split_rope(ssd_cache *cache, int layer_begin, int layer_end, const void *q, const void *k_new,
+                                          const void *v_new, void *out, int accumulate_scores, int compress, const float *cos_p,
+                                          const float *sin_p, int rope_layout, void *const *streams, int n_streams, int sync) {
+    clear_error();
+    int rc = check_step_args(cache, layer_begin, layer_end, q, k_new, v_new, out);
+    if (rc != SSD_OK) return rc;
+    rc = check_rope_args(cos_p, sin_p, rope_layout);
+    if (rc != SSD_OK) return rc;
+    return run_split(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, streams, n_streams, sync,
+                     "split decode step launch (rotary)", Rope{cos_p, sin_p, rope_layout});
 }
 
 extern "C" int ssd_decode_step_split_plan(const ssd_cache *cache, int layers_per_call, int n_streams, int32_t *part_seqs,
@@ -789,12 +816,10 @@ extern "C" int ssd_decode_step_rope(ssd_cache *cache, int layer_begin, int layer
                                     const void *v_new, void *out, int accumulate_scores, int compress, const float *cos_p,
                                     const float *sin_p, int rope_layout, void *stream) {
     clear_error();
-    const int rc = check_step_args(cache, layer_begin, layer_end, q, k_new, v_new, out);
+    int rc = check_step_args(cache, layer_begin, layer_end, q, k_new, v_new, out);
     if (rc != SSD_OK) return rc;
-    if (rope_layout != SSD_ROPE_HALF && rope_layout != SSD_ROPE_INTERLEAVED)
-        return fail(SSD_ERR_INVALID_ARG, "rope_layout=%d is neither SSD_ROPE_HALF nor SSD_ROPE_INTERLEAVED", rope_layout);
-    if (!cos_p || !sin_p || !aligned(cos_p, 16) || !aligned(sin_p, 16))
-        return fail(SSD_ERR_INVALID_ARG, "cos / sin must be given and 16-byte aligned");
+    rc = check_rope_args(cos_p, sin_p, rope_layout);
+    if (rc != SSD_OK) return rc;
     return run_step(cache, layer_begin, layer_end, q, k_new, v_new, out, accumulate_scores, compress, &stream, 1,
                     "decode step launch (rotary)", Rope{cos_p, sin_p, rope_layout});
 }

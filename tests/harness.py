@@ -130,7 +130,7 @@ def gpu_decode(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.ndar
         cos_t, sin_t = (torch.from_numpy(t).to(dev) for t in workload.rope_tables(wl.n_total, wl.d))
     streams = None
     if split:
-        assert fused and not rope
+        assert fused
         main = torch.cuda.current_stream()
         streams = ssd.stream_array([main] + [torch.cuda.Stream() for _ in range(split - 1)])      # default priority
     calls = [(lb, min(wl.L, lb + lpc)) for lb in range(0, wl.L, lpc)]
@@ -154,11 +154,14 @@ def gpu_decode(wl: workload.Workload, data: Dict[str, torch.Tensor], ht: np.ndar
 
     def fused_step(c, p, q, k, v, o, compress):
         for ci, (lb, le) in enumerate(calls):
-            if rope:
+            sync = (ssd.SSD_SPLIT_FORK if ci == 0 else 0) | (ssd.SSD_SPLIT_JOIN if ci == len(calls) - 1 else 0)
+            if rope and split:
+                ssd.ssd_decode_step_split_rope(c, lb, le, q[lb:le], k[lb:le], v[lb:le], o[lb:le], cos_t[p], sin_t[p], rope,
+                                               streams, sync, accumulate, compress)
+            elif rope:
                 ssd.ssd_decode_step_rope(c, lb, le, q[lb:le], k[lb:le], v[lb:le], o[lb:le], cos_t[p], sin_t[p], rope,
                                          accumulate, compress)
             elif split:
-                sync = (ssd.SSD_SPLIT_FORK if ci == 0 else 0) | (ssd.SSD_SPLIT_JOIN if ci == len(calls) - 1 else 0)
                 ssd.ssd_decode_step_split(c, lb, le, q[lb:le], k[lb:le], v[lb:le], o[lb:le], streams, sync, accumulate, compress)
             else:
                 ssd.ssd_decode_step(c, lb, le, q[lb:le], k[lb:le], v[lb:le], o[lb:le], accumulate, compress)

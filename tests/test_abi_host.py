@@ -579,3 +579,22 @@ def test_dense_split_hook_rejects_bad_split_counts_before_any_launch():
     assert "splits" in ssd.ssd_last_error()
     assert lib.ssd_dense_decode_attn_splits(*ok, 4, None, 0, None) == ssd.SSD_ERR_INVALID_ARG      # splits need a workspace
     assert lib.ssd_dense_decode_attn_splits(*ok, 4, FAKE, 16, None) == ssd.SSD_ERR_INVALID_ARG     # ... that is large enough
+
+
+def test_rotary_split_step_checks_rotary_and_stream_arguments():
+    cfg = make_config(2, 4, 4, 64, "f32", 5, 1, 4, 1, 3)
+    a = ssd.Cache(cfg, _ht(2, 4), device=None)
+    b = ssd.Cache(cfg, _ht(2, 4), device=None)
+    lib = ssd.lib
+    arr = ssd.stream_array([FAKE + 64, FAKE + 128])
+    ok = (a.handle, 0, 2, FAKE, FAKE, FAKE, FAKE, 1, 1)
+    assert lib.ssd_decode_step_split_rope(*ok, None, FAKE, ssd.SSD_ROPE_HALF, arr, 2, 0) == ssd.SSD_ERR_INVALID_ARG
+    assert lib.ssd_decode_step_split_rope(*ok, FAKE, FAKE + 4, ssd.SSD_ROPE_HALF, arr, 2, 0) == ssd.SSD_ERR_INVALID_ARG
+    assert lib.ssd_decode_step_split_rope(*ok, FAKE, FAKE, 3, arr, 2, 0) == ssd.SSD_ERR_INVALID_ARG
+    assert lib.ssd_decode_step_split_rope(*ok, FAKE, FAKE, ssd.SSD_ROPE_HALF, None, 2, 0) == ssd.SSD_ERR_INVALID_ARG
+    assert lib.ssd_decode_step_split_rope(*ok, FAKE, FAKE, ssd.SSD_ROPE_HALF, arr, 2, 8) == ssd.SSD_ERR_INVALID_ARG
+    assert a.layer_state(0)[0] == 0                                 # nothing moved
+    ssd.ssd_decode_step_split_rope(a, 0, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ssd.SSD_ROPE_INTERLEAVED, [FAKE + 64, FAKE + 128],
+                                   ssd.SSD_SPLIT_FORK | ssd.SSD_SPLIT_JOIN)
+    ssd.ssd_decode_step_rope(b, 0, 2, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ssd.SSD_ROPE_INTERLEAVED)
+    assert [a.layer_state(l) for l in range(2)] == [b.layer_state(l) for l in range(2)]

@@ -244,6 +244,21 @@ def test_fused_step_with_rotary_embedding(rope):
     _full_compare(wl.replace(name="rope-alg2", head_budget=None, W=9, M=7, alg2=True, R=0, C=5, cadence=5), lpc=1, fused=True, rope=rope)
     wl2 = workload.config(2).replace(name="cfg2-rope", L=2, prompts=4)
     _full_compare(wl2, lpc=1, k_units=32, export_every=50, device_gen=True, fused=True, rope=rope)
+    # the rotary step dealt to two and three streams: against the oracle, and bit-equal to the one-stream rotary step
+    _full_compare(wl2.replace(name="cfg2-rope-split"), lpc=1, k_units=32, export_every=50, device_gen=True, fused=True, rope=rope, split=2)
+    wl3 = workload.Workload("rope-split3", L=2, prompts=5, H=6, d=64, dtype="bf16", n0=7, grid_h=6, grid_w=10, W=9, M=7, S=1, R=1, C=4,
+                            cadence=3, seed=37, plain=True)
+    ht = workload.head_map(wl3)
+    data = _to_cuda(workload.generate(wl3, head_type=ht))
+    sched = workload.compress_schedule(wl3)
+    units = sample_units(wl3, ht, 10 ** 9)
+    last = [wl3.n_total - 1]
+    o1, e1, _ = gpu_decode(wl3, data, ht, sched, units, export_steps=last, fused=True, rope=rope, shadow=False)
+    o2, e2, c2 = gpu_decode(wl3, data, ht, sched, units, export_steps=last, fused=True, rope=rope, shadow=False, split=3)
+    assert c2.split_plan(wl3.L, 3) == (4, 3)
+    assert np.array_equal(o1, o2)
+    for a, b in zip(e1[last[0]]["post"], e2[last[0]]["post"]):
+        assert np.array_equal(a, b)
 
 
 def _fma_f32(a, b, c):
@@ -581,7 +596,7 @@ def test_random_small_configurations(seed):
     if r.random() < 0.35:         # budgets per head instead (drawn last: the other cases keep their draws)
         wl = wl.replace(W_layers=None, M_layers=None, head_budget=tuple(tuple(int(x) for x in r.integers(1, 40, H)) for _ in range(L)))
     rope = int(r.choice([0, 0, ssd.SSD_ROPE_HALF, ssd.SSD_ROPE_INTERLEAVED]))    # the fused leg, now and then with rotary embedding
-    split = 0 if rope else int(r.choice([0, 0, 2, 3]))                           # ... or dealt to several streams (drawn last)
+    split = int(r.choice([0, 0, 2, 3]))                                          # ... and / or dealt to several streams (drawn last)
     _full_compare(wl, lpc=lpc, fused=False)
     _full_compare(wl, lpc=lpc, fused=True, rope=rope, split=split)
 

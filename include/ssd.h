@@ -35,7 +35,9 @@
  *
  * Call order per generated token and layer:
  *     ssd_append_token -> ssd_decode_attn -> (ssd_compress_kv when due)
- * or the same three fused into one launch: ssd_decode_step.
+ * or the same three fused into one launch: ssd_decode_step -- or, with the
+ * batch dealt to several streams so that the launches overlap,
+ * ssd_decode_step_split.
  * Compressing after every token is Algorithm 1; compressing every 24 tokens
  * (one grid row) is Algorithm 2.  The row buffer holds C tokens, so at most
  * C - R tokens can be appended between two compressions.

@@ -271,7 +271,7 @@ def main():
 
     t0 = time.time()
     Ld = wl.L if not args.input_layers else min(wl.L, args.input_layers)       # layers that have inputs of their own
-    assert Ld == wl.L or (Ld % 2 == 0 and args.no_dense), "--input-layers: an even number (the head map alternates), and no dense leg"
+    assert Ld == wl.L or Ld % 2 == 0, "--input-layers: an even number (the head map alternates)"
     data = workload.generate(wl, device=dev, head_type=ht, layers=range(Ld))
     torch.cuda.synchronize()
     t_gen = time.time() - t0
@@ -612,8 +612,8 @@ def main():
     if not args.no_dense:
         t0 = time.time()
         n = wl.n_total
-        Kd = [workload.dense_layout(data["k"][:, l:l + 1])[0] for l in range(wl.L)]
-        Vd = [workload.dense_layout(data["v"][:, l:l + 1])[0] for l in range(wl.L)]
+        Kd = [workload.dense_layout(data["k"][:, l:l + 1])[0] for l in range(Ld)]     # layer l reads the rows of layer l mod Ld
+        Vd = [workload.dense_layout(data["v"][:, l:l + 1])[0] for l in range(Ld)]
         ws = torch.empty(ssd.ssd_dense_workspace_bytes(wl.B, wl.H, wl.d, n), dtype=torch.uint8, device=dev)
         outd = torch.empty((wl.B, wl.H, wl.d), dtype=wl.torch_dtype, device=dev)
         torch.cuda.synchronize()
@@ -622,7 +622,7 @@ def main():
 
         def dense_step(p):
             for l in range(wl.L):
-                ssd.ssd_dense_decode_attn(data["q"][p, l], Kd[l], Vd[l], outd, wl.B, wl.H, wl.d, wl.dtype, n, p + 1, 0.0,
+                ssd.ssd_dense_decode_attn(data["q"][p, l % Ld], Kd[l % Ld], Vd[l % Ld], outd, wl.B, wl.H, wl.d, wl.dtype, n, p + 1, 0.0,
                                           None, None, 1, 0, 32, ws)
         for p in range(n - reps - 2, n - reps):
             dense_step(p)

@@ -300,7 +300,16 @@ int ssd_decode_step(ssd_cache *cache, int layer_begin, int layer_end, const void
  * prompt meet only in Eq. 1, after the last layer), so a caller that runs its
  * model on parts of the batch in turn (micro-batches) keeps every part's
  * layers in order on that part's stream and never has to make the parts meet
- * between layers.  Results are those of ssd_decode_step, bit for bit.
+ * between layers.  The kernels are those of ssd_decode_step; results are the
+ * same up to rounding.  How many wavefronts share a (sequence, head) unit --
+ * and with it the order in which the unit's rows enter its softmax sums -- is
+ * chosen from the size of a launch, and a part's launch is smaller than the
+ * whole batch's (and has another launch running beside it).  Where both calls
+ * take the same launch shape the results are equal bit for bit (always the
+ * case for parts of at most 512 units; ssd_cache_set_launch_shape in
+ * ssd_hooks.h fixes the shape for tests); otherwise outputs and scores differ
+ * by the rounding of fp32 sums, and the kept sets are the same unless two
+ * candidates' scores are that close.
  *   streams   : host array of n_streams distinct hipStream_t, all of the
  *               default priority; n_streams in 1..SSD_MAX_SPLIT
  *   The batch is cut into n_parts consecutive parts of P sequences (P even: a prompt's two sequences stay

@@ -38,8 +38,11 @@ int ssd_cache_spatial_slot(const ssd_cache *cache, int layer, int head, int posi
 
 /*
  * Override, for this cache only, the launch shape of the attention / step
- * kernel, which the library otherwise picks from the launch size.  No effect on
- * results.  (0, 0, 0) restores the library's choice.
+ * kernel, which the library otherwise picks from the launch size.  Results
+ * change by rounding only: ch and the number of wavefronts per unit set the
+ * order of the fp32 softmax sums (the library's own choice is ch = 4 and one
+ * wavefront, two or four as the launch size says); units per workgroup and
+ * new_rows change nothing.  (0, 0, 0) restores the library's choice.
  *   ch       : wave-wide loads of K (and of V) per chunk: 0, 1, 2, 4
  *   wpb      : units per workgroup: 0, 1, 2, 4; 12 / 14 = one unit per workgroup
  *              shared by 2 / 4 wavefronts
@@ -48,6 +51,13 @@ int ssd_cache_spatial_slot(const ssd_cache *cache, int layer, int head, int posi
  * SSD_ERR_INVALID_ARG for values outside these sets.
  */
 int ssd_cache_set_launch_shape(ssd_cache *cache, int ch, int wpb, int new_rows);
+
+/*
+ * The shape the cache's newest attention / step launch took, in the codes of
+ * ssd_cache_set_launch_shape: out3 = { ch, wpb, new_rows } (all 0 before the
+ * first launch).  Lets a test check which results must be equal bit for bit.
+ */
+int ssd_cache_last_launch_shape(const ssd_cache *cache, int32_t out3[3]);
 
 /*
  * ssd_dense_decode_attn with the number of row splits given (1..64; 0 = the

@@ -107,6 +107,8 @@ lib.ssd_version.argtypes = []
 lib.ssd_version.restype = C.c_int
 lib.ssd_cache_set_launch_shape.argtypes = [_vp, C.c_int, C.c_int, C.c_int]
 lib.ssd_cache_set_launch_shape.restype = C.c_int
+lib.ssd_cache_last_launch_shape.argtypes = [_vp, C.POINTER(C.c_int32)]
+lib.ssd_cache_last_launch_shape.restype = C.c_int
 lib.ssd_dense_decode_attn_splits.argtypes = [_vp, _vp, _vp, _vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                              C.c_float, _vp, _vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, C.c_size_t, _vp]
 lib.ssd_dense_decode_attn_splits.restype = C.c_int
@@ -264,6 +266,12 @@ class Cache:
     def set_launch_shape(self, ch: int = 0, wpb: int = 0, new_rows: int = 0):
         """Test / sweep hook: override the attention launch shape of this cache ((0, 0, 0) = the library's choice)."""
         _check(lib.ssd_cache_set_launch_shape(self._h, ch, wpb, new_rows), "ssd_cache_set_launch_shape")
+
+    def last_launch_shape(self):
+        """Test hook: (ch, wpb, new_rows) of the newest attention / step launch, in set_launch_shape's codes."""
+        out = (C.c_int32 * 3)()
+        _check(lib.ssd_cache_last_launch_shape(self._h, out), "ssd_cache_last_launch_shape")
+        return tuple(out)
 
     def split_plan(self, layers_per_call: int, n_streams: int):
         """(sequences per part, number of parts) of ssd_decode_step_split for a call over that many layers."""

@@ -384,6 +384,7 @@ int ssd_cache_init_layered(const ssd_config *cfg, const uint8_t *head_type, cons
     c->bytes = bytes;
     c->launch_enabled = true;
     c->shape = LaunchShape{0, 0, 0};
+    c->last_shape = LaunchShape{0, 0, 0};
     c->have_events = false;
     c->st.assign(cfg->n_layers, LayerState{0, 0, 0, 0, 0});
     *out = c;

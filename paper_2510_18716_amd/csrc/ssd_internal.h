@@ -135,6 +135,7 @@ struct ssd_cache {
     size_t bytes;
     bool launch_enabled;
     ssd::LaunchShape shape;                   // test / sweep override of the attention launch shape (all 0: chosen by launch size)
+    ssd::LaunchShape last_shape;              // shape the newest attention / step launch took (read back by a test hook)
     hipEvent_t ev_fork, ev_join[SSD_MAX_SPLIT];   // ssd_decode_step_split: made on first use, timing disabled
     bool have_events;
 };

@@ -15,7 +15,7 @@
 //
 // Optional variants of the same kernel: HEADS (every head its own window or budget, taken from a table in the
 // arguments; heads dispatched longest first), ROPE (the fused step rotates q and the new k by the token's
-// position on the way in) and SPLIT (several waves share a unit: for launches of few, long units).  The plain
+// position on the way in) and SHARE (several waves share a unit: for launches of few units).  The plain
 // kernel pays for none of them.
 #include <algorithm>
 
@@ -192,11 +192,12 @@ static __device__ __forceinline__ uint4 rope_fragment(const uint4 &raw, const fl
 // in the arguments and derives its own rows and slots from it (the host's are those of the largest head).
 // ROPE: q and the new token's k are rotated by the position's angles on the way in (the rotated k is what the
 // cache receives), so that no separate launch has to touch them between the projections and this kernel.
-// SPLIT > 1 (with WPB = 1): SPLIT waves share one unit, taking every SPLIT-th wave-load of its rows, and meet
-// once in LDS; wave 0 carries on alone.  For launches of few, long units, which would leave most of the chip's
-// wave slots empty.
-template <typename T, int D, int CH, int WPB, bool FUSED, bool HEADS = false, bool ROPE = false, int SPLIT = 1>
-__global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {      // read through fetch_args
+// SHARE > 1 (with WPB = 1): SHARE waves share one unit, taking every SHARE-th wave-load of its rows, and meet
+// once in LDS; wave 0 carries on alone.  For launches of few units, which would leave most of the chip's wave
+// slots empty.  The partial sums of the waves are combined in another order than one wave adds them: outputs
+// and scores of the two forms agree to rounding, not to the bit.
+template <typename T, int D, int CH, int WPB, bool FUSED, bool HEADS = false, bool ROPE = false, int SHARE = 1>
+__global__ __launch_bounds__(WPB * SHARE * 64) void step_kernel(StepArgs) {      // read through fetch_args
     constexpr int VEC = Elem<T>::VEC;
     constexpr int LPR = D / VEC;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -208,10 +209,10 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
     const int t_c = a.c, t_base = a.base, t_R = a.R, t_lpr = a.lpr, t_new_pos = a.new_pos,
               t_new_slot_se = a.new_slot_se, t_do_compress = a.do_compress, t_accumulate = a.accumulate,
               t_M = a.g.M, t_C = a.g.C, t_row_bytes = a.g.row_bytes;
-    static_assert(SPLIT == 1 || (WPB == 1 && !HEADS), "a split unit has its workgroup to itself");
+    static_assert(SHARE == 1 || (WPB == 1 && !HEADS), "a shared unit has its workgroup to itself");
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: everything per-unit stays uniform
-    const int w = SPLIT > 1 ? 0 : wave;                   // unit of this workgroup the wave works on
-    const int part = SPLIT > 1 ? wave : 0;                // its share of that unit's rows
+    const int w = SHARE > 1 ? 0 : wave;                   // unit of this workgroup the wave works on
+    const int part = SHARE > 1 ? wave : 0;                // its share of that unit's rows
     const int lane = threadIdx.x & 63;
     const int sub = lane % LPR;
     // grid = (ceil(max heads of a type / WPB), B, 2 * layers): z selects the layer and the head type, the type
@@ -326,9 +327,9 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
         }
     };
     if (want_z)
-        stream_rows<T, D, CH, true, false>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, part, SPLIT, q, a.qscale, sm, zbuf, 0, 0, after_first_issue);
+        stream_rows<T, D, CH, true, false>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, part, SHARE, q, a.qscale, sm, zbuf, 0, 0, after_first_issue);
     else
-        stream_rows<T, D, CH, false, false>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, part, SPLIT, q, a.qscale, sm, nullptr, 0, 0, after_first_issue);
+        stream_rows<T, D, CH, false, false>(u.K, u.V, a.g.row_bytes, sg, 0, sg.total, part, SHARE, q, a.qscale, sm, nullptr, 0, 0, after_first_issue);
     if (FUSED && part == 0) {
         // The new token, from the registers it was loaded into, is folded into lane group 0's softmax as
         // one more row (index sg.total).
@@ -347,9 +348,9 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
         }
     }
     merge_groups<VEC, LPR, false>(sm);
-    if constexpr (SPLIT > 1) {
+    if constexpr (SHARE > 1) {
         // the waves of the unit leave their partial (max, sum, output) in LDS; wave 0 combines them and goes on alone
-        float *mg = reinterpret_cast<float *>(lds_raw + a.wave_lds);       // [SPLIT][2 + D]
+        float *mg = reinterpret_cast<float *>(lds_raw + a.wave_lds);       // [SHARE][2 + D]
         float *mine = mg + part * (2 + D);
         if (lane == 0) { mine[0] = sm.m; mine[1] = sm.l; }
         if (lane < LPR) {
@@ -360,12 +361,12 @@ __global__ __launch_bounds__(WPB * SPLIT * 64) void step_kernel(StepArgs) {     
         if (part != 0) return;
         float m_u = NEG_BIG;
 #pragma unroll
-        for (int p = 0; p < SPLIT; ++p) m_u = fmaxf(m_u, mg[p * (2 + D)]);
+        for (int p = 0; p < SHARE; ++p) m_u = fmaxf(m_u, mg[p * (2 + D)]);
         float l_u = 0.f, acc_u[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc_u[e] = 0.f;
 #pragma unroll
-        for (int p = 0; p < SPLIT; ++p) {
+        for (int p = 0; p < SHARE; ++p) {
             const float f = fast_exp2(mg[p * (2 + D)] - m_u);
             l_u = fmaf(mg[p * (2 + D) + 1], f, l_u);
 #pragma unroll
@@ -504,10 +505,14 @@ static void fill_head_order(const ssd_cache *c, int l, const LayerState &before,
     }
 }
 
-template <typename T, int D, int CH, int SPLIT>
-static void launch_split(const StepArgs &full, dim3 blocks, size_t lds, bool fused, hipStream_t s) {
-    if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, 1, true, false, false, SPLIT>), blocks, dim3(SPLIT * 64), lds, s, full);
-    else hipLaunchKernelGGL((step_kernel<T, D, CH, 1, false, false, false, SPLIT>), blocks, dim3(SPLIT * 64), lds, s, full);
+template <typename T, int D, int CH, int SHARE>
+static void launch_shared(const StepArgs &full, dim3 blocks, size_t lds, bool fused, hipStream_t s) {
+    if (full.h.rope_layout != 0) {                        // fused launches with four wave-loads per chunk only (the host sees to that)
+        if constexpr (CH == 4) hipLaunchKernelGGL((step_kernel<T, D, CH, 1, true, false, true, SHARE>), blocks, dim3(SHARE * 64), lds, s, full);
+        return;
+    }
+    if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, 1, true, false, false, SHARE>), blocks, dim3(SHARE * 64), lds, s, full);
+    else hipLaunchKernelGGL((step_kernel<T, D, CH, 1, false, false, false, SHARE>), blocks, dim3(SHARE * 64), lds, s, full);
 }
 
 template <typename T, int D, int CH, int WPB>
@@ -527,34 +532,45 @@ static void launch_one(const StepArgs &full, dim3 blocks, size_t lds, bool fused
     else hipLaunchKernelGGL((step_kernel<T, D, CH, WPB, false>), blocks, dim3(WPB * 64), lds, s, full);
 }
 
-// One launch over sequences [a.seq_off, a.seq_off + B) of the layers in `full`.
+// One launch over sequences [a.seq_off, a.seq_off + B) of the layers in `full`.  concurrent: the launch is one part of
+// a split call, so another part's launch runs beside it on another stream.
 template <typename T, int D>
-static hipError_t launch_step(StepArgs &full, const LaunchShape &shape, int H, int max_type_heads, int B, int layers, bool fused,
-                              bool heads, int M, hipStream_t s) {
+static hipError_t launch_step(StepArgs &full, const LaunchShape &shape, LaunchShape *used, int H, int max_type_heads, int B, int layers,
+                              bool fused, bool heads, bool concurrent, int M, hipStream_t s) {
     StepHot &a = full.h;
     const int n_old = a.c - a.R, n_cand = a.m + n_old;
-    // Launch shape by the number of units (measured on the 7B- and 1B-shaped workloads).  Up to half of
-    // what the chip holds at once (256 CUs x 16 waves) the launch is latency-bound: the waves are spread
-    // over as many CUs as possible (one unit per workgroup).  Four wave-loads of K and of V per chunk (two
-    // chunks in flight) are best at every size.  Between half a round and four rounds the new token's
-    // rows are stored after the stream (see the kernel).
+    // Launch shape by the number of units (measured on the 7B- and 1B-shaped workloads at 16 to 256 prompts).
+    // Up to half of what the chip holds at once (256 CUs x 16 waves) the launch is latency-bound: the waves
+    // are spread over as many CUs as possible (one unit per workgroup).  Four wave-loads of K and of V per
+    // chunk (two chunks in flight) are best at every size.  Between half a round and four rounds the new
+    // token's rows are stored after the stream (see the kernel).
     const long long units = (long long)H * B * layers;
     a.late_new_store = shape.new_rows == 1 ? 0 : shape.new_rows == 2 ? 1 : (units > 2048 && units <= 16384 ? 1 : 0);
     int ch = shape.ch && !heads && !a.rope_layout ? shape.ch : 4;
     int wpb = shape.wpb ? shape.wpb : (units <= 2048 ? 1 : 4);
-    // few and long units (the high-resolution shape: 2048 units of 129 to 385 rows): four waves share a unit (code 14)
+    // Several waves per unit (codes 12 and 14: two and four) where one wave per unit leaves wave slots empty:
+    //  * few and long units (the high-resolution shape, 2048 units of 129 to 385 rows): four, 41.0 -> 38.1 us;
+    //  * parts of a split call, two launches in flight: two waves for parts of 1025 to 2048 units (7B shape,
+    //    128 sequences on two streams: 0.705 -> 0.687 ms per step), four for parts of 513 to 1024 units (64
+    //    sequences: 0.415 -> 0.385 ms).  Alone on the chip such launches are faster with one wave per unit
+    //    (64 sequences on one stream: 0.443 ms against 0.452 and 0.466), and smaller parts gain nothing.
     const int longest = a.se.total > a.sp.total ? a.se.total : a.sp.total;
-    if (!shape.wpb && !heads && !a.rope_layout && units <= 2048 && longest >= 96) wpb = 14;
+    if (!shape.wpb && !heads && units <= 2048) {
+        if (longest >= 96) wpb = 14;
+        else if (concurrent && units > 1024) wpb = 12;
+        else if (concurrent && units > 512) wpb = 14;
+    }
     if (wpb > 10 && ch == 1) ch = 2;                      // the shared-unit launch exists with two and four loads per chunk
     a.wave_lds = (int)(((size_t)a.zcap * 4 + (a.do_compress ? select_lds_bytes(M, n_cand, n_old) + 16 : 0) + 15) / 16 * 16);
     while (wpb > 1 && wpb < 10 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;
     const size_t lds = (size_t)wpb * a.wave_lds;
+    *used = LaunchShape{ch, wpb, a.late_new_store ? 2 : 1};
     const dim3 blocks = heads ? dim3((unsigned)RANK_GROUPS, (unsigned)B, (unsigned)(((H + wpb - 1) / wpb + RANK_GROUPS - 1) / RANK_GROUPS))   // rank order, see the kernel
                               : dim3((unsigned)((max_type_heads + wpb - 1) / wpb), (unsigned)B, (unsigned)(2 * layers));
     // wpb codes 12 and 14: one unit per workgroup, shared by 2 or 4 waves
-#define SSD_SPLIT(CH_, SPLIT_) if (ch == CH_ && wpb == 10 + SPLIT_ && !heads && !a.rope_layout) { launch_split<T, D, CH_, SPLIT_>(full, dim3((unsigned)max_type_heads, (unsigned)B, (unsigned)(2 * layers)), (size_t)a.wave_lds + SPLIT_ * (2 + D) * sizeof(float), fused, s); return hipGetLastError(); }
-    SSD_SPLIT(2, 2) SSD_SPLIT(4, 2) SSD_SPLIT(2, 4) SSD_SPLIT(4, 4)
-#undef SSD_SPLIT
+#define SSD_SHARED(CH_, SHARE_) if (ch == CH_ && wpb == 10 + SHARE_ && !heads) { launch_shared<T, D, CH_, SHARE_>(full, dim3((unsigned)max_type_heads, (unsigned)B, (unsigned)(2 * layers)), (size_t)a.wave_lds + SHARE_ * (2 + D) * sizeof(float), fused, s); return hipGetLastError(); }
+    SSD_SHARED(2, 2) SSD_SHARED(4, 2) SSD_SHARED(2, 4) SSD_SHARED(4, 4)
+#undef SSD_SHARED
 #define SSD_CASE(CH_, WPB_) if (ch == CH_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_>(full, blocks, lds, fused, heads, s); return hipGetLastError(); }
     if constexpr (sizeof(T) == 2 && D == 128) {       // the shape the sweeps are run on has every variant
         SSD_CASE(1, 1) SSD_CASE(2, 1) SSD_CASE(4, 1)
@@ -665,11 +681,11 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
                 const bool hd = heads_differ(cache, lb);
                 hipError_t e;
                 if (cf.dtype == SSD_BF16)
-                    e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(full, cache->shape, cf.n_heads, mth, Bn, le - lb, fused, hd, cache->Ml[lb], s)
-                                           : launch_step<bf16_t, 64>(full, cache->shape, cf.n_heads, mth, Bn, le - lb, fused, hd, cache->Ml[lb], s);
+                    e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(full, cache->shape, &cache->last_shape, cf.n_heads, mth, Bn, le - lb, fused, hd, plan.parts > 1 && n_streams > 1, cache->Ml[lb], s)
+                                           : launch_step<bf16_t, 64>(full, cache->shape, &cache->last_shape, cf.n_heads, mth, Bn, le - lb, fused, hd, plan.parts > 1 && n_streams > 1, cache->Ml[lb], s);
                 else
-                    e = cf.head_dim == 128 ? launch_step<float, 128>(full, cache->shape, cf.n_heads, mth, Bn, le - lb, fused, hd, cache->Ml[lb], s)
-                                           : launch_step<float, 64>(full, cache->shape, cf.n_heads, mth, Bn, le - lb, fused, hd, cache->Ml[lb], s);
+                    e = cf.head_dim == 128 ? launch_step<float, 128>(full, cache->shape, &cache->last_shape, cf.n_heads, mth, Bn, le - lb, fused, hd, plan.parts > 1 && n_streams > 1, cache->Ml[lb], s)
+                                           : launch_step<float, 64>(full, cache->shape, &cache->last_shape, cf.n_heads, mth, Bn, le - lb, fused, hd, plan.parts > 1 && n_streams > 1, cache->Ml[lb], s);
                 if (e != hipSuccess) return hip_fail(e, what);
                 if (do_compress && !in_kernel) {
                     const int rc = launch_compress_inplace(cache, lb, le, at, a.seq_off, Bn, s);
@@ -713,6 +729,13 @@ extern "C" int ssd_cache_set_launch_shape(ssd_cache *cache, int ch, int wpb, int
         new_rows < 0 || new_rows > 2)
         return fail(SSD_ERR_INVALID_ARG, "launch shape (%d, %d, %d) is not one the library has", ch, wpb, new_rows);
     cache->shape = LaunchShape{ch, wpb, new_rows};
+    return SSD_OK;
+}
+
+extern "C" int ssd_cache_last_launch_shape(const ssd_cache *cache, int32_t out3[3]) {
+    clear_error();
+    if (!cache || !out3) return fail(SSD_ERR_INVALID_ARG, "cache or out3 is NULL");
+    out3[0] = cache->last_shape.ch; out3[1] = cache->last_shape.wpb; out3[2] = cache->last_shape.new_rows;
     return SSD_OK;
 }
 

@@ -569,6 +569,10 @@ def test_launch_shape_hook_accepts_only_shapes_the_library_has():
     # results of host-side calls are unaffected
     ssd.ssd_decode_step(a, 0, 1, FAKE, FAKE, FAKE, FAKE, True, True)
     assert a.layer_state(0)[0] == 1
+    # no launch has happened (launches are off): nothing to report yet
+    assert a.last_launch_shape() == (0, 0, 0)
+    assert ssd.lib.ssd_cache_last_launch_shape(None, None) == ssd.SSD_ERR_INVALID_ARG
+    assert ssd.lib.ssd_cache_last_launch_shape(a.handle, None) == ssd.SSD_ERR_INVALID_ARG
 
 
 def test_dense_split_hook_rejects_bad_split_counts_before_any_launch():

@@ -259,6 +259,14 @@ def test_fused_step_with_rotary_embedding(rope):
     assert np.array_equal(o1, o2)
     for a, b in zip(e1[last[0]]["post"], e2[last[0]]["post"]):
         assert np.array_equal(a, b)
+    # parts of 1024 and of 2048 units (four and two waves per unit, each rotating the query for itself)
+    wide = workload.Workload("rope-split-parts-of-1024", L=2, prompts=8, H=128, d=64, dtype="bf16", n0=8, grid_h=6, grid_w=6, W=12,
+                             M=10, S=1, R=1, C=4, cadence=3, seed=75, plain=True)
+    c = _full_compare(wide, lpc=1, k_units=32, export_every=4, device_gen=True, fused=True, rope=rope, split=2)
+    assert c.last_launch_shape()[:2] == (4, 14)
+    c = _full_compare(wide.replace(name="rope-split-parts-of-2048", prompts=16, d=128, seed=77), lpc=1, k_units=32, export_every=4,
+                      device_gen=True, fused=True, rope=rope, split=2)
+    assert c.last_launch_shape()[:2] == (4, 12)
 
 
 def _fma_f32(a, b, c):
@@ -445,9 +453,12 @@ def test_determinism_same_inputs_same_bits():
 @pytest.mark.parametrize("n_streams", [2, 3, 4])
 def test_split_step_on_several_streams_equals_the_one_stream_step(n_streams):
     """ssd_decode_step_split (the schedule bench.py times): the batch dealt to n streams, forked at a token's first
-    layer and joined at its last.  Sequences are independent, so outputs and final tables must equal the
-    one-stream ssd_decode_step bit for bit.  Includes a batch that does not divide evenly (10 sequences on 3 and 4
-    streams), a long row buffer whose selection runs in the stand-alone kernel, budgets per head and Algorithm 2."""
+    layer and joined at its last.  Sequences are independent, so with the launch shape pinned outputs and final
+    tables must equal the one-stream ssd_decode_step bit for bit, and with the library's own shapes too wherever
+    every part has at most 512 units; larger parts may take several waves per unit, which changes the order of the
+    fp32 sums: there the two calls agree to rounding.  Includes a batch that does not divide evenly (10 sequences
+    on 3 and 4 streams), a long row buffer whose selection runs in the stand-alone kernel, budgets per head and
+    Algorithm 2."""
     cases = [workload.config(2).replace(name="cfg2-split", L=3, prompts=8, grid_h=5),
              workload.config(2).replace(name="cfg2-split-uneven", L=2, prompts=5, grid_h=4),
              workload.Workload("split-long-buffer", L=2, prompts=3, H=4, d=64, dtype="f32", n0=6, grid_h=40, grid_w=40, W=30,
@@ -468,12 +479,28 @@ def test_split_step_on_several_streams_equals_the_one_stream_step(n_streams):
         units = sample_units(wl, ht, 10 ** 9)
         last = [wl.n_total - 1]
         for lpc in (1, None):
-            o1, e1, _ = gpu_decode(wl, data, ht, sched, units, layers_per_call=lpc, export_steps=last, fused=True, shadow=False)
-            o2, e2, _ = gpu_decode(wl, data, ht, sched, units, layers_per_call=lpc, export_steps=last, fused=True, shadow=False,
-                                    split=n_streams)
-            assert np.array_equal(o1, o2), ("outputs differ", wl.name, lpc)
-            for a, b in zip(e1[last[0]]["post"], e2[last[0]]["post"]):
-                assert np.array_equal(a, b), ("tables differ", wl.name, lpc)
+            span = wl.L if lpc is None else lpc
+            for shape in ((4, 1, 0), None):
+                o1, e1, c1 = gpu_decode(wl, data, ht, sched, units, layers_per_call=lpc, export_steps=last, fused=True, shadow=False,
+                                        shape=shape)
+                o2, e2, c2 = gpu_decode(wl, data, ht, sched, units, layers_per_call=lpc, export_steps=last, fused=True, shadow=False,
+                                        shape=shape, split=n_streams)
+                part_units = c2.split_plan(span, n_streams)[0] * wl.H * span
+                exact = shape is not None or part_units <= 512
+                if shape is None and wl.head_budget is None and 512 < part_units <= 2048:
+                    # the shapes ssd_decode_step_split takes for parts of these sizes: two or four waves per unit
+                    assert c2.last_launch_shape()[:2] == ((4, 12) if part_units > 1024 else (4, 14)), (wl.name, c2.last_launch_shape())
+                    assert c1.last_launch_shape()[1] in (1, 4)
+                    say("   parts of", part_units, "units take shape", c2.last_launch_shape(), "- compared to rounding")
+                if exact:
+                    assert np.array_equal(o1, o2), ("outputs differ", wl.name, lpc, shape)
+                else:
+                    check_outputs(o2, o1, wl.dtype, "split against one stream, %s" % wl.name)
+                for a, b in zip(e1[last[0]]["post"], e2[last[0]]["post"]):
+                    if exact or a.dtype.kind == "i":
+                        assert np.array_equal(a, b), ("tables differ", wl.name, lpc, shape)
+                    else:
+                        np.testing.assert_allclose(b, a, rtol=1e-5, atol=1e-6)
 
 
 def test_split_step_against_the_oracle():
@@ -481,6 +508,14 @@ def test_split_step_against_the_oracle():
     wl = workload.config(2).replace(name="cfg2-split-oracle", L=2, prompts=6)
     _full_compare(wl, lpc=1, k_units=32, export_every=50, device_gen=True, fused=True, split=2)
     _full_compare(wl.replace(name="cfg2-split3-oracle"), lpc=1, k_units=32, export_every=50, device_gen=True, fused=True, split=3)
+    # parts of 1024 and of 2048 units: the sizes at which a part of a split call takes four and two waves per unit
+    wide = workload.Workload("split-parts-of-1024", L=2, prompts=8, H=128, d=64, dtype="bf16", n0=8, grid_h=6, grid_w=6, W=12, M=10,
+                             S=1, R=1, C=4, cadence=3, seed=71, plain=True)
+    c = _full_compare(wide, lpc=1, k_units=48, export_every=4, device_gen=True, fused=True, split=2)
+    assert c.last_launch_shape()[:2] == (4, 14)
+    c = _full_compare(wide.replace(name="split-parts-of-2048", prompts=16, seed=73), lpc=1, k_units=48, export_every=4, device_gen=True,
+                      fused=True, split=2)
+    assert c.last_launch_shape()[:2] == (4, 12)
 
 
 def test_config3_headline_shape_split_on_two_streams_sampled_units():

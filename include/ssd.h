@@ -281,7 +281,9 @@ int ssd_cfg_mix(const void *p, int n_seqs, int V, int dtype, float gamma, float 
 /*
  * One whole decode step of the layers in a single launch per layer group:
  * ssd_append_token, then ssd_decode_attn, then (compress != 0) the in-place
- * mode of ssd_compress_kv, with exactly their results.  Each (sequence, head)
+ * mode of ssd_compress_kv, with their results: the same kept sets, outputs
+ * and scores equal to the rounding of the fp32 sums (the new token enters the
+ * softmax from registers as the last term of its sum, not at its slot).  Each (sequence, head)
  * is handled by one wavefront from append to selection, so the three steps
  * of Algorithm 1 cost one pass over the head's rows.
  *   q, k_new, v_new, out : dev [layer_end - layer_begin, B, H, d], cache dtype

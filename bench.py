@@ -21,7 +21,8 @@ Prints ONE JSON line:
   all_layers_one_launch   the same steps with all layers handed to the library in one call (possible only
                    because the synthetic queries of all layers exist up front: an upper bound)
   stream_ceiling   a plain read of as many units of as many bytes per launch, no arithmetic, without and with the
-                   least a step must store: what the memory system allows a launch of this shape
+                   least a step must store: what the memory system allows a launch of this shape, on one stream
+                   and (headline on several streams) dealt to the streams as the headline's launches are
   dense_baseline   the same steps through the full-cache decode kernel
   cpu_baseline     the CPU oracle timed on a sample of (layer, sequence, head) units
 """
@@ -574,6 +575,26 @@ def main():
             us = (time.perf_counter() - t0) / (reps * layers_c) * 1e6
             moved = n_units * (unit_b + 256 * rows_w)
             ceil[key] = {"us_per_launch": us, "GBps": moved / 1e3 / us, "frac_of_hbm_peak": moved / 1e3 / us / HBM_PEAK_GBS}
+            if head is not None and n_streams > 1:
+                # the same bytes in the headline's schedule: every layer's units dealt to the streams, each stream running free
+                st = [stream] + [x.cuda_stream for x in side_streams[: n_streams - 1]]
+                cut = [n_units * i // n_streams for i in range(n_streams + 1)]
+
+                def split_pass():
+                    for l in range(layers_c):
+                        for i in range(n_streams):
+                            rc = ssd.lib.ssd_bench_stream(buf.data_ptr() + (l * n_units + cut[i]) * unit_b, unit_b, cut[i + 1] - cut[i],
+                                                          rows_w, sink.data_ptr(), st[i])
+                            assert rc == 0, ssd.ssd_last_error()
+                split_pass()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    split_pass()
+                torch.cuda.synchronize()
+                us2 = (time.perf_counter() - t0) / (reps * layers_c) * 1e6
+                ceil[key + "_on_%d_streams" % n_streams] = {"us_per_layer": us2, "GBps": moved / 1e3 / us2,
+                                                            "frac_of_hbm_peak": moved / 1e3 / us2 / HBM_PEAK_GBS}
         result["stream_ceiling"] = dict(ceil, units_per_launch=n_units, bytes_per_unit=unit_b, launches_timed=layers_c,
                                         kind="ssd_bench_stream: every unit read once by one wavefront, no arithmetic; the second line "
                                              "also stores one 256-byte row into each plane of every unit (a new token's K and V)")

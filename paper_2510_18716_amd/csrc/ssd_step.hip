@@ -209,7 +209,7 @@ __global__ __launch_bounds__(WPB * SHARE * 64) void step_kernel(StepArgs) {     
     const int t_c = a.c, t_base = a.base, t_R = a.R, t_lpr = a.lpr, t_new_pos = a.new_pos,
               t_new_slot_se = a.new_slot_se, t_do_compress = a.do_compress, t_accumulate = a.accumulate,
               t_M = a.g.M, t_C = a.g.C, t_row_bytes = a.g.row_bytes;
-    static_assert(SHARE == 1 || (WPB == 1 && !HEADS), "a shared unit has its workgroup to itself");
+    static_assert(SHARE == 1 || WPB == 1, "a shared unit has its workgroup to itself");
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: everything per-unit stays uniform
     const int w = SHARE > 1 ? 0 : wave;                   // unit of this workgroup the wave works on
     const int part = SHARE > 1 ? wave : 0;                // its share of that unit's rows
@@ -506,9 +506,15 @@ static void fill_head_order(const ssd_cache *c, int l, const LayerState &before,
 }
 
 template <typename T, int D, int CH, int SHARE>
-static void launch_shared(const StepArgs &full, dim3 blocks, size_t lds, bool fused, hipStream_t s) {
-    if (full.h.rope_layout != 0) {                        // fused launches with four wave-loads per chunk only (the host sees to that)
-        if constexpr (CH == 4) hipLaunchKernelGGL((step_kernel<T, D, CH, 1, true, false, true, SHARE>), blocks, dim3(SHARE * 64), lds, s, full);
+static void launch_shared(const StepArgs &full, dim3 blocks, size_t lds, bool fused, bool heads, hipStream_t s) {
+    const bool rope = full.h.rope_layout != 0;
+    if (heads || rope) {                                  // four wave-loads per chunk only; the rotary step is always fused (the host sees to both)
+        if constexpr (CH == 4) {
+            if (rope && heads) hipLaunchKernelGGL((step_kernel<T, D, CH, 1, true, true, true, SHARE>), blocks, dim3(SHARE * 64), lds, s, full);
+            else if (rope) hipLaunchKernelGGL((step_kernel<T, D, CH, 1, true, false, true, SHARE>), blocks, dim3(SHARE * 64), lds, s, full);
+            else if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, 1, true, true, false, SHARE>), blocks, dim3(SHARE * 64), lds, s, full);
+            else hipLaunchKernelGGL((step_kernel<T, D, CH, 1, false, true, false, SHARE>), blocks, dim3(SHARE * 64), lds, s, full);
+        }
         return;
     }
     if (fused) hipLaunchKernelGGL((step_kernel<T, D, CH, 1, true, false, false, SHARE>), blocks, dim3(SHARE * 64), lds, s, full);
@@ -555,8 +561,8 @@ static hipError_t launch_step(StepArgs &full, const LaunchShape &shape, LaunchSh
     //    sequences: 0.415 -> 0.385 ms).  Alone on the chip such launches are faster with one wave per unit
     //    (64 sequences on one stream: 0.443 ms against 0.452 and 0.466), and smaller parts gain nothing.
     const int longest = a.se.total > a.sp.total ? a.se.total : a.sp.total;
-    if (!shape.wpb && !heads && units <= 2048) {
-        if (longest >= 96) wpb = 14;
+    if (!shape.wpb && units <= 2048) {
+        if (longest >= 96 && !heads) wpb = 14;            // (budgets per head: `longest` is the largest head's, most units are shorter)
         else if (concurrent && units > 1024) wpb = 12;
         else if (concurrent && units > 512) wpb = 14;
     }
@@ -568,7 +574,7 @@ static hipError_t launch_step(StepArgs &full, const LaunchShape &shape, LaunchSh
     const dim3 blocks = heads ? dim3((unsigned)RANK_GROUPS, (unsigned)B, (unsigned)(((H + wpb - 1) / wpb + RANK_GROUPS - 1) / RANK_GROUPS))   // rank order, see the kernel
                               : dim3((unsigned)((max_type_heads + wpb - 1) / wpb), (unsigned)B, (unsigned)(2 * layers));
     // wpb codes 12 and 14: one unit per workgroup, shared by 2 or 4 waves
-#define SSD_SHARED(CH_, SHARE_) if (ch == CH_ && wpb == 10 + SHARE_ && !heads) { launch_shared<T, D, CH_, SHARE_>(full, dim3((unsigned)max_type_heads, (unsigned)B, (unsigned)(2 * layers)), (size_t)a.wave_lds + SHARE_ * (2 + D) * sizeof(float), fused, s); return hipGetLastError(); }
+#define SSD_SHARED(CH_, SHARE_) if (ch == CH_ && wpb == 10 + SHARE_) { launch_shared<T, D, CH_, SHARE_>(full, heads ? dim3((unsigned)RANK_GROUPS, (unsigned)B, (unsigned)((H + RANK_GROUPS - 1) / RANK_GROUPS)) : dim3((unsigned)max_type_heads, (unsigned)B, (unsigned)(2 * layers)), (size_t)a.wave_lds + SHARE_ * (2 + D) * sizeof(float), fused, heads, s); return hipGetLastError(); }
     SSD_SHARED(2, 2) SSD_SHARED(4, 2) SSD_SHARED(2, 4) SSD_SHARED(4, 4)
 #undef SSD_SHARED
 #define SSD_CASE(CH_, WPB_) if (ch == CH_ && wpb == WPB_) { launch_one<T, D, CH_, WPB_>(full, blocks, lds, fused, heads, s); return hipGetLastError(); }

@@ -435,6 +435,15 @@ def test_every_launch_shape_variant(ch, wpu):
             _full_compare(wl.replace(name="variant-long", R=3, C=40, cadence=33), fused=True, shape=shape)
             _full_compare(wl.replace(name="variant-alg2", alg2=True, R=0, C=6, cadence=6), fused=True, shape=shape)
             _full_compare(wl.replace(name="variant-empty-parts", W=3, M=2, S=0, R=1, C=2, cadence=1), fused=True, shape=shape)
+            if ch == 4:       # budgets per head and the rotary step exist with four wave-loads per chunk
+                hb = ((24, 5, 1, 7, 40, 3), (9, 9, 30, 2, 1, 17))
+                heads = wl.replace(name="variant-per-head", W=99, M=99, head_budget=hb)
+                _full_compare(heads, fused=False, shape=shape)
+                _full_compare(heads, fused=True, shape=shape)
+                _full_compare(heads.replace(name="variant-per-head-alg2", alg2=True, R=0, C=6, cadence=6), fused=True, shape=shape)
+                for rope in (ssd.SSD_ROPE_HALF, ssd.SSD_ROPE_INTERLEAVED):
+                    _full_compare(wl.replace(name="variant-rope"), fused=True, shape=shape, rope=rope)
+                    _full_compare(heads.replace(name="variant-per-head-rope"), fused=True, shape=shape, rope=rope)
 
 
 def test_determinism_same_inputs_same_bits():
@@ -487,7 +496,7 @@ def test_split_step_on_several_streams_equals_the_one_stream_step(n_streams):
                                         shape=shape, split=n_streams)
                 part_units = c2.split_plan(span, n_streams)[0] * wl.H * span
                 exact = shape is not None or part_units <= 512
-                if shape is None and wl.head_budget is None and 512 < part_units <= 2048:
+                if shape is None and 512 < part_units <= 2048:
                     # the shapes ssd_decode_step_split takes for parts of these sizes: two or four waves per unit
                     assert c2.last_launch_shape()[:2] == ((4, 12) if part_units > 1024 else (4, 14)), (wl.name, c2.last_launch_shape())
                     assert c1.last_launch_shape()[1] in (1, 4)
@@ -515,6 +524,14 @@ def test_split_step_against_the_oracle():
     assert c.last_launch_shape()[:2] == (4, 14)
     c = _full_compare(wide.replace(name="split-parts-of-2048", prompts=16, seed=73), lpc=1, k_units=48, export_every=4, device_gen=True,
                       fused=True, split=2)
+    assert c.last_launch_shape()[:2] == (4, 12)
+    # the same part sizes with a window / budget per head (128 heads, seeded budgets of 3 to 20 rows)
+    hb = np.random.default_rng(79).integers(3, 21, (2, 128)).tolist()
+    heads = wide.replace(name="split-per-head-parts-of-1024", W=20, M=20, head_budget=hb, seed=81)
+    c = _full_compare(heads, lpc=1, k_units=48, export_every=4, device_gen=True, fused=True, split=2)
+    assert c.last_launch_shape()[:2] == (4, 14)
+    c = _full_compare(heads.replace(name="split-per-head-parts-of-2048", prompts=16, seed=83), lpc=1, k_units=48, export_every=4,
+                      device_gen=True, fused=True, split=2)
     assert c.last_launch_shape()[:2] == (4, 12)
 
 

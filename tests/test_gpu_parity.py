@@ -525,6 +525,10 @@ def test_split_step_against_the_oracle():
     c = _full_compare(wide.replace(name="split-parts-of-2048", prompts=16, seed=73), lpc=1, k_units=48, export_every=4, device_gen=True,
                       fused=True, split=2)
     assert c.last_launch_shape()[:2] == (4, 12)
+    # parts that fall on two sides of a shape boundary: 10 sequences x 64 heads (four waves per unit) and 8 x 64 (one)
+    c = _full_compare(wide.replace(name="split-parts-of-640-and-512", prompts=9, H=64, seed=85), lpc=1, k_units=48, export_every=4,
+                      device_gen=True, fused=True, split=2)
+    assert c.split_plan(1, 2) == (10, 2) and c.last_launch_shape()[:2] == (4, 1)
     # the same part sizes with a window / budget per head (128 heads, seeded budgets of 3 to 20 rows)
     hb = np.random.default_rng(79).integers(3, 21, (2, 128)).tolist()
     heads = wide.replace(name="split-per-head-parts-of-1024", W=20, M=20, head_budget=hb, seed=81)

@@ -627,6 +627,30 @@ def main():
                                     "algorithmic_GB": pf_bytes / 1e9, "GBps": pf_bytes / 1e9 / tp,
                                     "frac_of_hbm_peak": pf_bytes / 1e9 / tp / HBM_PEAK_GBS, "mfma_TFLOPs": pf_flops / 1e12 / tp,
                                     "kind": "ssd_prefill_scores, Q and K of the prompt read once, fp32 column sums written"}
+        if n_streams > 1:
+            # the same launches with the units of a layer dealt to the streams (units are independent: the caller offsets the
+            # pointers), every stream running free, as the decode headline's parts do
+            sts = [torch.cuda.current_stream()] + side_streams[: n_streams - 1]
+            cut = [units * i // n_streams for i in range(n_streams + 1)]
+            Qv = [x.view(units, n0, wl.d) for x in Qp]
+            Kv = [x.view(units, n0, wl.d) for x in Kp]
+            scv = sc.view(units, n0)
+
+            def prefill_split_pass():
+                for l in range(wl.L):
+                    for i in range(n_streams):
+                        ssd.ssd_prefill_scores(Qv[l % Ld][cut[i]:cut[i + 1]], Kv[l % Ld][cut[i]:cut[i + 1]], cut[i + 1] - cut[i], n0, wl.d,
+                                               wl.dtype, scv[cut[i]:cut[i + 1]], stream=sts[i])
+            prefill_split_pass()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                prefill_split_pass()
+            torch.cuda.synchronize()
+            tp2 = (time.perf_counter() - t0) / reps
+            result["prefill_scores"]["on_%d_streams" % n_streams] = {"ms_all_layers": tp2 * 1e3, "us_per_layer": tp2 * 1e6 / wl.L,
+                                                                      "GBps": pf_bytes / 1e9 / tp2,
+                                                                      "frac_of_hbm_peak": pf_bytes / 1e9 / tp2 / HBM_PEAK_GBS}
         del Qp, Kp
 
     # ---- the same steps through the dense full-cache kernel -----------------------------------------------

@@ -119,7 +119,8 @@ def sweep5(args, dev):
     """Configuration 5: B = 512 sequences, 32 heads, d = 128; spatial fraction in {25, 50, 75} %, W and M in
     {32, 64, 128}.  Steady-state fused per-layer launches on `--layers` layers (default 4; a per-layer launch has
     the full configuration's shape whatever the layer count), inputs plain Gaussians (timing does not depend on
-    the values)."""
+    the values).  Each point on one stream (ssd_decode_step) and, unless --streams 1, in the headline's schedule
+    (ssd_decode_step_split on --streams streams, default 2, every part running free)."""
     import numpy as np
     import torch
 
@@ -131,6 +132,9 @@ def sweep5(args, dev):
     base = workload.config(5).replace(L=L, plain=True, grid_h=8)          # 64 + 192 tokens: every window fills
     data = workload.generate(base, device=dev)
     K_steps = 40
+    n_split = 2 if args.streams == 0 else max(1, min(args.streams, ssd.SSD_MAX_SPLIT))
+    side = [torch.cuda.Stream() for _ in range(n_split - 1)]                     # default priority
+    stream_arr = ssd.stream_array([torch.cuda.current_stream()] + side)
     for frac in (0.25, 0.5, 0.75):
         for W in (32, 64, 128):
             for M in (32, 64, 128):
@@ -142,29 +146,41 @@ def sweep5(args, dev):
                 qb, kb, vb, ob = data["q"].data_ptr(), data["k"].data_ptr(), data["v"].data_ptr(), out.data_ptr()
                 stream = torch.cuda.current_stream().cuda_stream
 
-                def step(p):
-                    for l in range(wl.L):
-                        o = (p * wl.L + l) * stride_l
-                        rc = ssd.lib.ssd_decode_step(cache.handle, l, l + 1, qb + o, kb + o, vb + o, ob + l * stride_l, 1, 1, stream)
-                        assert rc == 0, ssd.ssd_last_error()
-                p_timed = wl.n_total - K_steps
-                for p in range(p_timed):
-                    step(p)
-                torch.cuda.synchronize()
-                t0 = time.perf_counter()
-                for p in range(p_timed, wl.n_total):
-                    step(p)
-                torch.cuda.synchronize()
-                dt = (time.perf_counter() - t0) / K_steps
+                def timed(ns):
+                    def step(p):
+                        for l in range(wl.L):
+                            o = (p * wl.L + l) * stride_l
+                            if ns > 1:
+                                rc = ssd.lib.ssd_decode_step_split(cache.handle, l, l + 1, qb + o, kb + o, vb + o, ob + l * stride_l, 1, 1,
+                                                                   stream_arr, ns, 0)
+                            else:
+                                rc = ssd.lib.ssd_decode_step(cache.handle, l, l + 1, qb + o, kb + o, vb + o, ob + l * stride_l, 1, 1, stream)
+                            assert rc == 0, ssd.ssd_last_error()
+                    cache.reset()
+                    p_timed = wl.n_total - K_steps
+                    for p in range(p_timed):
+                        step(p)
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    for p in range(p_timed, wl.n_total):
+                        step(p)
+                    torch.cuda.synchronize()
+                    return (time.perf_counter() - t0) / K_steps
+                dt = timed(1)
                 n_, m_, c_, _ = cache.layer_state(0)
                 gb = (algorithmic_bytes_attend(wl, ht, range(wl.L), (n_, m_, c_ + 1)) + algorithmic_bytes_append(wl, ht, range(wl.L))) / 1e9
-                rows.append({"spatial_frac": frac, "W": W, "M": M, "ms_per_layer": dt / wl.L * 1e3, "GB_per_layer": gb / wl.L,
-                             "GBps": gb / dt, "frac_of_hbm_peak": gb / dt / HBM_PEAK_GBS,
-                             "tokens_per_s_at_30_layers": wl.prompts / (dt / wl.L * 30)})
+                row = {"spatial_frac": frac, "W": W, "M": M, "ms_per_layer": dt / wl.L * 1e3, "GB_per_layer": gb / wl.L,
+                       "GBps": gb / dt, "frac_of_hbm_peak": gb / dt / HBM_PEAK_GBS,
+                       "tokens_per_s_at_30_layers": wl.prompts / (dt / wl.L * 30)}
+                if n_split > 1:
+                    dt2 = timed(n_split)
+                    row["split"] = {"streams": n_split, "ms_per_layer": dt2 / wl.L * 1e3, "GBps": gb / dt2, "frac_of_hbm_peak": gb / dt2 / HBM_PEAK_GBS,
+                                    "tokens_per_s_at_30_layers": wl.prompts / (dt2 / wl.L * 30)}
+                rows.append(row)
                 del cache
     print(json.dumps({"metric": "visual tokens/sec per GPU (compressed decode attn, all layers)", "unit": "tokens/s",
                       "config": {"workload": "cfg5-large sweep", "sequences": base.B, "heads": base.H, "head_dim": base.d,
-                                 "layers_timed": L, "launches": "ssd_decode_step, one per layer"},
+                                 "layers_timed": L, "launches": "ssd_decode_step, one per layer; 'split': ssd_decode_step_split, one call per layer"},
                       "sweep": rows}))
 
 
@@ -178,6 +194,11 @@ def main():
                     help="layers handed to each library call for the headline figure (1 = as a real model would)")
     ap.add_argument("--prompts", type=int, default=0, help="override the number of prompts (0 = the configuration's)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the configuration's)")
+    ap.add_argument("--window", type=int, default=0, help="override W of the configuration (0 = the configuration's)")
+    ap.add_argument("--budget", type=int, default=0, help="override M of the configuration (0 = the configuration's)")
+    ap.add_argument("--spatial-heads", type=int, default=-1,
+                    help="override the number of spatial heads per layer (-1 = the configuration's half); the paper's tau = 0.8 leaves "
+                         "about 2 of 32 heads semantic on the 7B model (Table 6)")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
@@ -243,6 +264,11 @@ def main():
         wl = wl.replace(prompts=args.prompts)
     if args.layers:
         wl = wl.replace(L=args.layers, name=wl.name + "-L%d" % args.layers)
+    if args.window or args.budget or args.spatial_heads >= 0:
+        wl = wl.replace(W=args.window or wl.W, M=args.budget or wl.M,
+                        spatial_frac=wl.spatial_frac if args.spatial_heads < 0 else args.spatial_heads / wl.H,
+                        name=wl.name + "-W%d-M%d-sp%d" % (args.window or wl.W, args.budget or wl.M,
+                                                        round(wl.spatial_frac * wl.H) if args.spatial_heads < 0 else args.spatial_heads))
     if args.alg2:
         wl = wl.replace(alg2=True, R=0, C=wl.grid_w, cadence=wl.grid_w, name=wl.name + "-alg2")
     if args.grid_rows:

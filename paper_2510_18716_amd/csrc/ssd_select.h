@@ -84,8 +84,25 @@ static __device__ __forceinline__ void select_and_move(const Geom &g, const Unit
     // rank by counting; bit k of keepbits = candidate tid + k*THREADS is kept
     unsigned long long keepbits = 0;
     static_assert((4096 + THREADS - 1) / THREADS <= 64, "one 64-bit mask per thread");
+    const int n_evict = n_cand - M;
+    const int per = (n_cand + THREADS - 1) / THREADS;                // candidates per thread
     if (n_cand <= M) {
         keepbits = ~0ull;
+    } else if (WAVE && (long long)n_evict * (per + 20) < (long long)per * n_cand) {
+        // Few evictions among many candidates (compression after every token: one): take the smallest keys out one
+        // by one -- a pass over this lane's keys and a wave-wide minimum each -- instead of ranking every candidate
+        // against every other.  Keys are distinct, so each minimum has one owner, and the kept set is the same.
+        keepbits = ~0ull;
+        for (int e = 0; e < n_evict; ++e) {
+            unsigned long long least = ~0ull;
+            int at = -1;
+            for (int k = 0; k * THREADS + tid < n_cand; ++k) {
+                const unsigned long long key = keys[k * THREADS + tid];
+                if (((keepbits >> k) & 1ull) && key < least) { least = key; at = k; }
+            }
+            const unsigned long long lowest = wave_min_u64(least);      // every lane takes part, with or without a candidate
+            if (at >= 0 && least == lowest) keepbits &= ~(1ull << at);
+        }
     } else {
         for (int k = 0; k * THREADS + tid < n_cand; ++k) {
             const unsigned long long mine = keys[k * THREADS + tid];

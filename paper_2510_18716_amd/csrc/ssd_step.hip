@@ -541,9 +541,10 @@ static void launch_one(const StepArgs &full, dim3 blocks, size_t lds, bool fused
 // One launch over sequences [a.seq_off, a.seq_off + B) of the layers in `full`.  concurrent: the launch is one part of
 // a split call, so another part's launch runs beside it on another stream.
 template <typename T, int D>
-static hipError_t launch_step(StepArgs &full, const LaunchShape &shape, LaunchShape *used, int H, int max_type_heads, int B, int layers,
-                              bool fused, bool heads, bool concurrent, int M, hipStream_t s) {
+static hipError_t launch_step(StepArgs &full, const LaunchShape &shape, LaunchShape *used, int H, int max_sp_heads, int max_se_heads, int B,
+                              int layers, bool fused, bool heads, bool concurrent, int M, hipStream_t s) {
     StepHot &a = full.h;
+    const int max_type_heads = max_sp_heads > max_se_heads ? max_sp_heads : max_se_heads;
     const int n_old = a.c - a.R, n_cand = a.m + n_old;
     // Launch shape by the number of units (measured on the 7B- and 1B-shaped workloads at 16 to 256 prompts).
     // Up to half of what the chip holds at once (256 CUs x 16 waves) the launch is latency-bound: the waves
@@ -566,6 +567,21 @@ static hipError_t launch_step(StepArgs &full, const LaunchShape &shape, LaunchSh
         else if (concurrent && units > 1024) wpb = 12;
         else if (concurrent && units > 512) wpb = 14;
     }
+    //  * a few long units beside many short ones -- the head mix the paper's threshold gives (Sec. 3.3, Table 6: a
+    //    handful of semantic heads with a large budget, most heads spatial with a short window): with one wave per
+    //    unit the launch lasts as long as its longest units while the waves of the short ones are long gone.  Where
+    //    one head type streams at least twice the rows of the other and has at most a quarter of the heads, every
+    //    unit gets two waves -- four if the long type is the semantic one with at least 96 rows and the launch is
+    //    small (up to 2048 units, or up to 4096 with at least 192 rows).  7B shape, 30 spatial heads with W = 32
+    //    beside 2 semantic ones, one stream, ms per step: M = 64 0.678 -> 0.482, M = 128 0.856 -> 0.588, M = 320
+    //    1.523 -> 0.742; 512 sequences, M = 128: 2.999 -> 1.792.  (On two streams the parts of those shapes had two
+    //    waves per unit already; four bring 0.555 -> 0.514 at M = 128 and 0.781 -> 0.706 at M = 320.)
+    const bool long_sem = a.sem_first != 0;
+    const int rows_long = long_sem ? a.se.total : a.sp.total, rows_short = long_sem ? a.sp.total : a.se.total;
+    const int heads_long = long_sem ? max_se_heads : max_sp_heads;
+    if (!shape.wpb && !heads && max_sp_heads > 0 && max_se_heads > 0 && rows_short > 0 && rows_long >= 2 * rows_short &&
+        4 * heads_long <= H)
+        wpb = long_sem && rows_long >= 96 && (units <= 2048 || (units <= 4096 && rows_long >= 192)) ? 14 : 12;
     if (wpb > 10 && ch == 1) ch = 2;                      // the shared-unit launch exists with two and four loads per chunk
     a.wave_lds = (int)(((size_t)a.zcap * 4 + (a.do_compress ? select_lds_bytes(M, n_cand, n_old) + 16 : 0) + 15) / 16 * 16);
     while (wpb > 1 && wpb < 10 && (size_t)wpb * a.wave_lds > 60000) wpb >>= 1;
@@ -674,10 +690,10 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
             a.rope_layout = rope.layout; a.rope_cos = rope.cos; a.rope_sin = rope.sin;
             if (heads_differ(cache, lb)) fill_head_order(cache, lb, before, at, fused, &full.ho);
             else full.ho = HeadOrder{};                  // never read then; keeps the argument bytes defined
-            int mth = 1;
+            int mx_sp = 0, mx_se = 0;                       // most heads of a type in a layer of the launch
             for (int l = lb; l < le; ++l) {
-                mth = cache->ldesc[l].n_sp > mth ? cache->ldesc[l].n_sp : mth;
-                mth = cache->ldesc[l].n_se > mth ? cache->ldesc[l].n_se : mth;
+                mx_sp = cache->ldesc[l].n_sp > mx_sp ? cache->ldesc[l].n_sp : mx_sp;
+                mx_se = cache->ldesc[l].n_se > mx_se ? cache->ldesc[l].n_se : mx_se;
             }
             a.sem_first = a.se.total + (fused ? 1 : 0) >= a.sp.total + (fused ? 1 : 0) ? 1 : 0;
             for (int part = 0; part < plan.parts; ++part) {
@@ -687,11 +703,11 @@ static int run_step(ssd_cache *cache, int layer_begin, int layer_end, const void
                 const bool hd = heads_differ(cache, lb);
                 hipError_t e;
                 if (cf.dtype == SSD_BF16)
-                    e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(full, cache->shape, &cache->last_shape, cf.n_heads, mth, Bn, le - lb, fused, hd, plan.parts > 1 && n_streams > 1, cache->Ml[lb], s)
-                                           : launch_step<bf16_t, 64>(full, cache->shape, &cache->last_shape, cf.n_heads, mth, Bn, le - lb, fused, hd, plan.parts > 1 && n_streams > 1, cache->Ml[lb], s);
+                    e = cf.head_dim == 128 ? launch_step<bf16_t, 128>(full, cache->shape, &cache->last_shape, cf.n_heads, mx_sp, mx_se, Bn, le - lb, fused, hd, plan.parts > 1 && n_streams > 1, cache->Ml[lb], s)
+                                           : launch_step<bf16_t, 64>(full, cache->shape, &cache->last_shape, cf.n_heads, mx_sp, mx_se, Bn, le - lb, fused, hd, plan.parts > 1 && n_streams > 1, cache->Ml[lb], s);
                 else
-                    e = cf.head_dim == 128 ? launch_step<float, 128>(full, cache->shape, &cache->last_shape, cf.n_heads, mth, Bn, le - lb, fused, hd, plan.parts > 1 && n_streams > 1, cache->Ml[lb], s)
-                                           : launch_step<float, 64>(full, cache->shape, &cache->last_shape, cf.n_heads, mth, Bn, le - lb, fused, hd, plan.parts > 1 && n_streams > 1, cache->Ml[lb], s);
+                    e = cf.head_dim == 128 ? launch_step<float, 128>(full, cache->shape, &cache->last_shape, cf.n_heads, mx_sp, mx_se, Bn, le - lb, fused, hd, plan.parts > 1 && n_streams > 1, cache->Ml[lb], s)
+                                           : launch_step<float, 64>(full, cache->shape, &cache->last_shape, cf.n_heads, mx_sp, mx_se, Bn, le - lb, fused, hd, plan.parts > 1 && n_streams > 1, cache->Ml[lb], s);
                 if (e != hipSuccess) return hip_fail(e, what);
                 if (do_compress && !in_kernel) {
                     const int rc = launch_compress_inplace(cache, lb, le, at, a.seq_off, Bn, s);

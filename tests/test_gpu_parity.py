@@ -446,6 +446,29 @@ def test_every_launch_shape_variant(ch, wpu):
                     _full_compare(heads.replace(name="variant-per-head-rope"), fused=True, shape=shape, rope=rope)
 
 
+@pytest.mark.parametrize("fused", [False, True], ids=["three-calls", "fused-step"])
+def test_few_long_heads_beside_many_short_ones(fused):
+    """The head mix the paper's threshold produces (Sec. 3.3, Table 6: a few semantic heads with a large budget beside many
+    spatial heads with a short window), and its mirror image: once one head type streams twice the rows of the other and
+    has at most a quarter of the heads, the library gives every unit two waves, or four if the long type is the semantic
+    one with at least 96 rows."""
+    few_sem = workload.Workload("few-long-semantic", L=2, prompts=3, H=16, d=128, dtype="bf16", n0=12, grid_h=8, grid_w=12, W=8, M=40,
+                                S=1, R=1, C=3, cadence=2, seed=111, plain=True, spatial_frac=0.875)
+    c = _full_compare(few_sem, lpc=1, k_units=40, export_every=3, fused=fused)
+    assert c.last_launch_shape()[:2] == (4, 12)                      # 43 rows against 9
+    c = _full_compare(few_sem.replace(name="few-very-long-semantic", M=96, seed=113), lpc=None, k_units=40, export_every=3, fused=fused)
+    assert c.last_launch_shape()[:2] == (4, 14)                      # 99 rows against 9
+    few_sp = few_sem.replace(name="few-long-spatial", W=70, M=10, spatial_frac=0.125, seed=115, d=64, dtype="f32")
+    c = _full_compare(few_sp, lpc=1, k_units=40, export_every=3, fused=fused)
+    assert c.last_launch_shape()[:2] == (4, 12)                      # 71 rows against 13
+    c = _full_compare(few_sem.replace(name="few-long-semantic-alg2", alg2=True, R=0, C=6, cadence=6, M=60, seed=117), lpc=1, k_units=40,
+                      export_every=3, fused=fused)
+    assert c.last_launch_shape()[:2] == (4, 12)                      # 60 rows and the row buffer against 9 and the row buffer
+    # as many long heads as short ones: the plain shape
+    c = _full_compare(few_sem.replace(name="half-long-semantic", spatial_frac=0.5, seed=119), lpc=1, k_units=40, export_every=3, fused=fused)
+    assert c.last_launch_shape()[1] in (1, 4)
+
+
 def test_determinism_same_inputs_same_bits():
     wl = workload.config(2).replace(name="cfg2-determinism", L=2, prompts=4, grid_h=6)
     ht = workload.head_map(wl)

@@ -469,6 +469,17 @@ def test_few_long_heads_beside_many_short_ones(fused):
     assert c.last_launch_shape()[1] in (1, 4)
 
 
+@pytest.mark.parametrize("fused", [False, True], ids=["three-calls", "fused-step"])
+def test_selection_with_few_evictions_among_many_candidates(fused):
+    """More than 128 candidates and one to a few evictions per compression: the step kernel's wave takes the smallest keys
+    out one by one instead of ranking all candidates.  The kept sets must be the oracle's at every cut (exported every
+    step once the budget is full), with one, two, three and five evictions per cut and 131 to 310 candidates."""
+    for M, cadence, C, R in ((130, 1, 2, 1), (150, 2, 4, 1), (200, 3, 6, 2), (300, 5, 7, 1)):
+        wl = workload.Workload("few-evictions-M%d-c%d" % (M, cadence), L=1, prompts=1, H=4, d=64, dtype="f32", n0=M + 10, grid_h=4,
+                               grid_w=6, W=5, M=M, S=1, R=R, C=C, cadence=cadence, seed=121 + M, plain=True, spatial_frac=0.25)
+        _full_compare(wl, fused=fused, export_every=1)
+
+
 def test_determinism_same_inputs_same_bits():
     wl = workload.config(2).replace(name="cfg2-determinism", L=2, prompts=4, grid_h=6)
     ht = workload.head_map(wl)

@@ -307,9 +307,10 @@ int ssd_decode_step(ssd_cache *cache, int layer_begin, int layer_end, const void
  * and with it the order in which the unit's rows enter its softmax sums -- is
  * chosen from the size of a launch, and a part's launch is smaller than the
  * whole batch's (and has another launch running beside it).  Where both calls
- * take the same launch shape the results are equal bit for bit (always the
- * case for parts of at most 512 units; ssd_cache_set_launch_shape in
- * ssd_hooks.h fixes the shape for tests); otherwise outputs and scores differ
+ * give a unit the same number of wavefronts the results are equal bit for bit
+ * (in ssd_hooks.h, ssd_cache_last_launch_shape reports what a launch took and
+ * ssd_cache_set_launch_shape pins it; batches of at most 512 (sequence, head,
+ * layer) units per call always qualify); otherwise outputs and scores differ
  * by the rounding of fp32 sums, and the kept sets are the same unless two
  * candidates' scores are that close.
  *   streams   : host array of n_streams distinct hipStream_t, all of the

@@ -544,6 +544,11 @@ def main():
             "library_source_digest": library_source_digest(),
             "setup_s": {"generate_inputs": round(t_gen, 2)},
         }
+        dense_bytes_total = 2 * wl.L * wl.B * wl.H * wl.n_total * row_bytes(wl)
+        result["memory"] = {"compressed_cache_GB": cache.nbytes / 1e9, "full_cache_GB_at_end_of_image": dense_bytes_total / 1e9,
+                            "ratio": dense_bytes_total / cache.nbytes,
+                            "note": "K and V of all layers: the compressed cache block (ssd_cache_bytes: rows, scores, positions) "
+                                    "against n = %d rows for every head" % wl.n_total}
         if "roofline" in head:
             result["roofline"] = head["roofline"]
         result["whole_decode"] = head["whole_decode"]

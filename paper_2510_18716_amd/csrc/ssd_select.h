@@ -58,7 +58,7 @@ static __device__ __forceinline__ int wave_prefix(bool flag, int &total) {
 
 // LDS bytes select_and_move needs for n_cand candidates of which n_old come from the row buffer.
 static __host__ __device__ inline size_t select_lds_bytes(int M, int n_cand, int n_old) {
-    size_t b = 8 * (size_t)n_cand + 4 * (size_t)M + 4 * (size_t)n_old + 8 + (size_t)M + (size_t)n_old;
+    size_t b = 8 * (size_t)n_cand + 64 + 4 * (size_t)M + 4 * (size_t)n_old + 8 + (size_t)M + (size_t)n_old;
     return (b + 15) / 16 * 16;
 }
 
@@ -76,7 +76,8 @@ static __device__ __forceinline__ void select_and_move(const Geom &g, const Unit
                                                       int m, int n_old, int base, int lpr, int tid, int M) {
     const int C = g.C;
     unsigned long long *keys = reinterpret_cast<unsigned long long *>(lds);   // [n_cand]
-    int *dest = reinterpret_cast<int *>(keys + n_cand);                        // [M]     free heavy slots, ascending
+    unsigned long long *wave_least = keys + n_cand;                            // [8]     one minimum per wave of a workgroup
+    int *dest = reinterpret_cast<int *>(wave_least + 8);                       // [M]     free heavy slots, ascending
     int *src = dest + M;                                                       // [n_old] promoted candidates (indices)
     int *counts = src + n_old;                                                 // [2]
     unsigned char *flag = reinterpret_cast<unsigned char *>(counts + 2);       // [M + n_old]
@@ -88,10 +89,10 @@ static __device__ __forceinline__ void select_and_move(const Geom &g, const Unit
     const int per = (n_cand + THREADS - 1) / THREADS;                // candidates per thread
     if (n_cand <= M) {
         keepbits = ~0ull;
-    } else if (WAVE && (long long)n_evict * (per + 20) < (long long)per * n_cand) {
+    } else if ((long long)n_evict * (per + (WAVE ? 20 : 60)) < (long long)per * n_cand) {
         // Few evictions among many candidates (compression after every token: one): take the smallest keys out one
-        // by one -- a pass over this lane's keys and a wave-wide minimum each -- instead of ranking every candidate
-        // against every other.  Keys are distinct, so each minimum has one owner, and the kept set is the same.
+        // by one -- a pass over this thread's keys and a minimum over all threads each -- instead of ranking every
+        // candidate against every other.  Keys are distinct, so each minimum has one owner, and the kept set is the same.
         keepbits = ~0ull;
         for (int e = 0; e < n_evict; ++e) {
             unsigned long long least = ~0ull;
@@ -100,7 +101,15 @@ static __device__ __forceinline__ void select_and_move(const Geom &g, const Unit
                 const unsigned long long key = keys[k * THREADS + tid];
                 if (((keepbits >> k) & 1ull) && key < least) { least = key; at = k; }
             }
-            const unsigned long long lowest = wave_min_u64(least);      // every lane takes part, with or without a candidate
+            unsigned long long lowest = wave_min_u64(least);            // every lane takes part, with or without a candidate
+            if (!WAVE && THREADS > 64) {                                // a workgroup: the waves' minima meet in LDS
+                static_assert(THREADS <= 512, "room for eight waves' minima");
+                if ((tid & 63) == 0) wave_least[tid >> 6] = lowest;
+                __syncthreads();
+#pragma unroll
+                for (int wv = 0; wv < THREADS / 64; ++wv) lowest = min_u64(lowest, wave_least[wv]);
+                __syncthreads();                                        // before the next round writes the minima again
+            }
             if (at >= 0 && least == lowest) keepbits &= ~(1ull << at);
         }
     } else {

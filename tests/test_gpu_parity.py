@@ -467,6 +467,13 @@ def test_few_long_heads_beside_many_short_ones(fused):
     # as many long heads as short ones: the plain shape
     c = _full_compare(few_sem.replace(name="half-long-semantic", spatial_frac=0.5, seed=119), lpc=1, k_units=40, export_every=3, fused=fused)
     assert c.last_launch_shape()[1] in (1, 4)
+    if fused:       # the same mix through the rotary step and through the split call
+        c = _full_compare(few_sem.replace(name="few-long-semantic-rope", seed=123), lpc=1, k_units=40, export_every=3, fused=True,
+                          rope=ssd.SSD_ROPE_HALF)
+        assert c.last_launch_shape()[:2] == (4, 12)
+        c = _full_compare(few_sem.replace(name="few-very-long-semantic-split", M=96, prompts=4, seed=125), lpc=1, k_units=40, export_every=3,
+                          fused=True, split=2)
+        assert c.last_launch_shape()[:2] == (4, 14)
 
 
 @pytest.mark.parametrize("fused", [False, True], ids=["three-calls", "fused-step"])

@@ -426,10 +426,25 @@ __global__ __launch_bounds__(WPB * SHARE * 64) void step_kernel(StepArgs) {     
         const int r = lane + 64 * k;
         if (r < total) my_key[k] = score_row(r, pre_score[k], pre_pos[k]);
     }
-    for (int r = lane + 128; r < total; r += 64) {       // long row buffers only
-        const bool is_new = FUSED && r == sg.total;
-        const int slot = is_new ? t_new_slot_se : seg_slot(sg, r);
-        score_row(r, is_new ? 0.f : u.score[slot], (is_new || !compress) ? 0 : u.pos[slot]);
+    // Rows from 128 on (long budgets and row buffers only), four per lane at a time: the four loads of a batch are
+    // issued together and the stores follow them.  One row at a time, every load had to wait for the store before it
+    // (the compiler cannot tell the slots apart), a memory round trip per 64 rows at the end of the unit's longest wave.
+    for (int r0 = lane + 128; r0 - lane < total; r0 += 4 * 64) {
+        float s_old[4];
+        int p_old[4];
+        const int last = total - 1;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {                     // unconditional loads: rows past the end read the last row's slot
+            const int r = r0 + 64 * j < last ? r0 + 64 * j : last;
+            const int slot = (FUSED && r == sg.total) ? t_new_slot_se : seg_slot(sg, r);
+            s_old[j] = u.score[slot];
+            p_old[j] = u.pos[slot];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = r0 + 64 * j;
+            if (r < total) score_row(r, s_old[j], p_old[j]);
+        }
     }
     if (!compress) return;
     if (general) {

@@ -23,6 +23,8 @@ Prints ONE JSON line:
   stream_ceiling   a plain read of as many units of as many bytes per launch, no arithmetic, without and with the
                    least a step must store: what the memory system allows a launch of this shape, on one stream
                    and (headline on several streams) dealt to the streams as the headline's launches are
+  paper_head_mix   the same shape with the head mix of the paper's own settings (few long semantic heads beside many
+                   short spatial ones), on the headline's schedule and on one stream
   dense_baseline   the same steps through the full-cache decode kernel
   cpu_baseline     the CPU oracle timed on a sample of (layer, sequence, head) units
 """
@@ -217,6 +219,9 @@ def main():
                     help="generate the per-token inputs (q, k_new, v_new) for this many layers only and let layer l read those of layer "
                          "l mod this (0 = every layer its own).  For configurations whose inputs for all layers and all tokens would not fit "
                          "beside the cache (the large batch: 240 GB); the cache itself stays that of all layers")
+    ap.add_argument("--no-head-mix", action="store_true",
+                    help="skip the 'paper_head_mix' leg: the same shape with the head mix of the paper's own settings (W = 32, M = 128, 2 "
+                         "semantic heads of 32; Sec. 4.1, Table 6), timed on the headline's schedule and on one stream")
     ap.add_argument("--no-one-stream", action="store_true", help="skip the one-stream figure reported beside a split headline")
     ap.add_argument("--only", choices=["dense", "prefill", "ceiling"], default="",
                     help="run one of the side legs alone, without the decode measurement (for a profiler run of its own)")
@@ -511,7 +516,7 @@ def main():
     if args.only:
         head = None
         result = {"metric": "side leg '%s' alone" % args.only, "config": {"workload": wl.name, "layers": wl.L}}
-        args.no_all_layers = args.no_one_stream = args.no_cpu = True
+        args.no_all_layers = args.no_one_stream = args.no_cpu = args.no_head_mix = True
         args.no_dense, args.no_prefill, args.no_ceiling = args.only != "dense", args.only != "prefill", args.only != "ceiling"
     else:
         head = measure(lpc, with_events=not args.no_roofline, ns=n_streams)
@@ -728,6 +733,49 @@ def main():
                                                      "speedup_of_compressed": None if head is None else dense_whole / head["whole_decode"]["seconds"]}}
         result.setdefault("setup_s", {})["dense_layout"] = round(t_dense_setup, 2)
         del Kd, Vd
+
+    # ---- the head mix of the paper's own settings: few long semantic heads beside many short spatial ones --------------
+    if not args.no_head_mix and head is not None and fused and wl.H >= 16 and not args.rope and wl.head_budget is None and Ld == wl.L \
+            and R_rep == 1:
+        wl_m = wl.replace(W=32, M=128, spatial_frac=(wl.H - max(1, wl.H // 16)) / wl.H, alg2=False, R=1, C=2, cadence=1, name=wl.name + "-paper-mix")
+        ht_m = workload.head_map(wl_m)
+        cfg_m = make_config(wl_m.L, wl_m.B, wl_m.H, wl_m.d, wl_m.dtype, wl_m.W, wl_m.S, wl_m.M, wl_m.R, wl_m.C, 0.0, 0)
+        cache_m = ssd.Cache(cfg_m, ht_m, device=dev)
+        stride_l = wl.B * wl.H * wl.d * (2 if wl.dtype == "bf16" else 4)
+        qb, kb, vb, ob = data["q"].data_ptr(), data["k"].data_ptr(), data["v"].data_ptr(), out.data_ptr()
+        stream = torch.cuda.current_stream().cuda_stream
+        arr = ssd.stream_array([torch.cuda.current_stream()] + side_streams[: n_streams - 1])
+
+        def mix_timed(ns):
+            def step(p):                                  # the inputs are the headline's (their values do not matter for the time)
+                for l in range(wl_m.L):
+                    o = (p * wl_m.L + l) * stride_l
+                    if ns > 1:
+                        rc = ssd.lib.ssd_decode_step_split(cache_m.handle, l, l + 1, qb + o, kb + o, vb + o, ob + l * stride_l, 1, 1, arr, ns, 0)
+                    else:
+                        rc = ssd.lib.ssd_decode_step(cache_m.handle, l, l + 1, qb + o, kb + o, vb + o, ob + l * stride_l, 1, 1, stream)
+                    assert rc == 0, ssd.ssd_last_error()
+            cache_m.reset()
+            for p in range(wl_m.n_total - K_steps):
+                step(p)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for p in range(wl_m.n_total - K_steps, wl_m.n_total):
+                step(p)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / K_steps
+        n_, m_, c_, _ = (wl_m.n_total, wl_m.M, 1, 0)
+        gb = (algorithmic_bytes_attend(wl_m, ht_m, range(wl_m.L), (n_, m_, c_ + 1)) + algorithmic_bytes_append(wl_m, ht_m, range(wl_m.L))) / 1e9
+        leg = {"window": wl_m.W, "budget": wl_m.M, "spatial_heads": int((ht_m[0] == 0).sum()), "semantic_heads": int((ht_m[0] == 1).sum()),
+               "algorithmic_GB_per_step": gb}
+        for key, ns in (("headline_schedule", n_streams), ("one_stream", 1)):
+            dt_m = mix_timed(ns)
+            leg[key] = {"streams": ns, "ms_per_step": dt_m * 1e3, "value": wl_m.prompts / dt_m, "unit": "tokens/s",
+                        "frac_of_hbm_peak": gb / dt_m / HBM_PEAK_GBS}
+            if ns == 1:
+                break
+        result["paper_head_mix"] = leg
+        del cache_m
 
     # ---- CPU oracle on a sample of units ------------------------------------------------------------------
     if not args.no_cpu:
